@@ -1,0 +1,142 @@
+/*
+ * ttf.h -- C ABI of the Temporal Token Fusion (TTF) pre-LLM compression pass for AMD
+ * Instinct MI355X (gfx950).
+ *
+ * TTF (paper Section 3, "Temporal Token Fusion") takes the visual tokens of a clip,
+ * X in R^{FN x C} viewed as [F, N=H*W, C], and
+ *   1. picks an anchor frame a: the frame whose mean token has the largest cosine with the
+ *      clip's mean token (anchor-frame-selection equation), or a caller-fixed frame
+ *      (ablation A2: first / last frame);
+ *   2. for every token (k,i) of every other ("source") frame searches the (2r+1)x(2r+1)
+ *      neighbourhood of its grid cell in the anchor frame, clamped to the grid with
+ *      duplicate cells counted once, for the anchor token of largest cosine similarity:
+ *      best similarity s^(k,i) and anchor flat index dst(k,i) (pointwise matching with
+ *      local window search: projection, flat-index map, similarity, arg max, s^/dst);
+ *   3. fuses the token (drops it; the anchor token at dst stands for it) iff s^ > t, keeps
+ *      it iff s^ <= t (threshold-gating equation);
+ *   4. emits the compressed sequence X' = [N anchor rows ; P kept source rows in ascending
+ *      flat order k*N+i] as bit-exact copies of input rows (no averaging), together with
+ *      each row's original position triple (k, y, x) (stacked-X' equation, positional
+ *      alignment: mask, gather of X and P) and the compressed length L' = N + P that
+ *      cache-aware decode alignment needs.
+ *
+ * A batch holds B independent clips: every clip gets its own anchor, matches, mask and
+ * L'; outputs are packed clip after clip.  (The paper's tied-batch rule -- one offset from
+ * the batch-mean similarity, keep = union over the batch -- is a different mode and is
+ * not offered by this entry point.)
+ *
+ * General conventions
+ *   - All data pointers are DEVICE pointers unless a field says HOST.  Every buffer is
+ *     owned by the caller, before, during and after the call.  The library allocates and
+ *     frees no device memory.
+ *   - Work is enqueued on the caller's stream and the call returns without synchronising.
+ *     Buffers must stay alive until the stream has drained.  Calls that share a workspace
+ *     must be ordered by the caller (same stream, or events).
+ *   - Every function returns a ttf_status.  On any status other than TTF_OK no kernel has
+ *     been launched and no output has been written, except TTF_ERR_HIP, which reports a
+ *     failed launch or copy part-way through the sequence (outputs are then undefined).
+ *   - Same inputs give bit-identical outputs on every call (no floating-point atomics, fixed
+ *     reduction orders).
+ *   - Input values are not scanned.  A NaN similarity compares false against "> t", so the
+ *     token is kept.
+ */
+#ifndef TTF_H
+#define TTF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TTF_OK = 0,
+    TTF_ERR_INVALID_ARG = 1,          /* NULL required pointer, size <= 0, r < 0, non-finite t, ... */
+    TTF_ERR_UNSUPPORTED = 2,          /* unknown dtype, misaligned features / tokens_out            */
+    TTF_ERR_WORKSPACE_TOO_SMALL = 3,  /* workspace_bytes < ttf_workspace_size()                     */
+    TTF_ERR_HIP = 4                   /* a HIP call failed; see ttf_last_hip_error()                */
+} ttf_status;
+
+typedef enum { TTF_BF16 = 0, TTF_F32 = 1 } ttf_dtype;
+
+typedef enum { TTF_ANCHOR_AUTO = 0, TTF_ANCHOR_FIXED = 1 } ttf_anchor_mode;
+
+/* Problem description.  B*F*H*W must be < 2^31. */
+typedef struct {
+    int32_t B, F, H, W, C;    /* clips, frames, token-grid height and width, channels; all >= 1 */
+    int32_t dtype;            /* ttf_dtype of `features` and `tokens_out`                        */
+    int32_t r;                /* search radius >= 0, window (2r+1)^2; r >= max(H,W)-1 = whole grid */
+    float   t;                /* cosine threshold; fused iff s^ > t (strict).  Any finite value.  */
+    int32_t anchor_mode;      /* ttf_anchor_mode                                                  */
+    int32_t anchor_index;     /* FIXED only: frame in [-F, F); negative counts from the last     */
+} ttf_params;
+
+/*
+ * Outputs.  cap = B*F*H*W rows is the capacity the row-indexed buffers must have; rows at
+ * and beyond row_offsets[B] are left untouched.  N = H*W.
+ */
+typedef struct {
+    void*    tokens_out;    /* [cap, C] dtype.  Clip b owns rows row_offsets[b] .. row_offsets[b+1)-1:
+                               first its N anchor rows, then its kept source rows (stacked-X' equation). */
+    int32_t* pos_ids;       /* [3, cap] planes k (frame), y, x of every output row (plane stride cap). */
+    int32_t* src_index;     /* [cap]    flat index k*N+i inside its clip of every output row (I_keep). */
+    int32_t* row_offsets;   /* [B+1]    exclusive prefix sum of kept_count.                            */
+    int32_t* kept_count;    /* [B]      L'_b = N + P_b.                                                */
+    int32_t* anchor_index;  /* [B]      anchor frame chosen (or given) per clip.                       */
+    int32_t* fuse_map;      /* [B,F,N]  dst(k,i) in [0,N) if the token was fused, else -1
+                                        (anchor-frame tokens: -1).                                     */
+    float*   best_sim;      /* [B,F,N]  s^(k,i); 1.0f on anchor-frame tokens.  May be NULL.            */
+    int32_t* best_idx;      /* [B,F,N]  dst(k,i) for every source token whether fused or not;
+                                        i on anchor-frame tokens.  May be NULL.                        */
+    int32_t* host_counts;   /* HOST, pinned, [2B+1]: kept_count[0..B) then row_offsets[0..B]; filled by
+                               an asynchronous copy on the stream.  May be NULL.                       */
+} ttf_outputs;
+
+/* Bytes of device workspace ttf_compress needs for these sizes (depends on B,F,H,W,C only).
+ * The workspace must be 256-byte aligned.  INVALID_ARG on bad sizes or NULL pointers. */
+ttf_status ttf_workspace_size(const ttf_params* params, size_t* bytes);
+
+/*
+ * The whole pass (Section 3: anchor frame selection, pointwise matching with local window
+ * search, threshold gating and token compression, positional alignment).
+ *   features   DEVICE [B,F,H,W,C] contiguous, dtype per params, 16-byte aligned; read only.
+ *   workspace  DEVICE scratch of at least ttf_workspace_size() bytes, 256-byte aligned; its
+ *              contents on entry do not matter and are garbage afterwards.
+ *   out        see ttf_outputs; all but the three optional fields are required.
+ *   hip_stream hipStream_t (NULL = the default stream).
+ * Errors: INVALID_ARG (NULL params/features/workspace/out or required output, a size < 1,
+ * B*F*H*W >= 2^31, r < 0, t not finite, anchor_index outside [-F,F) in FIXED mode, unknown
+ * anchor_mode), UNSUPPORTED (unknown dtype; features, tokens_out or workspace misaligned;
+ * C*sizeof(element) not a multiple of 4), WORKSPACE_TOO_SMALL, HIP.
+ */
+ttf_status ttf_compress(const ttf_params* params, const void* features,
+                        void* workspace, size_t workspace_bytes,
+                        const ttf_outputs* out, void* hip_stream);
+
+/* Static, NUL-terminated description of a status code (never NULL). */
+const char* ttf_status_string(ttf_status status);
+
+/* hipError_t (as int) behind the calling thread's last TTF_ERR_HIP; 0 if none. */
+int ttf_last_hip_error(void);
+
+/*
+ * Per-stage timing, for benchmarks.  Stages, in launch order:
+ *   0 frame sums   1 anchor choice   2 anchor norms   3 window search + gate
+ *   4 offsets scan 5 row emission
+ * ttf_profile_enable(1) makes every following ttf_compress on this thread record HIP
+ * events around each stage on the call's stream (events are created once and reused);
+ * ttf_profile_read() waits for the last profiled call to finish and returns the stage
+ * durations in milliseconds (ms_out[0..n), n <= TTF_NUM_STAGES; stages that did not run
+ * report 0).  Profiling inserts event records between kernels and is off by default.
+ * ttf_profile_read returns INVALID_ARG if nothing was recorded.
+ */
+#define TTF_NUM_STAGES 6
+ttf_status ttf_profile_enable(int enable);
+ttf_status ttf_profile_read(float* ms_out, int n);
+const char* ttf_stage_name(int stage);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TTF_H */

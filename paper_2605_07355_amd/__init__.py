@@ -1,0 +1,21 @@
+"""Temporal Token Fusion (TTF) for AMD Instinct MI355X.
+
+Thin Python binding over the C-ABI library ``libttf.so`` (hand-written HIP kernels for
+gfx950).  PyTorch is used for device memory and streams only; every step of the pass runs in
+the library's kernels.  There is no CPU or PyTorch fallback: if the library is missing the
+import of :mod:`paper_2605_07355_amd.binding` functions raises.
+"""
+from .binding import (  # noqa: F401
+    TTFError,
+    TTFOutput,
+    TTFBuffers,
+    STAGE_NAMES,
+    library_path,
+    load_library,
+    ttf_compress,
+    ttf_workspace_size,
+    ttf_status_string,
+    ttf_last_hip_error,
+    ttf_profile_enable,
+    ttf_profile_read,
+)

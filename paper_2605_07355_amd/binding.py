@@ -1,0 +1,224 @@
+"""ctypes binding of ``include/ttf.h``: same names, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Union
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG_DIR, "libttf.so")
+
+TTF_OK, TTF_ERR_INVALID_ARG, TTF_ERR_UNSUPPORTED, TTF_ERR_WORKSPACE_TOO_SMALL, TTF_ERR_HIP = range(5)
+TTF_BF16, TTF_F32 = 0, 1
+TTF_ANCHOR_AUTO, TTF_ANCHOR_FIXED = 0, 1
+TTF_NUM_STAGES = 6
+
+
+class TTFError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"ttf status {status}: {message}")
+        self.status = status
+
+
+class _Params(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("F", ctypes.c_int32), ("H", ctypes.c_int32), ("W", ctypes.c_int32),
+                ("C", ctypes.c_int32), ("dtype", ctypes.c_int32), ("r", ctypes.c_int32), ("t", ctypes.c_float),
+                ("anchor_mode", ctypes.c_int32), ("anchor_index", ctypes.c_int32)]
+
+
+class _Outputs(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("tokens_out", "pos_ids", "src_index", "row_offsets", "kept_count", "anchor_index",
+                 "fuse_map", "best_sim", "best_idx", "host_counts")]
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load ``libttf.so`` from the package directory.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} not found: build it with `python -m paper_2605_07355_amd.build` "
+                "(there is no fallback implementation)")
+        lib = ctypes.CDLL(_LIB_PATH)
+        lib.ttf_workspace_size.restype = ctypes.c_int
+        lib.ttf_workspace_size.argtypes = [ctypes.POINTER(_Params), ctypes.POINTER(ctypes.c_size_t)]
+        lib.ttf_compress.restype = ctypes.c_int
+        lib.ttf_compress.argtypes = [ctypes.POINTER(_Params), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                     ctypes.POINTER(_Outputs), ctypes.c_void_p]
+        lib.ttf_status_string.restype = ctypes.c_char_p
+        lib.ttf_status_string.argtypes = [ctypes.c_int]
+        lib.ttf_last_hip_error.restype = ctypes.c_int
+        lib.ttf_profile_enable.restype = ctypes.c_int
+        lib.ttf_profile_enable.argtypes = [ctypes.c_int]
+        lib.ttf_profile_read.restype = ctypes.c_int
+        lib.ttf_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int]
+        lib.ttf_stage_name.restype = ctypes.c_char_p
+        lib.ttf_stage_name.argtypes = [ctypes.c_int]
+        _lib = lib
+    return _lib
+
+
+def ttf_status_string(status: int) -> str:
+    return load_library().ttf_status_string(int(status)).decode()
+
+
+def ttf_last_hip_error() -> int:
+    return int(load_library().ttf_last_hip_error())
+
+
+def _check(status: int) -> None:
+    if status != TTF_OK:
+        raise TTFError(status, ttf_status_string(status))
+
+
+def _stage_names():
+    try:
+        lib = load_library()
+    except (FileNotFoundError, OSError):
+        return tuple(f"stage{i}" for i in range(TTF_NUM_STAGES))
+    return tuple(lib.ttf_stage_name(i).decode() for i in range(TTF_NUM_STAGES))
+
+
+STAGE_NAMES = _stage_names()
+
+
+def _dtype_code(dt: torch.dtype) -> int:
+    if dt == torch.bfloat16:
+        return TTF_BF16
+    if dt == torch.float32:
+        return TTF_F32
+    raise TypeError(f"features must be bfloat16 or float32, got {dt}")
+
+
+def _make_params(B, F, H, W, C, dtype_code, r, t, anchor) -> _Params:
+    if isinstance(anchor, str):
+        if anchor != "auto":
+            raise ValueError("anchor must be 'auto' or a frame index")
+        mode, idx = TTF_ANCHOR_AUTO, 0
+    else:
+        mode, idx = TTF_ANCHOR_FIXED, int(anchor)
+    return _Params(int(B), int(F), int(H), int(W), int(C), int(dtype_code), int(r), float(t), mode, idx)
+
+
+def ttf_workspace_size(B: int, F: int, H: int, W: int, C: int, dtype: torch.dtype = torch.bfloat16,
+                       r: int = 1, t: float = 0.7, anchor: Union[str, int] = "auto") -> int:
+    p = _make_params(B, F, H, W, C, _dtype_code(dtype), r, t, anchor)
+    n = ctypes.c_size_t(0)
+    _check(load_library().ttf_workspace_size(ctypes.byref(p), ctypes.byref(n)))
+    return int(n.value)
+
+
+@dataclass
+class TTFBuffers:
+    """Caller-owned device buffers of one problem size, reusable across calls."""
+    tokens_out: torch.Tensor     # [cap, C]
+    pos_ids: torch.Tensor        # [3, cap] int32
+    src_index: torch.Tensor      # [cap] int32
+    row_offsets: torch.Tensor    # [B+1] int32
+    kept_count: torch.Tensor     # [B] int32
+    anchor_index: torch.Tensor   # [B] int32
+    fuse_map: torch.Tensor       # [B,F,N] int32
+    best_sim: Optional[torch.Tensor]   # [B,F,N] float32
+    best_idx: Optional[torch.Tensor]   # [B,F,N] int32
+    workspace: torch.Tensor      # uint8
+    host_counts: Optional[torch.Tensor] = None   # pinned int32 [2B+1]
+
+    @staticmethod
+    def allocate(B, F, H, W, C, dtype, device, want_sim=True, want_host_counts=False) -> "TTFBuffers":
+        N, cap = H * W, B * F * H * W
+        i32 = dict(dtype=torch.int32, device=device)
+        ws = ttf_workspace_size(B, F, H, W, C, dtype)
+        return TTFBuffers(
+            tokens_out=torch.empty((cap, C), dtype=dtype, device=device),
+            pos_ids=torch.empty((3, cap), **i32), src_index=torch.empty((cap,), **i32),
+            row_offsets=torch.empty((B + 1,), **i32), kept_count=torch.empty((B,), **i32),
+            anchor_index=torch.empty((B,), **i32), fuse_map=torch.empty((B, F, N), **i32),
+            best_sim=torch.empty((B, F, N), dtype=torch.float32, device=device) if want_sim else None,
+            best_idx=torch.empty((B, F, N), **i32) if want_sim else None,
+            workspace=torch.empty((ws + 256,), dtype=torch.uint8, device=device),
+            host_counts=torch.empty((2 * B + 1,), dtype=torch.int32, pin_memory=True) if want_host_counts else None)
+
+
+@dataclass
+class TTFOutput:
+    buffers: TTFBuffers
+    B: int
+    F: int
+    H: int
+    W: int
+    C: int
+
+    # views; reading them synchronises as any torch op on the stream does
+    @property
+    def total_rows(self) -> int:
+        return int(self.buffers.row_offsets[-1].item())
+
+    def clip_tokens(self, b: int) -> torch.Tensor:
+        ro = self.buffers.row_offsets
+        return self.buffers.tokens_out[int(ro[b]):int(ro[b + 1])]
+
+    def clip_pos_ids(self, b: int) -> torch.Tensor:
+        ro = self.buffers.row_offsets
+        return self.buffers.pos_ids[:, int(ro[b]):int(ro[b + 1])]
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _aligned_workspace(ws: torch.Tensor):
+    base = ws.data_ptr()
+    off = (-base) % 256
+    return base + off, ws.numel() - off
+
+
+def ttf_compress(features: torch.Tensor, r: int = 1, t: float = 0.70, anchor: Union[str, int] = "auto",
+                 buffers: Optional[TTFBuffers] = None, want_sim: bool = True,
+                 stream: Optional[torch.cuda.Stream] = None) -> TTFOutput:
+    """Run the TTF pass on ``features`` [B,F,H,W,C] (CUDA/HIP tensor, bf16 or fp32, contiguous).
+
+    Enqueues on ``stream`` (default: the current stream) and returns without synchronising.
+    ``buffers`` may be passed to reuse allocations; otherwise they are allocated with torch.
+    """
+    if features.dim() != 5:
+        raise ValueError("features must be [B,F,H,W,C]")
+    if not features.is_cuda:
+        raise ValueError("features must live on the GPU (the library has no CPU path)")
+    if not features.is_contiguous():
+        raise ValueError("features must be contiguous")
+    B, F, H, W, C = (int(v) for v in features.shape)
+    p = _make_params(B, F, H, W, C, _dtype_code(features.dtype), r, t, anchor)
+    if buffers is None:
+        buffers = TTFBuffers.allocate(B, F, H, W, C, features.dtype, features.device, want_sim=want_sim)
+    ws_ptr, ws_bytes = _aligned_workspace(buffers.workspace)
+    o = _Outputs(_ptr(buffers.tokens_out), _ptr(buffers.pos_ids), _ptr(buffers.src_index),
+                 _ptr(buffers.row_offsets), _ptr(buffers.kept_count), _ptr(buffers.anchor_index),
+                 _ptr(buffers.fuse_map), _ptr(buffers.best_sim), _ptr(buffers.best_idx),
+                 _ptr(buffers.host_counts))
+    s = stream if stream is not None else torch.cuda.current_stream(features.device)
+    with torch.cuda.device(features.device):
+        _check(load_library().ttf_compress(ctypes.byref(p), features.data_ptr(), ws_ptr, ws_bytes,
+                                           ctypes.byref(o), ctypes.c_void_p(s.cuda_stream)))
+    return TTFOutput(buffers, B, F, H, W, C)
+
+
+def ttf_profile_enable(enable: bool) -> None:
+    _check(load_library().ttf_profile_enable(1 if enable else 0))
+
+
+def ttf_profile_read():
+    """Stage durations (ms) of the last profiled call on this thread, keyed by stage name."""
+    buf = (ctypes.c_float * TTF_NUM_STAGES)()
+    _check(load_library().ttf_profile_read(buf, TTF_NUM_STAGES))
+    return {STAGE_NAMES[i]: float(buf[i]) for i in range(TTF_NUM_STAGES)}

@@ -1,0 +1,203 @@
+// Anchor frame selection (Section 3, "Anchor Frame Selection"):
+//   a* = argmax_k cos( (1/N) sum_i x_{k,i} , (1/(FN)) sum_{k',i} x_{k',i} )
+// The cosine does not change when either argument is scaled, so the kernels work with plain
+// sums: frame sums in fp32 (one streaming pass over X, the only large read of this stage),
+// everything after that in fp64 on [B,F,C] numbers.  A last kernel picks the arg max (lowest
+// k on ties) and computes 1/||x_{a,j}|| for the anchor tokens, which the window search uses
+// as the anchor half of every cosine denominator.
+#include "ttf_device.h"
+#include "ttf_internal.h"
+
+namespace ttf {
+namespace {
+
+// One block = one frame x one slice of 64*V channels.  Wave w adds rows w, w+4, ...; the four
+// partial sums are combined through LDS in wave order, so the result is order-stable.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void k_frame_sums(const T* __restrict__ x, float* __restrict__ frame_sum,
+                                                    int N, int C)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t frame = blockIdx.x;
+    const int c0 = (blockIdx.y * 64 + lane) * V;
+    __shared__ float part[4][64 * V];
+    float acc[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[e] = 0.f;
+    if (c0 < C) {
+        const T* base = x + frame * (size_t)N * C + c0;
+        int i = wave;
+        for (; i + 12 < N; i += 16) {          // four rows in flight per wave
+            RowVec<T, V> r0, r1, r2, r3;
+            r0.load(base + (size_t)i * C);
+            r1.load(base + (size_t)(i + 4) * C);
+            r2.load(base + (size_t)(i + 8) * C);
+            r3.load(base + (size_t)(i + 12) * C);
+#pragma unroll
+            for (int e = 0; e < V; ++e) acc[e] += r0.v[e];
+#pragma unroll
+            for (int e = 0; e < V; ++e) acc[e] += r1.v[e];
+#pragma unroll
+            for (int e = 0; e < V; ++e) acc[e] += r2.v[e];
+#pragma unroll
+            for (int e = 0; e < V; ++e) acc[e] += r3.v[e];
+        }
+        for (; i < N; i += 4) {
+            RowVec<T, V> r0;
+            r0.load(base + (size_t)i * C);
+#pragma unroll
+            for (int e = 0; e < V; ++e) acc[e] += r0.v[e];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < V; ++e) part[wave][lane * V + e] = acc[e];
+    __syncthreads();
+    if (wave == 0 && c0 < C) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            const int q = lane * V + e;
+            frame_sum[frame * (size_t)C + c0 + e] = ((part[0][q] + part[1][q]) + part[2][q]) + part[3][q];
+        }
+    }
+}
+
+// clip_sum[b,c] = sum_k frame_sum[b,k,c], fp64, k ascending.
+__global__ __launch_bounds__(256) void k_clip_sum(const float* __restrict__ frame_sum,
+                                                  double* __restrict__ clip_sum, int F, int C)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    const size_t b = blockIdx.y;
+    if (c >= C) return;
+    const float* fs = frame_sum + b * (size_t)F * C + c;
+    double g = 0.0;
+    for (int k = 0; k < F; ++k) g += (double)fs[(size_t)k * C];
+    clip_sum[b * (size_t)C + c] = g;
+}
+
+// frame_score[b,k] = cos(frame_sum[b,k,:], clip_sum[b,:]) in fp64; 0 when a norm is 0.
+__global__ __launch_bounds__(256) void k_frame_score(const float* __restrict__ frame_sum,
+                                                     const double* __restrict__ clip_sum,
+                                                     double* __restrict__ frame_score, int F, int C)
+{
+    const size_t frame = blockIdx.x;              // b*F + k
+    const size_t b = frame / F;
+    const float* fs = frame_sum + frame * (size_t)C;
+    const double* g = clip_sum + b * (size_t)C;
+    double uv = 0.0, uu = 0.0, vv = 0.0;
+    for (int c = threadIdx.x; c < C; c += 256) {
+        const double u = (double)fs[c], v = g[c];
+        uv += u * v;
+        uu += u * u;
+        vv += v * v;
+    }
+    uv = wave_sum(uv);
+    uu = wave_sum(uu);
+    vv = wave_sum(vv);
+    __shared__ double red[3][4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { red[0][wave] = uv; red[1][wave] = uu; red[2][wave] = vv; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const double d  = ((red[0][0] + red[0][1]) + red[0][2]) + red[0][3];
+        const double nu = ((red[1][0] + red[1][1]) + red[1][2]) + red[1][3];
+        const double nv = ((red[2][0] + red[2][1]) + red[2][2]) + red[2][3];
+        const double den = sqrt(nu) * sqrt(nv);
+        frame_score[frame] = den > 0.0 ? d / den : 0.0;
+    }
+}
+
+// Picks the anchor of clip b (arg max of frame_score, lowest k on ties, or the fixed frame),
+// publishes it, and writes 1/||x_{a,j}|| for the anchor tokens.  One wave per anchor token.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void k_anchor_norms(const T* __restrict__ x,
+                                                      const double* __restrict__ frame_score,
+                                                      int32_t* __restrict__ anchor_index,
+                                                      float* __restrict__ anchor_inv,
+                                                      int F, int N, int C, int fixed_anchor, int groups)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int b = blockIdx.x / groups;
+    const int j = (blockIdx.x % groups) * 4 + wave;
+    int a = fixed_anchor;
+    if (a < 0) {
+        double best = -1.0e300;
+        int arg = 0x7fffffff;
+        for (int k = lane; k < F; k += 64) {            // ascending k per lane: strict > keeps the lowest
+            const double s = frame_score[(size_t)b * F + k];
+            if (s > best) { best = s; arg = k; }
+        }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            const double ob = __shfl_xor(best, m, 64);
+            const int oa = __shfl_xor(arg, m, 64);
+            if (ob > best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+        }
+        a = arg == 0x7fffffff ? 0 : arg;                // all-NaN scores: frame 0
+    }
+    if (blockIdx.x % groups == 0 && threadIdx.x == 0) anchor_index[b] = a;
+    if (j >= N) return;
+    const T* row = x + (((size_t)b * F + a) * N + j) * (size_t)C;
+    float ss = 0.f;
+    for (int c = lane * V; c < C; c += 64 * V) {
+        RowVec<T, V> r;
+        r.load(row + c);
+#pragma unroll
+        for (int e = 0; e < V; ++e) ss = fmaf(r.v[e], r.v[e], ss);
+    }
+    ss = wave_sum(ss);
+    if (lane == 0) anchor_inv[(size_t)b * N + j] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+}
+
+template <typename F>
+hipError_t by_layout(const ttf_params& p, F&& f)
+{
+    // 16-byte vector loads need rows that start 16-byte aligned: C*sizeof(T) % 16 == 0.
+    if (p.dtype == TTF_BF16) {
+        if (p.C % 8 == 0) return f(bf16_t{}, std::integral_constant<int, 8>{});
+        return f(bf16_t{}, std::integral_constant<int, 1>{});
+    }
+    if (p.C % 4 == 0) return f(float{}, std::integral_constant<int, 4>{});
+    return f(float{}, std::integral_constant<int, 1>{});
+}
+
+}  // namespace
+
+hipError_t launch_frame_sums(const ttf_params& p, const void* x, const Workspace& w, hipStream_t s)
+{
+    const int N = p.H * p.W;
+    return by_layout(p, [&](auto tag, auto vtag) {
+        using T = decltype(tag);
+        constexpr int V = decltype(vtag)::value;
+        dim3 grid((unsigned)(p.B * p.F), (unsigned)((p.C + 64 * V - 1) / (64 * V)));
+        k_frame_sums<T, V><<<grid, 256, 0, s>>>(static_cast<const T*>(x), w.frame_sum, N, p.C);
+        return hipGetLastError();
+    });
+}
+
+hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, hipStream_t s)
+{
+    dim3 g1((unsigned)((p.C + 255) / 256), (unsigned)p.B);
+    k_clip_sum<<<g1, 256, 0, s>>>(w.frame_sum, w.clip_sum, p.F, p.C);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    k_frame_score<<<(unsigned)(p.B * p.F), 256, 0, s>>>(w.frame_sum, w.clip_sum, w.frame_score, p.F, p.C);
+    return hipGetLastError();
+}
+
+hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const Workspace& w,
+                               int32_t* anchor_index, hipStream_t s)
+{
+    const int N = p.H * p.W;
+    const int groups = (N + 3) / 4;
+    int fixed = -1;
+    if (p.anchor_mode == TTF_ANCHOR_FIXED) fixed = p.anchor_index < 0 ? p.anchor_index + p.F : p.anchor_index;
+    return by_layout(p, [&](auto tag, auto vtag) {
+        using T = decltype(tag);
+        constexpr int V = decltype(vtag)::value;
+        k_anchor_norms<T, V><<<(unsigned)(p.B * groups), 256, 0, s>>>(
+            static_cast<const T*>(x), w.frame_score, anchor_index, w.anchor_inv, p.F, N, p.C, fixed, groups);
+        return hipGetLastError();
+    });
+}
+
+}  // namespace ttf

@@ -1,0 +1,183 @@
+// C ABI of the TTF library: argument checks, workspace carving, the launch sequence of
+// Section 3 (anchor selection -> window search + gate -> offsets -> row emission) and the
+// optional per-stage event timing.  Nothing here allocates device memory.
+#include <cmath>
+#include <cstring>
+
+#include "ttf_internal.h"
+
+namespace ttf {
+
+hipError_t launch_window_search_generic(const ttf_params& p, const void* x, const Workspace& w,
+                                        const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
+                                        int32_t* best_idx, hipStream_t s);
+
+hipError_t launch_window_search(const ttf_params& p, const void* x, const Workspace& w,
+                                const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
+                                int32_t* best_idx, hipStream_t s)
+{
+    return launch_window_search_generic(p, x, w, anchor_index, fuse_map, best_sim, best_idx, s);
+}
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+struct Profile {
+    bool enabled = false;
+    bool created = false;
+    bool recorded = false;
+    hipEvent_t ev[TTF_NUM_STAGES + 1];
+};
+thread_local Profile g_prof;
+
+ttf_status check_params(const ttf_params* p)
+{
+    if (!p) return TTF_ERR_INVALID_ARG;
+    if (p->B < 1 || p->F < 1 || p->H < 1 || p->W < 1 || p->C < 1) return TTF_ERR_INVALID_ARG;
+    const long long tokens = (long long)p->B * p->F * p->H * p->W;
+    if ((long long)p->H * p->W >= (1ll << 31) || tokens >= (1ll << 31)) return TTF_ERR_INVALID_ARG;
+    if (p->C > (1 << 22)) return TTF_ERR_INVALID_ARG;       // keeps every launch grid inside HIP limits
+    if (p->r < 0) return TTF_ERR_INVALID_ARG;
+    if (!std::isfinite(p->t)) return TTF_ERR_INVALID_ARG;
+    if (p->anchor_mode != TTF_ANCHOR_AUTO && p->anchor_mode != TTF_ANCHOR_FIXED) return TTF_ERR_INVALID_ARG;
+    if (p->anchor_mode == TTF_ANCHOR_FIXED && (p->anchor_index < -p->F || p->anchor_index >= p->F))
+        return TTF_ERR_INVALID_ARG;
+    if (p->dtype != TTF_BF16 && p->dtype != TTF_F32) return TTF_ERR_UNSUPPORTED;
+    return TTF_OK;
+}
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+}  // namespace
+}  // namespace ttf
+
+using namespace ttf;
+
+extern "C" {
+
+ttf_status ttf_workspace_size(const ttf_params* params, size_t* bytes)
+{
+    if (!bytes) return TTF_ERR_INVALID_ARG;
+    const ttf_status st = check_params(params);
+    if (st != TTF_OK) return st;
+    *bytes = carve(*params, nullptr).bytes;
+    return TTF_OK;
+}
+
+ttf_status ttf_compress(const ttf_params* params, const void* features, void* workspace,
+                        size_t workspace_bytes, const ttf_outputs* out, void* hip_stream)
+{
+    const ttf_status st = check_params(params);
+    if (st != TTF_OK) return st;
+    if (!features || !workspace || !out) return TTF_ERR_INVALID_ARG;
+    if (!out->tokens_out || !out->pos_ids || !out->src_index || !out->row_offsets || !out->kept_count ||
+        !out->anchor_index || !out->fuse_map)
+        return TTF_ERR_INVALID_ARG;
+    if (!aligned(features, 16) || !aligned(out->tokens_out, 16) || !aligned(workspace, 256))
+        return TTF_ERR_UNSUPPORTED;
+
+    ttf_params p = *params;
+    p.r = p.r > (p.H > p.W ? p.H : p.W) ? (p.H > p.W ? p.H : p.W) : p.r;   // beyond the grid = whole grid
+    const Workspace w = carve(p, workspace);
+    if (workspace_bytes < w.bytes) return TTF_ERR_WORKSPACE_TOO_SMALL;
+
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    Profile& prof = g_prof;
+    const bool timing = prof.enabled && prof.created;
+    hipError_t e = hipSuccess;
+    int stage = 0;
+    auto mark = [&]() {
+        if (timing && e == hipSuccess) e = hipEventRecord(prof.ev[stage], s);
+        ++stage;
+    };
+#define TTF_STEP(call)                 \
+    do {                               \
+        if (e == hipSuccess) e = (call); \
+    } while (0)
+
+    mark();                                                    // start of stage 0
+    if (p.anchor_mode == TTF_ANCHOR_AUTO) TTF_STEP(launch_frame_sums(p, features, w, s));
+    mark();
+    if (p.anchor_mode == TTF_ANCHOR_AUTO) TTF_STEP(launch_anchor_scores(p, w, s));
+    mark();
+    TTF_STEP(launch_anchor_norms(p, features, w, out->anchor_index, s));
+    mark();
+    TTF_STEP(launch_window_search(p, features, w, out->anchor_index, out->fuse_map, out->best_sim,
+                                  out->best_idx, s));
+    mark();
+    TTF_STEP(launch_offsets_scan(p, w, out->anchor_index, out->kept_count, out->row_offsets, s));
+    mark();
+    TTF_STEP(launch_emit_rows(p, features, w, out->anchor_index, out->tokens_out, out->pos_ids,
+                              out->src_index, s));
+    mark();                                                    // end of stage 5
+    if (out->host_counts) {
+        TTF_STEP(hipMemcpyAsync(out->host_counts, out->kept_count, sizeof(int32_t) * p.B,
+                                hipMemcpyDeviceToHost, s));
+        TTF_STEP(hipMemcpyAsync(out->host_counts + p.B, out->row_offsets, sizeof(int32_t) * (p.B + 1),
+                                hipMemcpyDeviceToHost, s));
+    }
+#undef TTF_STEP
+    if (e != hipSuccess) {
+        g_last_hip_error = static_cast<int>(e);
+        return TTF_ERR_HIP;
+    }
+    if (timing) prof.recorded = true;
+    return TTF_OK;
+}
+
+const char* ttf_status_string(ttf_status status)
+{
+    switch (status) {
+        case TTF_OK: return "ok";
+        case TTF_ERR_INVALID_ARG: return "invalid argument";
+        case TTF_ERR_UNSUPPORTED: return "unsupported dtype or alignment";
+        case TTF_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case TTF_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+int ttf_last_hip_error(void) { return g_last_hip_error; }
+
+ttf_status ttf_profile_enable(int enable)
+{
+    Profile& prof = g_prof;
+    if (enable && !prof.created) {
+        for (int i = 0; i <= TTF_NUM_STAGES; ++i) {
+            const hipError_t e = hipEventCreate(&prof.ev[i]);
+            if (e != hipSuccess) {
+                for (int j = 0; j < i; ++j) (void)hipEventDestroy(prof.ev[j]);
+                g_last_hip_error = static_cast<int>(e);
+                return TTF_ERR_HIP;
+            }
+        }
+        prof.created = true;
+    }
+    prof.enabled = enable != 0;
+    if (!prof.enabled) prof.recorded = false;
+    return TTF_OK;
+}
+
+ttf_status ttf_profile_read(float* ms_out, int n)
+{
+    Profile& prof = g_prof;
+    if (!ms_out || n < 0 || !prof.created || !prof.recorded) return TTF_ERR_INVALID_ARG;
+    hipError_t e = hipEventSynchronize(prof.ev[TTF_NUM_STAGES]);
+    for (int i = 0; i < n && i < TTF_NUM_STAGES && e == hipSuccess; ++i)
+        e = hipEventElapsedTime(&ms_out[i], prof.ev[i], prof.ev[i + 1]);
+    if (e != hipSuccess) {
+        g_last_hip_error = static_cast<int>(e);
+        return TTF_ERR_HIP;
+    }
+    return TTF_OK;
+}
+
+const char* ttf_stage_name(int stage)
+{
+    static const char* names[TTF_NUM_STAGES] = {"frame_sums", "anchor_scores", "anchor_norms",
+                                                "window_search", "offsets_scan", "emit_rows"};
+    return (stage >= 0 && stage < TTF_NUM_STAGES) ? names[stage] : "";
+}
+
+}  // extern "C"

@@ -1,0 +1,61 @@
+// Device-side helpers shared by the TTF kernels: element widening, vector row loads and
+// fixed-order wavefront reductions (64 lanes).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ttf {
+
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float widen(bf16_t v)
+{
+    return __builtin_bit_cast(float, static_cast<uint32_t>(v.bits) << 16);
+}
+__device__ __forceinline__ float widen(float v) { return v; }
+
+// V consecutive elements of a row, widened to fp32.  V*sizeof(T) is 16 (vector path, needs a
+// 16-byte aligned address) or sizeof(T) (scalar path, any C).
+template <typename T, int V>
+struct RowVec {
+    float v[V];
+    __device__ __forceinline__ void load(const T* p)
+    {
+        if constexpr (V == 1) {
+            v[0] = widen(p[0]);
+        } else if constexpr (sizeof(T) == 2) {
+            static_assert(V == 8, "bf16 vector path is 8 elements");
+            const uint4 q = *reinterpret_cast<const uint4*>(p);
+            const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                v[2 * i]     = __builtin_bit_cast(float, w[i] << 16);
+                v[2 * i + 1] = __builtin_bit_cast(float, w[i] & 0xffff0000u);
+            }
+        } else {
+            static_assert(V == 4, "fp32 vector path is 4 elements");
+            const float4 q = *reinterpret_cast<const float4*>(p);
+            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+        }
+    }
+};
+
+// Sum over the 64 lanes of a wavefront, butterfly order (identical on every call); every
+// lane ends with the total.
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1)
+        v += __shfl_xor(v, m, 64);
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1)
+        v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+}  // namespace ttf

@@ -1,0 +1,168 @@
+// Sequence compaction and positional alignment (Section 3: stacked X' = [anchor rows ; kept
+// source rows], retention mask m_{k,i}, gather of X and P by I_keep, L' = N + P).
+//
+// The search leaves one keep bit per token.  A single small block turns per-frame popcounts
+// into output row offsets (anchor frame first inside each clip, clips packed one after the
+// other); the emit kernel then copies every kept row bit-exactly and writes its original
+// (k, y, x) triple and flat index.
+#include "ttf_device.h"
+#include "ttf_internal.h"
+
+namespace ttf {
+namespace {
+
+// Exclusive scan over the sequence  [N, c(b,0), ..., c(b,F-1)]  for b = 0..B-1, where c(b,k) is
+// the number of kept tokens of source frame k and 0 for the anchor frame.  The entry in front
+// of each clip places its N anchor rows first.
+__global__ __launch_bounds__(1024) void k_offsets_scan(const uint64_t* __restrict__ keep_bits,
+                                                       const int32_t* __restrict__ anchor_index,
+                                                       int32_t* __restrict__ frame_base,
+                                                       int32_t* __restrict__ kept_count,
+                                                       int32_t* __restrict__ row_offsets,
+                                                       int B, int F, int N, int NW)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ int wave_tot[16];
+    __shared__ int carry_s;
+    if (tid == 0) carry_s = 0;
+    __syncthreads();
+    const long long E = (long long)B * (F + 1);
+    for (long long e0 = 0; e0 < E; e0 += 1024) {
+        const long long e = e0 + tid;
+        int v = 0, b = 0, s = 0, a = 0;
+        if (e < E) {
+            b = (int)(e / (F + 1));
+            s = (int)(e % (F + 1));
+            a = anchor_index[b];
+            if (s == 0) {
+                v = N;
+            } else if (s - 1 != a) {
+                const uint64_t* kb = keep_bits + ((size_t)b * F + (s - 1)) * NW;
+                for (int q = 0; q < NW; ++q) v += __popcll(kb[q]);
+            }
+        }
+        int inc = v;                                   // inclusive scan inside the wave
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int o = __shfl_up(inc, d, 64);
+            if (lane >= d) inc += o;
+        }
+        if (lane == 63) wave_tot[wave] = inc;
+        __syncthreads();
+        int pre = carry_s;
+        for (int q = 0; q < wave; ++q) pre += wave_tot[q];
+        const int excl = pre + inc - v;
+        if (e < E) {
+            if (s == 0) {
+                row_offsets[b] = excl;
+                frame_base[(size_t)b * F + a] = excl;
+            } else if (s - 1 != a) {
+                frame_base[(size_t)b * F + (s - 1)] = excl;
+            }
+        }
+        __syncthreads();
+        if (tid == 1023) carry_s = excl + v;
+        __syncthreads();
+    }
+    if (tid == 0) row_offsets[B] = carry_s;
+    __syncthreads();
+    for (int b = tid; b < B; b += 1024) kept_count[b] = row_offsets[b + 1] - row_offsets[b];
+}
+
+// U = bytes moved per lane per step: 16 (row bytes % 16 == 0), 4 or 2.
+template <int U>
+__device__ __forceinline__ void copy_row(const char* __restrict__ src, char* __restrict__ dst,
+                                         size_t row_bytes, int lane)
+{
+    if constexpr (U == 16) {
+        const uint4* s = reinterpret_cast<const uint4*>(src);
+        uint4* d = reinterpret_cast<uint4*>(dst);
+        const int n = (int)(row_bytes / 16);
+        int q = lane;
+        for (; q + 192 < n; q += 256) {               // four 16-byte pieces in flight per lane
+            const uint4 v0 = s[q], v1 = s[q + 64], v2 = s[q + 128], v3 = s[q + 192];
+            d[q] = v0; d[q + 64] = v1; d[q + 128] = v2; d[q + 192] = v3;
+        }
+        for (; q < n; q += 64) d[q] = s[q];
+    } else if constexpr (U == 4) {
+        const uint32_t* s = reinterpret_cast<const uint32_t*>(src);
+        uint32_t* d = reinterpret_cast<uint32_t*>(dst);
+        const int n = (int)(row_bytes / 4);
+        for (int q = lane; q < n; q += 64) d[q] = s[q];
+    } else {
+        const uint16_t* s = reinterpret_cast<const uint16_t*>(src);
+        uint16_t* d = reinterpret_cast<uint16_t*>(dst);
+        const int n = (int)(row_bytes / 2);
+        for (int q = lane; q < n; q += 64) d[q] = s[q];
+    }
+}
+
+// One block = one 64-token word of one frame; wave w copies the kept tokens among its 16.
+template <int U>
+__global__ __launch_bounds__(256) void k_emit_rows(const char* __restrict__ x,
+                                                   const uint64_t* __restrict__ keep_bits,
+                                                   const int32_t* __restrict__ frame_base,
+                                                   char* __restrict__ tokens_out,
+                                                   int32_t* __restrict__ pos_ids,
+                                                   int32_t* __restrict__ src_index,
+                                                   int F, int N, int W, int NW, size_t row_bytes, size_t cap)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int word = blockIdx.x % NW;
+    const size_t frame = blockIdx.x / NW;
+    const int k = (int)(frame % F);
+    const uint64_t* kb = keep_bits + frame * (size_t)NW;
+    const uint64_t bits = kb[word];
+    if (bits == 0) return;
+    int before = frame_base[frame];
+    for (int q = 0; q < word; ++q) before += __popcll(kb[q]);
+    for (int q = 0; q < 16; ++q) {
+        const int bit = wave * 16 + q;
+        if (!((bits >> bit) & 1ull)) continue;
+        const int i = word * 64 + bit;
+        const size_t row = (size_t)before + __popcll(bits & ((1ull << bit) - 1ull));
+        copy_row<U>(x + (frame * (size_t)N + i) * row_bytes, tokens_out + row * row_bytes, row_bytes, lane);
+        if (lane == 0) {
+            pos_ids[row] = k;
+            pos_ids[cap + row] = i / W;
+            pos_ids[2 * cap + row] = i % W;
+            src_index[row] = k * N + i;
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_offsets_scan(const ttf_params& p, const Workspace& w, const int32_t* anchor_index,
+                               int32_t* kept_count, int32_t* row_offsets, hipStream_t s)
+{
+    const int N = p.H * p.W, NW = (N + 63) / 64;
+    k_offsets_scan<<<1, 1024, 0, s>>>(w.keep_bits, anchor_index, w.frame_base, kept_count, row_offsets,
+                                      p.B, p.F, N, NW);
+    return hipGetLastError();
+}
+
+hipError_t launch_emit_rows(const ttf_params& p, const void* x, const Workspace& w,
+                            const int32_t* anchor_index, void* tokens_out, int32_t* pos_ids,
+                            int32_t* src_index, hipStream_t s)
+{
+    (void)anchor_index;
+    const int N = p.H * p.W, NW = (N + 63) / 64;
+    const size_t row_bytes = (size_t)p.C * (p.dtype == TTF_BF16 ? 2 : 4);
+    const size_t cap = (size_t)p.B * p.F * N;
+    const unsigned grid = (unsigned)((size_t)p.B * p.F * NW);
+    const char* xs = static_cast<const char*>(x);
+    char* out = static_cast<char*>(tokens_out);
+    if (row_bytes % 16 == 0)
+        k_emit_rows<16><<<grid, 256, 0, s>>>(xs, w.keep_bits, w.frame_base, out, pos_ids, src_index,
+                                             p.F, N, p.W, NW, row_bytes, cap);
+    else if (row_bytes % 4 == 0)
+        k_emit_rows<4><<<grid, 256, 0, s>>>(xs, w.keep_bits, w.frame_base, out, pos_ids, src_index,
+                                            p.F, N, p.W, NW, row_bytes, cap);
+    else
+        k_emit_rows<2><<<grid, 256, 0, s>>>(xs, w.keep_bits, w.frame_base, out, pos_ids, src_index,
+                                            p.F, N, p.W, NW, row_bytes, cap);
+    return hipGetLastError();
+}
+
+}  // namespace ttf

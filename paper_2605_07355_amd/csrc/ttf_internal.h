@@ -1,0 +1,65 @@
+// Internal declarations of the TTF library for gfx950: workspace layout and the launch
+// functions behind ttf_compress.  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "ttf.h"
+
+namespace ttf {
+
+constexpr int kWave = 64;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Device scratch carved out of the caller's workspace.  All sections are 256-byte aligned.
+struct Workspace {
+    float*    frame_sum;     // [B,F,C]  sum over the N tokens of every frame (anchor rule, inner sum)
+    double*   clip_sum;      // [B,C]    sum over all F*N tokens of a clip (anchor rule, outer sum)
+    double*   frame_score;   // [B,F]    cosine(frame mean, clip mean)
+    float*    anchor_inv;    // [B,N]    1/||x_{a,j}|| of every anchor token (0 for a zero token)
+    uint64_t* keep_bits;     // [B,F,NW] bit i%64 of word i/64 set iff token i is kept (NW=ceil(N/64))
+    int32_t*  frame_base;    // [B,F]    output row of the first kept token of every frame
+    size_t    bytes;
+};
+
+inline Workspace carve(const ttf_params& p, void* base)
+{
+    const size_t B = p.B, F = p.F, N = (size_t)p.H * p.W, C = p.C, NW = (N + 63) / 64;
+    size_t off = 0;
+    auto take = [&](size_t n) { size_t o = off; off = align_up(off + n, 256); return o; };
+    const size_t o_fs = take(B * F * C * sizeof(float));
+    const size_t o_cs = take(B * C * sizeof(double));
+    const size_t o_sc = take(B * F * sizeof(double));
+    const size_t o_ai = take(B * N * sizeof(float));
+    const size_t o_kb = take(B * F * NW * sizeof(uint64_t));
+    const size_t o_fb = take(B * F * sizeof(int32_t));
+    char* c = static_cast<char*>(base);
+    Workspace w;
+    w.frame_sum   = reinterpret_cast<float*>(c + o_fs);
+    w.clip_sum    = reinterpret_cast<double*>(c + o_cs);
+    w.frame_score = reinterpret_cast<double*>(c + o_sc);
+    w.anchor_inv  = reinterpret_cast<float*>(c + o_ai);
+    w.keep_bits   = reinterpret_cast<uint64_t*>(c + o_kb);
+    w.frame_base  = reinterpret_cast<int32_t*>(c + o_fb);
+    w.bytes = off;
+    return w;
+}
+
+// Stage launchers.  Each enqueues on `s` and returns the launch status.
+hipError_t launch_frame_sums(const ttf_params& p, const void* x, const Workspace& w, hipStream_t s);
+hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, hipStream_t s);
+hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const Workspace& w,
+                               int32_t* anchor_index, hipStream_t s);
+hipError_t launch_window_search(const ttf_params& p, const void* x, const Workspace& w,
+                                const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
+                                int32_t* best_idx, hipStream_t s);
+hipError_t launch_offsets_scan(const ttf_params& p, const Workspace& w, const int32_t* anchor_index,
+                               int32_t* kept_count, int32_t* row_offsets, hipStream_t s);
+hipError_t launch_emit_rows(const ttf_params& p, const void* x, const Workspace& w,
+                            const int32_t* anchor_index, void* tokens_out, int32_t* pos_ids,
+                            int32_t* src_index, hipStream_t s);
+
+}  // namespace ttf

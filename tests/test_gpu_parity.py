@@ -1,0 +1,238 @@
+"""GPU parity: the HIP library, called through its C ABI, against the fp64 CPU oracle on the
+same seeded inputs.  Integer, index and byte outputs must match bit for bit; best_sim within
+1e-5 absolute.  Inputs come from the workload generator with decision margins enforced
+(|s^ - t| >= 1e-3, best - runner-up >= 1e-4, anchor score gap >= 1e-4), so that the fp32
+GPU arithmetic and the fp64 oracle must take the same decisions."""
+import numpy as np
+import pytest
+import torch
+
+from workloads import CONFIGS, make_clip_batch, f32_to_bf16_bits
+from workloads.ttf_gen import identical_frames, independent_frames, translated_frames
+
+from helpers import compare_with_oracle, run_gpu, to_device
+
+pytestmark = pytest.mark.gpu
+
+ANCHOR_AUTO, ANCHOR_FIXED = 0, 1
+
+
+def _prepared(cfg, seed=None, anchor="auto", ts=None, r=None):
+    """Generate, enforce margins with the oracle, return (batch, oracle result for ts[0])."""
+    from oracle import margins
+    ts = cfg.t if ts is None else ts
+    r = cfg.r if r is None else r
+    mode, idx = (ANCHOR_AUTO, 0) if anchor == "auto" else (ANCHOR_FIXED, int(anchor))
+    seed = cfg.seed if seed is None else seed
+    for attempt in range(4):
+        batch = make_clip_batch(cfg, seed=seed + 1000 * attempt)
+        try:
+            res = margins.enforce_margins(batch, r, ts, mode, idx, want_tokens=False)
+            return batch, res
+        except margins.MarginError:
+            continue
+    raise RuntimeError("no seed met the margins")
+
+
+def _parity(cfg, seed=None, anchor="auto", r=None, t=None):
+    r = cfg.r if r is None else r
+    t = cfg.t[0] if t is None else t
+    batch, res = _prepared(cfg, seed, anchor, ts=(t,), r=r)
+    _, out = run_gpu(batch.x, r, t, anchor)
+    compare_with_oracle(batch.x, out, res)
+    return batch, res, out
+
+
+# ----------------------------------------------------------------- the named workloads
+def test_tiny_config():
+    _, res, _ = _parity(CONFIGS["tiny"])
+    assert 0 < res.fused_fraction() < 1
+
+
+def test_qwen3vl_2b_config():
+    _, res, _ = _parity(CONFIGS["qwen3vl_2b"])
+    assert abs(res.fused_fraction() - 0.67) < 0.03
+
+
+def test_qwen3vl_8b_batched_config():
+    """The headline workload at full size, in the launch configuration the benchmark times."""
+    _, res, _ = _parity(CONFIGS["qwen3vl_8b_batched"])
+    assert abs(res.fused_fraction() - 0.67) < 0.02
+    assert len(set(res.anchor_index.tolist())) > 4            # clips pick different anchors
+
+
+def test_long_video_config_threshold_sweep(oracle):
+    cfg = CONFIGS["long_video"]
+    batch, res0 = _prepared(cfg)                               # margins hold for all three thresholds
+    rhos = []
+    for t in cfg.t:
+        res = res0 if t == cfg.t[0] else oracle.compress(batch.x, cfg.r, t, want_tokens=False)
+        _, out = run_gpu(batch.x, cfg.r, t)
+        compare_with_oracle(batch.x, out, res)
+        rhos.append(float(res.reduction_ratio().mean()))
+    by_t = dict(zip(cfg.t, rhos))
+    assert by_t[0.60] > by_t[0.70] > by_t[0.80] > 0.02         # lower threshold, more fusion (ablation A1)
+
+
+def test_highres_wide_config():
+    _, res, _ = _parity(CONFIGS["highres_wide"])
+    assert res.fused_fraction() > 0.5
+
+
+# ----------------------------------------------------------------- shapes that span tiles and ragged tails
+SHAPES = [
+    # B, F, H,  W,  C,   dtype,  r
+    (2, 3, 5, 7, 40, "f32", 1),          # N=35 < one 64-token word, C multiple of 4 only
+    (1, 4, 9, 9, 33, "f32", 2),          # odd C: scalar loads
+    (3, 5, 10, 13, 72, "bf16", 1),       # N=130: two full words and a ragged one
+    (2, 4, 6, 6, 50, "bf16", 0),         # C % 8 != 0: scalar bf16 loads, 1x1 window
+    (1, 6, 16, 16, 256, "bf16", 1),      # tile-aligned grid
+    (2, 5, 16, 16, 96, "bf16", 2),
+    (1, 3, 32, 32, 64, "bf16", 2),
+    (1, 3, 32, 16, 128, "bf16", 3),
+    (2, 3, 12, 20, 64, "f32", 30),       # radius beyond the grid: global matching
+    (1, 2, 1, 1, 8, "f32", 1),           # single-token frames
+    (1, 9, 3, 200, 32, "bf16", 1),       # wide, flat grid
+]
+
+
+@pytest.mark.parametrize("B,F,H,W,C,dtype,r", SHAPES)
+def test_shapes(B, F, H, W, C, dtype, r):
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=B, F=F, H=H, W=W, C=C, dtype=dtype, r=r, max_offset=min(max(r, 1), 2),
+                                       sigma=0.5)
+    _parity(cfg, seed=100 + B + F + H + W + C + r)
+
+
+@pytest.mark.parametrize("anchor", [0, -1, 2, -3])
+def test_fixed_anchor(anchor):
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=2, F=6, H=8, W=8, C=128)
+    _, res, out = _parity(cfg, seed=7, anchor=anchor)
+    assert (res.anchor_index == anchor % cfg.F).all()
+
+
+# ----------------------------------------------------------------- degenerate cases
+def _direct(x_np, r, t, anchor, oracle, check_sim=True):
+    mode, idx = (ANCHOR_AUTO, 0) if anchor == "auto" else (ANCHOR_FIXED, int(anchor))
+    res = oracle.compress(x_np, r, t, mode, idx, want_tokens=False)
+    _, out = run_gpu(x_np, r, t, anchor)
+    compare_with_oracle(x_np, out, res, check_sim=check_sim)
+    return res, out
+
+
+def test_single_frame(oracle):
+    cfg = CONFIGS["tiny"].scaled(F=1)
+    res, out = _direct(make_clip_batch(cfg).x, 1, 0.7, "auto", oracle)
+    assert res.kept_count[0] == cfg.N
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_identical_frames_fuse_everything(oracle, dtype):
+    """Every source token equals its anchor token: cos = 1 at dst = i, everything fused."""
+    cfg = CONFIGS["tiny"].scaled(B=2, F=5, H=9, W=9, C=128)
+    x = identical_frames(cfg, seed=3)
+    x = f32_to_bf16_bits(x) if dtype == "bf16" else x
+    res, out = _direct(x, 1, 0.7, 2, oracle)         # anchor fixed: all frame scores tie
+    assert (res.kept_count == cfg.N).all()
+    sim = out.buffers.best_sim.cpu().numpy()
+    assert np.abs(sim - 1.0).max() <= 1e-5
+
+
+def test_independent_frames_fuse_nothing(oracle):
+    cfg = CONFIGS["tiny"].scaled(B=1, F=4, H=8, W=8, C=1024)
+    res, _ = _direct(independent_frames(cfg, seed=4), 1, 0.7, 0, oracle)
+    assert res.kept_count[0] == cfg.F * cfg.N
+
+
+def test_translated_frames_recover_motion(oracle):
+    cfg = CONFIGS["tiny"].scaled(F=5, H=7, W=9, C=64)
+    x = translated_frames(cfg, [(1, 0), (0, -1), (-1, 1), (1, 1)], seed=5)
+    # border tokens see the same content twice (clamped translation): ties between distinct anchor
+    # tokens of equal similarity resolve to the lowest index on both sides
+    res, _ = _direct(x, 1, 0.999, 0, oracle)
+    assert res.kept_count[0] == cfg.N
+
+
+def test_zero_rows(oracle):
+    cfg = CONFIGS["tiny"].scaled(F=3, H=4, W=4, C=32)
+    x = make_clip_batch(cfg, seed=6).x.copy()
+    x[0, 1, 1, 1] = 0.0          # zero source token: cosine 0, kept
+    x[0, 0, 2, 2] = 0.0          # zero anchor token
+    res, out = _direct(x, 1, 0.0, 0, oracle)
+    assert res.fuse_map[0, 1, 5] == -1 and out.buffers.best_sim[0, 1, 5].item() == 0.0
+
+
+def test_duplicate_anchor_tokens_tie_to_lowest_index(oracle):
+    cfg = CONFIGS["tiny"].scaled(F=2, H=6, W=6, C=64)
+    x = identical_frames(cfg, seed=9)
+    x[0, 0, :, :] = x[0, 0, 2, 2]
+    res, _ = _direct(x, 1, 0.5, 0, oracle)
+    ys, xs = np.divmod(np.arange(cfg.N), cfg.W)
+    np.testing.assert_array_equal(res.best_idx[0, 1], np.maximum(ys - 1, 0) * cfg.W + np.maximum(xs - 1, 0))
+
+
+def test_two_calls_are_bit_identical():
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=2, F=8)
+    x_np = make_clip_batch(cfg, seed=12).x
+    _, a = run_gpu(x_np, 1, 0.7)
+    _, b = run_gpu(x_np, 1, 0.7)
+    for name in ("tokens_out", "pos_ids", "src_index", "row_offsets", "kept_count", "anchor_index",
+                 "fuse_map", "best_idx"):
+        ta, tb = getattr(a.buffers, name), getattr(b.buffers, name)
+        assert torch.equal(ta.view(torch.uint8), tb.view(torch.uint8)), name
+    assert torch.equal(a.buffers.best_sim.view(torch.int32), b.buffers.best_sim.view(torch.int32))
+
+
+def test_optional_outputs_and_host_counts(oracle):
+    import paper_2605_07355_amd as ttf
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=3, F=4, H=8, W=8, C=64)
+    batch, res = _prepared(cfg, seed=13)
+    x = to_device(batch.x)
+    buf = ttf.TTFBuffers.allocate(cfg.B, cfg.F, cfg.H, cfg.W, cfg.C, x.dtype, x.device, want_sim=False,
+                                  want_host_counts=True)
+    buf.host_counts.fill_(-1)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    out = ttf.ttf_compress(x, r=1, t=0.7, buffers=buf, want_sim=False, stream=side)   # a non-default stream
+    side.synchronize()
+    np.testing.assert_array_equal(buf.host_counts[:cfg.B].numpy(), res.kept_count)
+    np.testing.assert_array_equal(buf.host_counts[cfg.B:].numpy(), res.row_offsets)
+    np.testing.assert_array_equal(buf.fuse_map.cpu().numpy(), res.fuse_map)
+    np.testing.assert_array_equal(buf.src_index.cpu().numpy()[:res.total_rows], res.src_index[:res.total_rows])
+
+
+def test_errors_touch_nothing():
+    import paper_2605_07355_amd as ttf
+    cfg = CONFIGS["tiny"]
+    x = to_device(make_clip_batch(cfg).x)
+    buf = ttf.TTFBuffers.allocate(cfg.B, cfg.F, cfg.H, cfg.W, cfg.C, x.dtype, x.device)
+    buf.fuse_map.fill_(-7)
+    with pytest.raises(ttf.TTFError) as e:
+        ttf.ttf_compress(x, r=-1, t=0.7, buffers=buf)
+    assert e.value.status == 1
+    with pytest.raises(ttf.TTFError) as e:
+        ttf.ttf_compress(x, r=1, t=float("nan"), buffers=buf)
+    assert e.value.status == 1
+    with pytest.raises(ttf.TTFError) as e:
+        ttf.ttf_compress(x, r=1, t=0.7, anchor=cfg.F, buffers=buf)
+    assert e.value.status == 1
+    small = ttf.TTFBuffers.allocate(cfg.B, cfg.F, cfg.H, cfg.W, cfg.C, x.dtype, x.device)
+    small.workspace = small.workspace[:512]
+    with pytest.raises(ttf.TTFError) as e:
+        ttf.ttf_compress(x, r=1, t=0.7, buffers=small)
+    assert e.value.status == 3
+    torch.cuda.synchronize()
+    assert (buf.fuse_map == -7).all()
+
+
+def test_stage_profile_reports_every_stage():
+    import paper_2605_07355_amd as ttf
+    cfg = CONFIGS["qwen3vl_2b"].scaled(F=8)
+    x = to_device(make_clip_batch(cfg).x)
+    ttf.ttf_profile_enable(True)
+    try:
+        ttf.ttf_compress(x)
+        ms = ttf.ttf_profile_read()
+    finally:
+        ttf.ttf_profile_enable(False)
+    assert set(ms) == set(ttf.STAGE_NAMES)
+    assert all(v >= 0 for v in ms.values()) and ms["window_search"] > 0
