@@ -107,8 +107,9 @@ ttf_status ttf_workspace_size(const ttf_params* params, size_t* bytes);
  *   hip_stream hipStream_t (NULL = the default stream).
  * Errors: INVALID_ARG (NULL params/features/workspace/out or required output, a size < 1,
  * B*F*H*W >= 2^31, r < 0, t not finite, anchor_index outside [-F,F) in FIXED mode, unknown
- * anchor_mode), UNSUPPORTED (unknown dtype; features, tokens_out or workspace misaligned;
- * C*sizeof(element) not a multiple of 4), WORKSPACE_TOO_SMALL, HIP.
+ * anchor_mode), UNSUPPORTED (unknown dtype; features, tokens_out or workspace misaligned),
+ * WORKSPACE_TOO_SMALL, HIP.  Any C works; rows whose byte length is a multiple of 16 take the
+ * vector paths.
  */
 ttf_status ttf_compress(const ttf_params* params, const void* features,
                         void* workspace, size_t workspace_bytes,
@@ -122,18 +123,22 @@ int ttf_last_hip_error(void);
 
 /*
  * Per-stage timing, for benchmarks.  Stages, in launch order:
- *   0 frame sums   1 anchor choice   2 anchor norms   3 window search + gate
+ *   0 frame sums   1 anchor scores   2 anchor choice + norms   3 window search + gate
  *   4 offsets scan 5 row emission
- * ttf_profile_enable(1) makes every following ttf_compress on this thread record HIP
- * events around each stage on the call's stream (events are created once and reused);
- * ttf_profile_read() waits for the last profiled call to finish and returns the stage
- * durations in milliseconds (ms_out[0..n), n <= TTF_NUM_STAGES; stages that did not run
- * report 0).  Profiling inserts event records between kernels and is off by default.
- * ttf_profile_read returns INVALID_ARG if nothing was recorded.
+ * ttf_profile_enable(slots), 1 <= slots <= TTF_PROFILE_MAX_SLOTS, makes every following
+ * ttf_compress on the calling thread record HIP events around each stage on the call's
+ * stream; successive calls use `slots` event sets round-robin (created once, reused), so up to
+ * `slots` calls can be in flight or waiting to be read.  ttf_profile_enable(0) turns it off.
+ * Enabling resets the call counter.  ttf_profile_read(call, ms_out, n) waits for profiled call
+ * number `call` (0-based since enabling; must be one of the last `slots` calls) and writes its
+ * stage durations in milliseconds to ms_out[0..min(n, TTF_NUM_STAGES)); stages that did not
+ * run report ~0.  Event records sit between the kernels; profiling is off by default.
+ * Errors: INVALID_ARG (bad slot count, NULL, call not available), HIP.
  */
 #define TTF_NUM_STAGES 6
-ttf_status ttf_profile_enable(int enable);
-ttf_status ttf_profile_read(float* ms_out, int n);
+#define TTF_PROFILE_MAX_SLOTS 256
+ttf_status ttf_profile_enable(int slots);
+ttf_status ttf_profile_read(int call, float* ms_out, int n);
 const char* ttf_stage_name(int stage);
 
 #ifdef __cplusplus

@@ -62,7 +62,7 @@ def load_library() -> ctypes.CDLL:
         lib.ttf_profile_enable.restype = ctypes.c_int
         lib.ttf_profile_enable.argtypes = [ctypes.c_int]
         lib.ttf_profile_read.restype = ctypes.c_int
-        lib.ttf_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_int]
+        lib.ttf_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.c_int]
         lib.ttf_stage_name.restype = ctypes.c_char_p
         lib.ttf_stage_name.argtypes = [ctypes.c_int]
         _lib = lib
@@ -213,12 +213,13 @@ def ttf_compress(features: torch.Tensor, r: int = 1, t: float = 0.70, anchor: Un
     return TTFOutput(buffers, B, F, H, W, C)
 
 
-def ttf_profile_enable(enable: bool) -> None:
-    _check(load_library().ttf_profile_enable(1 if enable else 0))
+def ttf_profile_enable(slots: int) -> None:
+    """Record per-stage HIP events for the following calls (``slots`` event sets, 0 = off)."""
+    _check(load_library().ttf_profile_enable(int(slots)))
 
 
-def ttf_profile_read():
-    """Stage durations (ms) of the last profiled call on this thread, keyed by stage name."""
+def ttf_profile_read(call: int = 0):
+    """Stage durations (ms) of profiled call number ``call`` on this thread, keyed by stage name."""
     buf = (ctypes.c_float * TTF_NUM_STAGES)()
-    _check(load_library().ttf_profile_read(buf, TTF_NUM_STAGES))
+    _check(load_library().ttf_profile_read(int(call), buf, TTF_NUM_STAGES))
     return {STAGE_NAMES[i]: float(buf[i]) for i in range(TTF_NUM_STAGES)}

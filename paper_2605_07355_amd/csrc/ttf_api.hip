@@ -2,6 +2,7 @@
 // Section 3 (anchor selection -> window search + gate -> offsets -> row emission) and the
 // optional per-stage event timing.  Nothing here allocates device memory.
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 
 #include "ttf_internal.h"
@@ -12,10 +13,22 @@ hipError_t launch_window_search_generic(const ttf_params& p, const void* x, cons
                                         const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                         int32_t* best_idx, hipStream_t s);
 
+bool mfma_search_supported(const ttf_params& p);
+hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, const Workspace& w,
+                                     const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
+                                     int32_t* best_idx, hipStream_t s);
+
+// bf16 tokens on 16- or 32-wide grids take the matrix-core kernel; everything else (fp32 input,
+// other grids, large radii, odd channel counts) takes the general wave-per-token kernel.  Setting
+// the environment variable TTF_SEARCH=general forces the general kernel (for comparisons).
 hipError_t launch_window_search(const ttf_params& p, const void* x, const Workspace& w,
                                 const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                 int32_t* best_idx, hipStream_t s)
 {
+    const char* force = std::getenv("TTF_SEARCH");
+    const bool general = force && std::strcmp(force, "general") == 0;
+    if (!general && mfma_search_supported(p))
+        return launch_window_search_mfma(p, x, w, anchor_index, fuse_map, best_sim, best_idx, s);
     return launch_window_search_generic(p, x, w, anchor_index, fuse_map, best_sim, best_idx, s);
 }
 
@@ -23,11 +36,13 @@ namespace {
 
 thread_local int g_last_hip_error = 0;
 
+// Event sets for stage timing: `slots` sets of TTF_NUM_STAGES+1 events, used round-robin by
+// successive profiled calls so that a benchmark can time many calls and read them afterwards.
 struct Profile {
-    bool enabled = false;
-    bool created = false;
-    bool recorded = false;
-    hipEvent_t ev[TTF_NUM_STAGES + 1];
+    int slots = 0;                 // 0 = profiling off
+    int created = 0;               // event sets that exist
+    long long calls = 0;           // profiled calls since enabling
+    hipEvent_t ev[TTF_PROFILE_MAX_SLOTS][TTF_NUM_STAGES + 1];
 };
 thread_local Profile g_prof;
 
@@ -84,11 +99,12 @@ ttf_status ttf_compress(const ttf_params* params, const void* features, void* wo
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     Profile& prof = g_prof;
-    const bool timing = prof.enabled && prof.created;
+    const bool timing = prof.slots > 0;
+    hipEvent_t* ev = timing ? prof.ev[prof.calls % prof.slots] : nullptr;
     hipError_t e = hipSuccess;
     int stage = 0;
     auto mark = [&]() {
-        if (timing && e == hipSuccess) e = hipEventRecord(prof.ev[stage], s);
+        if (timing && e == hipSuccess) e = hipEventRecord(ev[stage], s);
         ++stage;
     };
 #define TTF_STEP(call)                 \
@@ -122,7 +138,7 @@ ttf_status ttf_compress(const ttf_params* params, const void* features, void* wo
         g_last_hip_error = static_cast<int>(e);
         return TTF_ERR_HIP;
     }
-    if (timing) prof.recorded = true;
+    if (timing) ++prof.calls;
     return TTF_OK;
 }
 
@@ -140,32 +156,34 @@ const char* ttf_status_string(ttf_status status)
 
 int ttf_last_hip_error(void) { return g_last_hip_error; }
 
-ttf_status ttf_profile_enable(int enable)
+ttf_status ttf_profile_enable(int slots)
 {
     Profile& prof = g_prof;
-    if (enable && !prof.created) {
+    if (slots < 0 || slots > TTF_PROFILE_MAX_SLOTS) return TTF_ERR_INVALID_ARG;
+    for (; prof.created < slots; ++prof.created) {
         for (int i = 0; i <= TTF_NUM_STAGES; ++i) {
-            const hipError_t e = hipEventCreate(&prof.ev[i]);
+            const hipError_t e = hipEventCreate(&prof.ev[prof.created][i]);
             if (e != hipSuccess) {
-                for (int j = 0; j < i; ++j) (void)hipEventDestroy(prof.ev[j]);
+                for (int j = 0; j < i; ++j) (void)hipEventDestroy(prof.ev[prof.created][j]);
                 g_last_hip_error = static_cast<int>(e);
                 return TTF_ERR_HIP;
             }
         }
-        prof.created = true;
     }
-    prof.enabled = enable != 0;
-    if (!prof.enabled) prof.recorded = false;
+    prof.slots = slots;
+    prof.calls = 0;
     return TTF_OK;
 }
 
-ttf_status ttf_profile_read(float* ms_out, int n)
+ttf_status ttf_profile_read(int call, float* ms_out, int n)
 {
     Profile& prof = g_prof;
-    if (!ms_out || n < 0 || !prof.created || !prof.recorded) return TTF_ERR_INVALID_ARG;
-    hipError_t e = hipEventSynchronize(prof.ev[TTF_NUM_STAGES]);
+    if (!ms_out || n < 0 || prof.slots <= 0) return TTF_ERR_INVALID_ARG;
+    if (call < 0 || call >= prof.calls || call < prof.calls - prof.slots) return TTF_ERR_INVALID_ARG;
+    hipEvent_t* ev = prof.ev[call % prof.slots];
+    hipError_t e = hipEventSynchronize(ev[TTF_NUM_STAGES]);
     for (int i = 0; i < n && i < TTF_NUM_STAGES && e == hipSuccess; ++i)
-        e = hipEventElapsedTime(&ms_out[i], prof.ev[i], prof.ev[i + 1]);
+        e = hipEventElapsedTime(&ms_out[i], ev[i], ev[i + 1]);
     if (e != hipSuccess) {
         g_last_hip_error = static_cast<int>(e);
         return TTF_ERR_HIP;

@@ -228,11 +228,15 @@ def test_stage_profile_reports_every_stage():
     import paper_2605_07355_amd as ttf
     cfg = CONFIGS["qwen3vl_2b"].scaled(F=8)
     x = to_device(make_clip_batch(cfg).x)
-    ttf.ttf_profile_enable(True)
+    ttf.ttf_profile_enable(2)
     try:
-        ttf.ttf_compress(x)
-        ms = ttf.ttf_profile_read()
+        for _ in range(3):
+            ttf.ttf_compress(x)
+        ms = ttf.ttf_profile_read(2)
+        ttf.ttf_profile_read(1)
+        with pytest.raises(ttf.TTFError):
+            ttf.ttf_profile_read(0)              # overwritten: only the last two calls are held
     finally:
-        ttf.ttf_profile_enable(False)
+        ttf.ttf_profile_enable(0)
     assert set(ms) == set(ttf.STAGE_NAMES)
     assert all(v >= 0 for v in ms.values()) and ms["window_search"] > 0
