@@ -5,6 +5,8 @@
 // everything after that in fp64 on [B,F,C] numbers.  A last kernel picks the arg max (lowest
 // k on ties) and computes 1/||x_{a,j}|| for the anchor tokens, which the window search uses
 // as the anchor half of every cosine denominator.
+#include <type_traits>
+
 #include "ttf_device.h"
 #include "ttf_internal.h"
 
@@ -106,6 +108,25 @@ __global__ __launch_bounds__(256) void k_frame_score(const float* __restrict__ f
     }
 }
 
+// Arg max of frame_score[b, 0..F) computed by one wave (every lane gets the result); lowest k on
+// ties; frame 0 if every score is NaN.
+__device__ __forceinline__ int pick_anchor(const double* __restrict__ frame_score, int b, int F, int lane)
+{
+    double best = -1.0e300;
+    int arg = 0x7fffffff;
+    for (int k = lane; k < F; k += 64) {                // ascending k per lane: strict > keeps the lowest
+        const double s = frame_score[(size_t)b * F + k];
+        if (s > best) { best = s; arg = k; }
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        const double ob = __shfl_xor(best, m, 64);
+        const int oa = __shfl_xor(arg, m, 64);
+        if (ob > best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+    }
+    return arg == 0x7fffffff ? 0 : arg;
+}
+
 // Picks the anchor of clip b (arg max of frame_score, lowest k on ties, or the fixed frame),
 // publishes it, and writes 1/||x_{a,j}|| for the anchor tokens.  One wave per anchor token.
 template <typename T, int V>
@@ -118,22 +139,7 @@ __global__ __launch_bounds__(256) void k_anchor_norms(const T* __restrict__ x,
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int b = blockIdx.x / groups;
     const int j = (blockIdx.x % groups) * 4 + wave;
-    int a = fixed_anchor;
-    if (a < 0) {
-        double best = -1.0e300;
-        int arg = 0x7fffffff;
-        for (int k = lane; k < F; k += 64) {            // ascending k per lane: strict > keeps the lowest
-            const double s = frame_score[(size_t)b * F + k];
-            if (s > best) { best = s; arg = k; }
-        }
-#pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) {
-            const double ob = __shfl_xor(best, m, 64);
-            const int oa = __shfl_xor(arg, m, 64);
-            if (ob > best || (ob == best && oa < arg)) { best = ob; arg = oa; }
-        }
-        a = arg == 0x7fffffff ? 0 : arg;                // all-NaN scores: frame 0
-    }
+    const int a = fixed_anchor >= 0 ? fixed_anchor : pick_anchor(frame_score, b, F, lane);
     if (blockIdx.x % groups == 0 && threadIdx.x == 0) anchor_index[b] = a;
     if (j >= N) return;
     const T* row = x + (((size_t)b * F + a) * N + j) * (size_t)C;
@@ -146,6 +152,65 @@ __global__ __launch_bounds__(256) void k_anchor_norms(const T* __restrict__ x,
     }
     ss = wave_sum(ss);
     if (lane == 0) anchor_inv[(size_t)b * N + j] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+}
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+// Matrix-core path.  One workgroup (8 waves) per anchor tile of 16 tokens: picks the anchor,
+// reads the tile once with coalesced loads (lane l: chunk l%4 of token l/4), accumulates squared
+// norms, permutes every 16x64-byte block into MFMA operand order (lane = token + 16*chunk) and
+// stores it as one contiguous KiB: anchor_frag[b][tile][K-step][lane][8 bf16].
+__global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restrict__ x,
+                                                        const double* __restrict__ frame_score,
+                                                        int32_t* __restrict__ anchor_index,
+                                                        float* __restrict__ anchor_inv,
+                                                        uint16_t* __restrict__ anchor_frag,
+                                                        int F, int N, int C, int fixed_anchor)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tiles = N / 16;
+    const int b = blockIdx.x / tiles, tile = blockIdx.x % tiles;
+    const int a = fixed_anchor >= 0 ? fixed_anchor : pick_anchor(frame_score, b, F, lane);
+    if (tile == 0 && threadIdx.x == 0) anchor_index[b] = a;
+    const int KS = C / 32;
+    const uint16_t* src = x + (((size_t)b * F + a) * N + 16 * tile + (lane >> 2)) * (size_t)C + (lane & 3) * 8;
+    uint16_t* dst = anchor_frag + ((size_t)b * tiles + tile) * (size_t)KS * 512 + lane * 8;
+    const int bperm = (4 * (lane & 15) + (lane >> 4)) * 4;
+    float nn = 0.f;
+    constexpr int UN = 8;                                   // K-steps in flight per wave
+    for (int k0 = wave; k0 < KS; k0 += 8 * UN) {
+        uint4 v[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int ks = k0 + 8 * u;
+            if (ks < KS) v[u] = *reinterpret_cast<const uint4*>(src + (size_t)ks * 32);
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int ks = k0 + 8 * u;
+            if (ks < KS) {
+                uint32_t r[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bf16x2 p = __builtin_bit_cast(bf16x2, r[e]);
+                    nn = __builtin_amdgcn_fdot2_f32_bf16(p, p, nn, false);
+                    r[e] = (uint32_t)__builtin_amdgcn_ds_bpermute(bperm, (int)r[e]);
+                }
+                *reinterpret_cast<uint4*>(dst + (size_t)ks * 512) = uint4{r[0], r[1], r[2], r[3]};
+            }
+        }
+    }
+    nn += __shfl_xor(nn, 1, 64);
+    nn += __shfl_xor(nn, 2, 64);
+    __shared__ float part[8][16];
+    if ((lane & 3) == 0) part[wave][lane >> 2] = nn;
+    __syncthreads();
+    if (threadIdx.x < 16) {
+        float ss = part[0][threadIdx.x];
+#pragma unroll
+        for (int w = 1; w < 8; ++w) ss += part[w][threadIdx.x];
+        anchor_inv[(size_t)b * N + 16 * tile + threadIdx.x] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+    }
 }
 
 template <typename F>
@@ -198,6 +263,18 @@ hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const Workspa
             static_cast<const T*>(x), w.frame_score, anchor_index, w.anchor_inv, p.F, N, p.C, fixed, groups);
         return hipGetLastError();
     });
+}
+
+hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const Workspace& w,
+                                      int32_t* anchor_index, hipStream_t s)
+{
+    const int N = p.H * p.W;
+    int fixed = -1;
+    if (p.anchor_mode == TTF_ANCHOR_FIXED) fixed = p.anchor_index < 0 ? p.anchor_index + p.F : p.anchor_index;
+    k_anchor_prepare<<<(unsigned)(p.B * (N / 16)), 512, 0, s>>>(static_cast<const uint16_t*>(x), w.frame_score,
+                                                                anchor_index, w.anchor_inv, w.anchor_frag,
+                                                                p.F, N, p.C, fixed);
+    return hipGetLastError();
 }
 
 }  // namespace ttf

@@ -13,21 +13,25 @@ hipError_t launch_window_search_generic(const ttf_params& p, const void* x, cons
                                         const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                         int32_t* best_idx, hipStream_t s);
 
-bool mfma_search_supported(const ttf_params& p);
 hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, const Workspace& w,
                                      const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                      int32_t* best_idx, hipStream_t s);
 
-// bf16 tokens on 16- or 32-wide grids take the matrix-core kernel; everything else (fp32 input,
+// bf16 tokens on 16- or 32-wide grids take the matrix-core kernels; everything else (fp32 input,
 // other grids, large radii, odd channel counts) takes the general wave-per-token kernel.  Setting
-// the environment variable TTF_SEARCH=general forces the general kernel (for comparisons).
+// the environment variable TTF_SEARCH=general forces the general kernels (for comparisons).
+bool use_mfma_path(const ttf_params& p)
+{
+    const char* force = std::getenv("TTF_SEARCH");
+    const bool general = force && std::strcmp(force, "general") == 0;
+    return !general && mfma_search_supported(p);
+}
+
 hipError_t launch_window_search(const ttf_params& p, const void* x, const Workspace& w,
                                 const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                 int32_t* best_idx, hipStream_t s)
 {
-    const char* force = std::getenv("TTF_SEARCH");
-    const bool general = force && std::strcmp(force, "general") == 0;
-    if (!general && mfma_search_supported(p))
+    if (use_mfma_path(p))
         return launch_window_search_mfma(p, x, w, anchor_index, fuse_map, best_sim, best_idx, s);
     return launch_window_search_generic(p, x, w, anchor_index, fuse_map, best_sim, best_idx, s);
 }
@@ -117,7 +121,8 @@ ttf_status ttf_compress(const ttf_params* params, const void* features, void* wo
     mark();
     if (p.anchor_mode == TTF_ANCHOR_AUTO) TTF_STEP(launch_anchor_scores(p, w, s));
     mark();
-    TTF_STEP(launch_anchor_norms(p, features, w, out->anchor_index, s));
+    if (use_mfma_path(p)) TTF_STEP(launch_anchor_prepare_mfma(p, features, w, out->anchor_index, s));
+    else TTF_STEP(launch_anchor_norms(p, features, w, out->anchor_index, s));
     mark();
     TTF_STEP(launch_window_search(p, features, w, out->anchor_index, out->fuse_map, out->best_sim,
                                   out->best_idx, s));

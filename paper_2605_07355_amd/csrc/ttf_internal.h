@@ -20,6 +20,7 @@ struct Workspace {
     double*   clip_sum;      // [B,C]    sum over all F*N tokens of a clip (anchor rule, outer sum)
     double*   frame_score;   // [B,F]    cosine(frame mean, clip mean)
     float*    anchor_inv;    // [B,N]    1/||x_{a,j}|| of every anchor token (0 for a zero token)
+    uint16_t* anchor_frag;   // [B,N/16,C/32,64,8] bf16 anchor frame in MFMA fragment order (matrix-core path)
     uint64_t* keep_bits;     // [B,F,NW] bit i%64 of word i/64 set iff token i is kept (NW=ceil(N/64))
     int32_t*  frame_base;    // [B,F]    output row of the first kept token of every frame
     size_t    bytes;
@@ -34,6 +35,7 @@ inline Workspace carve(const ttf_params& p, void* base)
     const size_t o_cs = take(B * C * sizeof(double));
     const size_t o_sc = take(B * F * sizeof(double));
     const size_t o_ai = take(B * N * sizeof(float));
+    const size_t o_af = take(p.dtype == TTF_BF16 ? B * N * C * sizeof(uint16_t) : 0);
     const size_t o_kb = take(B * F * NW * sizeof(uint64_t));
     const size_t o_fb = take(B * F * sizeof(int32_t));
     char* c = static_cast<char*>(base);
@@ -42,6 +44,7 @@ inline Workspace carve(const ttf_params& p, void* base)
     w.clip_sum    = reinterpret_cast<double*>(c + o_cs);
     w.frame_score = reinterpret_cast<double*>(c + o_sc);
     w.anchor_inv  = reinterpret_cast<float*>(c + o_ai);
+    w.anchor_frag = reinterpret_cast<uint16_t*>(c + o_af);
     w.keep_bits   = reinterpret_cast<uint64_t*>(c + o_kb);
     w.frame_base  = reinterpret_cast<int32_t*>(c + o_fb);
     w.bytes = off;
@@ -53,6 +56,10 @@ hipError_t launch_frame_sums(const ttf_params& p, const void* x, const Workspace
 hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, hipStream_t s);
 hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const Workspace& w,
                                int32_t* anchor_index, hipStream_t s);
+// Matrix-core path: anchor choice, inverse norms and the anchor frame re-laid in fragment order.
+hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const Workspace& w,
+                                      int32_t* anchor_index, hipStream_t s);
+bool mfma_search_supported(const ttf_params& p);
 hipError_t launch_window_search(const ttf_params& p, const void* x, const Workspace& w,
                                 const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                 int32_t* best_idx, hipStream_t s);

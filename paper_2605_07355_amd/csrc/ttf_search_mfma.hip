@@ -9,19 +9,23 @@
 // consecutive anchor tokens) with fp32 accumulation at a small fraction of that cost; only the
 // band |dx| <= r of each 16x16 result is used.  The kernel is then bound by HBM, as intended.
 //
-// Work split.  One workgroup of 8 wavefronts owns 32 consecutive tokens of one source frame
-// (two source tiles: two grid rows when W = 16, one grid row when W = 32).  The channel axis is
-// split across the wavefronts: wave w owns channels [w*C/8, (w+1)*C/8).  Each wave loads its
-// slice of both source tiles straight from HBM into registers in MFMA operand layout (16 rows x
-// 64 bytes per load; the dot product is invariant under any permutation of channels applied to
-// both operands, so the natural 8-channel groups per lane are used), streams the matching
-// slices of the anchor tiles from L2, and accumulates partial 16x16 products.  The partials of
-// the 8 waves are added through LDS in wave order (fixed order: results are reproducible),
-// then one wave per source tile forms the cosines, masks the band, takes the arg max (lowest
-// anchor index on ties), applies the threshold and writes s^, dst, the fuse map and 16 keep bits.
-//
-// Source squared norms come from the diagonal of tile x tile^T on the matrix cores; anchor
-// inverse norms are precomputed per clip.
+// Data movement is what the design is about:
+//  * Source tokens are read exactly once, with coalesced 16-byte loads (lane l reads chunk l%4 of
+//    token l/4: four tokens x 64 contiguous bytes per quarter-wave), and moved into MFMA operand
+//    order (lane = token + 16*chunk) by four ds_bpermute per fragment.  Loading straight in
+//    operand order would make every lane of a quarter-wave touch a different cache line, which
+//    the texture path serves at one line per clock.
+//  * Anchor tokens are re-used by every source frame, so their inverse norms and a copy of the
+//    anchor frame in fragment order (1 KiB per tile and K-step, lane-major) are prepared once
+//    per clip (ttf_anchor.hip); the search streams those fragments from L2 fully coalesced.
+//  * One workgroup (4 wavefronts) owns the same 32 grid cells (two source tiles) in FR
+//    consecutive source frames, so every anchor fragment fetched from L2 feeds FR frames.
+//  * The channel axis is split across the 4 wavefronts; partial 16x16 products are added through
+//    LDS in wave order (fixed order: reproducible), then one wave per source tile forms the
+//    cosines, masks the band, takes the arg max (lowest anchor index on ties), applies the
+//    threshold and writes s^, dst, the fuse map and 16 keep bits.
+//  * Source squared norms: v_dot2 on the loaded fragments (one VGPR per tile), reduced with the
+//    products.
 #include "ttf_device.h"
 #include "ttf_internal.h"
 
@@ -29,10 +33,10 @@ namespace ttf {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-constexpr int kWaves = 8;                 // wavefronts per workgroup = channel slices
-constexpr int kGroup = 7;                 // result tiles reduced through LDS per round (7*8 KiB)
+constexpr int kWaves = 4;                 // wavefronts per workgroup = channel slices
 constexpr float kNegInf = -__builtin_inff();
 
 // Geometry of one workgroup's problem.  CT = W/16 column tiles per grid row.
@@ -40,22 +44,21 @@ template <int CT, int RAD>
 struct Shape {
     static_assert(CT == 1 || CT == 2, "grids of width 16 or 32");
     static constexpr int W = 16 * CT;
-    static constexpr int ROWS = (2 * RAD + 1);
-    // anchor tiles held per K-step: CT==1: rows y0-RAD .. y0+1+RAD; CT==2: rows y-RAD .. y+RAD, 2 columns
+    static constexpr int ROWS = 2 * RAD + 1;
+    // anchor tiles fetched per K-step: CT==1: rows y0-RAD .. y0+1+RAD; CT==2: rows y-RAD .. y+RAD, 2 columns
     static constexpr int NA = CT == 1 ? 2 * RAD + 2 : 2 * ROWS;
     // anchor tiles paired with each source tile
     static constexpr int NPS = CT == 1 ? ROWS : 2 * ROWS;
-    // anchor tile index of pair q of source tile s
-    __device__ static constexpr int pair_tile(int s, int q) { return CT == 1 ? s + q : q; }
-    __device__ static constexpr int tile_row(int a) { return CT == 1 ? a : a / 2; }   // offset from ylo
+    // source frames per workgroup and anchor fragment prefetch distance: sized so accumulators
+    // (4*NPS VGPRs per source tile), source fragments (4 per tile and K-step) and the anchor
+    // ring (4*NA per K-step) fit the 256 VGPRs of a wave at two waves per SIMD
+    static constexpr int FR = NPS <= 3 ? 4 : (NPS <= 6 ? 2 : 1);
+    static constexpr int PF = NA <= 6 ? 2 : 1;
+    // source tiles whose partial products go through LDS together (<= 48 KiB)
+    static constexpr int RT = NPS <= 3 ? 4 : (NPS <= 6 ? 2 : 1);
+    __device__ static constexpr int pair_tile(int u, int q) { return CT == 1 ? u + q : q; }   // u = tile within frame
+    __device__ static constexpr int tile_row(int a) { return CT == 1 ? a : a / 2; }           // offset from ylo
     __device__ static constexpr int tile_col(int a) { return CT == 1 ? 0 : a % 2; }
-    __device__ static constexpr int src_col(int s) { return CT == 1 ? 0 : s; }
-    __device__ static constexpr int src_row(int s) { return CT == 1 ? s : 0; }       // offset from first row
-    // K-steps of both source tiles a wave keeps in registers at once; bounded by the 256 VGPRs a
-    // wave may use at two waves per SIMD (accumulators take 8*(NPS+1), anchor fragments 4*NA)
-    static constexpr int MAXK = NPS <= 3 ? 16 : (NPS <= 6 ? 8 : 4);
-    // K-steps of anchor fragments requested ahead of use (ring of PF+1 buffers, 4*NA VGPRs each)
-    static constexpr int PF = NA <= 4 ? 3 : (NA <= 6 ? 2 : 1);
 };
 
 __device__ __forceinline__ bf16x8 load_frag(const uint16_t* p)
@@ -63,27 +66,29 @@ __device__ __forceinline__ bf16x8 load_frag(const uint16_t* p)
     return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p));
 }
 
-template <int CT, int RAD, int KSW, int PF>
+template <int CT, int RAD, int KSW>
 __global__ __launch_bounds__(kWaves * 64) void k_search_mfma(
-    const uint16_t* __restrict__ x, const int32_t* __restrict__ anchor_index,
-    const float* __restrict__ anchor_inv, int32_t* __restrict__ fuse_map, float* __restrict__ best_sim,
-    int32_t* __restrict__ best_idx, uint16_t* __restrict__ keep16, int F, int H, int C, float t, int passes)
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ anchor_frag,
+    const int32_t* __restrict__ anchor_index, const float* __restrict__ anchor_inv,
+    int32_t* __restrict__ fuse_map, float* __restrict__ best_sim, int32_t* __restrict__ best_idx,
+    uint16_t* __restrict__ keep16, int F, int H, int C, float t, int passes, int groups)
 {
     using S = Shape<CT, RAD>;
-    constexpr int W = S::W, NA = S::NA, NPS = S::NPS;
+    constexpr int W = S::W, NA = S::NA, NPS = S::NPS, FR = S::FR, PF = S::PF, RT = S::RT;
+    constexpr int NS = 2 * FR;                               // source tiles of the workgroup
     constexpr int NB = PF + 1;                               // anchor fragment ring
     const int N = H * W;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, g = lane >> 4;
-    const int tpf = N / 32;                                  // workgroups per frame
+    const int tpf = N / 32;                                  // workgroups per frame group
     const int tp = blockIdx.x % tpf;
-    const size_t frame = blockIdx.x / tpf;                   // b*F + k
-    const int b = (int)(frame / F), k = (int)(frame % F);
+    const int grp = (blockIdx.x / tpf) % (groups + 1);
+    const int b = blockIdx.x / tpf / (groups + 1);
     const int a = anchor_index[b];
-    const int i0 = tp * 32;                                  // first token of this workgroup
-    const size_t o0 = frame * (size_t)N + i0;
+    const int i0 = tp * 32;                                  // first grid cell of this workgroup
 
-    if (k == a) {                                            // anchor tokens are always retained
+    if (grp == groups) {                                     // anchor tokens are always retained
+        const size_t o0 = ((size_t)b * F + a) * N + i0;
         if (threadIdx.x < 32) {
             fuse_map[o0 + threadIdx.x] = -1;
             if (best_sim) best_sim[o0 + threadIdx.x] = 1.0f;
@@ -96,127 +101,146 @@ __global__ __launch_bounds__(kWaves * 64) void k_search_mfma(
     const int y0 = i0 / W;                                   // first (or only) source row
     const int ylo = y0 - RAD;
     const int slice = C / kWaves;                            // channels per wave
-    const uint16_t* xf = x + frame * (size_t)N * C;
-    const uint16_t* xa = x + ((size_t)b * F + a) * (size_t)N * C;
-    const int kofs = wave * slice + g * 8;
+    const int KS = C / 32;                                   // K-steps per token
+    const int nsrc = F - 1;                                  // source frames of the clip (>= 1 here)
 
-    const uint16_t* sp[2];
+    // source frame of slot f: the f-th source frame of this group, the last one repeated past the end
+    const uint16_t* sp[NS];                                  // load order: lane -> token lane/4, chunk lane%4
 #pragma unroll
-    for (int s = 0; s < 2; ++s) sp[s] = xf + (size_t)(i0 + 16 * s + m) * C + kofs;
+    for (int s = 0; s < NS; ++s) {
+        const int si = min(grp * FR + s / 2, nsrc - 1);
+        const int k = si + (si >= a ? 1 : 0);
+        sp[s] = x + (((size_t)b * F + k) * N + i0 + 16 * (s % 2) + (lane >> 2)) * (size_t)C +
+                wave * slice + (lane & 3) * 8;
+    }
+    const int bperm = (4 * m + g) * 4;                       // operand lane (token m, chunk g) <- load lane 4m+g
     const uint16_t* ap[NA];
 #pragma unroll
     for (int q = 0; q < NA; ++q) {
         const int yy = min(max(ylo + S::tile_row(q), 0), H - 1);      // rows outside the grid: clamped, masked later
-        ap[q] = xa + (size_t)(yy * W + 16 * S::tile_col(q) + m) * C + kofs;
+        const int tile = yy * CT + S::tile_col(q);
+        ap[q] = anchor_frag + (((size_t)b * (N / 16) + tile) * KS + wave * (slice / 32)) * 512 + lane * 8;
     }
 
-    f32x4 acc[2][NPS], nrm[2];
+    f32x4 acc[NS][NPS];
+    float nv[NS];
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        nrm[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < NS; ++s) {
+        nv[s] = 0.f;
 #pragma unroll
         for (int q = 0; q < NPS; ++q) acc[s][q] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
     for (int pass = 0; pass < passes; ++pass) {
-        const int off = pass * KSW * 32;
-        // Anchor fragments run PF K-steps ahead of their use in a ring of PF+1 buffers.  Their
-        // first PF K-steps are requested before the source loads: loads complete in issue order,
-        // so products can start as soon as the first source fragments land.
+        const int ks0 = pass * KSW;
+        // Anchor fragments run PF K-steps ahead of their use in a ring of PF+1 buffers; the first
+        // PF are requested before the source loads (loads complete in issue order).
         bf16x8 Bt[NB][NA];
 #pragma unroll
         for (int d = 0; d < PF && d < KSW; ++d) {
 #pragma unroll
-            for (int q = 0; q < NA; ++q) Bt[d][q] = load_frag(ap[q] + off + d * 32);
+            for (int q = 0; q < NA; ++q) Bt[d][q] = load_frag(ap[q] + (size_t)(ks0 + d) * 512);
         }
-        bf16x8 A[2][KSW];
+        uint4 A[NS][KSW];
 #pragma unroll
         for (int ks = 0; ks < KSW; ++ks) {
 #pragma unroll
-            for (int s = 0; s < 2; ++s) A[s][ks] = load_frag(sp[s] + off + ks * 32);
+            for (int s = 0; s < NS; ++s) A[s][ks] = *reinterpret_cast<const uint4*>(sp[s] + (ks0 + ks) * 32);
         }
-        // all source loads of the pass go out before any product: that many bytes in flight per
-        // wave is what hides HBM latency (the scheduler would otherwise sink them to their uses)
+        // every source load of the pass is issued before any product (the scheduler would
+        // otherwise sink them to their uses and serialise on HBM latency)
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < KSW; ++ks) {
             if (ks + PF < KSW) {
 #pragma unroll
-                for (int q = 0; q < NA; ++q) Bt[(ks + PF) % NB][q] = load_frag(ap[q] + off + (ks + PF) * 32);
+                for (int q = 0; q < NA; ++q) Bt[(ks + PF) % NB][q] = load_frag(ap[q] + (size_t)(ks0 + ks + PF) * 512);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                nrm[s] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[s][ks], A[s][ks], nrm[s], 0, 0, 0);
+            for (int s = 0; s < NS; ++s) {
+                // (fragments are kept as four plain 32-bit words: v_dot2 on elements extracted from
+                // a bit-cast vector was observed to read element 0 four times)
+                uint32_t r[4] = {A[s][ks].x, A[s][ks].y, A[s][ks].z, A[s][ks].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bf16x2 p = __builtin_bit_cast(bf16x2, r[e]);
+                    nv[s] = __builtin_amdgcn_fdot2_f32_bf16(p, p, nv[s], false);
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) r[e] = (uint32_t)__builtin_amdgcn_ds_bpermute(bperm, (int)r[e]);
+                const bf16x8 av = __builtin_bit_cast(bf16x8, uint4{r[0], r[1], r[2], r[3]});
 #pragma unroll
                 for (int q = 0; q < NPS; ++q)
-                    acc[s][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[s][ks], Bt[ks % NB][S::pair_tile(s, q)],
+                    acc[s][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, Bt[ks % NB][S::pair_tile(s % 2, q)],
                                                                         acc[s][q], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
     }
 
-    // ---- add the 8 channel slices through LDS (wave order), one source tile at a time ----
-    __shared__ f32x4 red[kWaves][kGroup][64];
+    // squared-norm partials: lanes 4i..4i+3 hold the four chunks of token i
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        nv[s] += __shfl_xor(nv[s], 1, 64);
+        nv[s] += __shfl_xor(nv[s], 2, 64);
+    }
+
+    // ---- add the channel slices through LDS (wave order), RT source tiles per round ----
+    __shared__ f32x4 red[kWaves][RT][NPS][64];
+    __shared__ float rnv[kWaves][RT][64];
     const float* ainv = anchor_inv + (size_t)b * N;
 
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        float best[4] = {kNegInf, kNegInf, kNegInf, kNegInf};
-        int arg[4] = {-1, -1, -1, -1};
-        float sinv[4] = {0.f, 0.f, 0.f, 0.f};
-        // tile slot 0 is the norm tile, slots 1..NPS the pair tiles; groups of kGroup slots
+    for (int round = 0; round < NS / RT; ++round) {
 #pragma unroll
-        for (int base = 0; base <= NPS; base += kGroup) {
+        for (int sl = 0; sl < RT; ++sl) {
+            const int s = round * RT + sl;
+            rnv[wave][sl][lane] = nv[s];
 #pragma unroll
-            for (int u = 0; u < kGroup; ++u) {
-                const int slot = base + u;
-                if (slot <= NPS) red[wave][u][lane] = slot == 0 ? nrm[s] : acc[s][slot == 0 ? 0 : slot - 1];
+            for (int q = 0; q < NPS; ++q) red[wave][sl][q][lane] = acc[s][q];
+        }
+        __syncthreads();
+        if (wave < RT) {
+            const int sl = wave;
+            const int s = round * RT + sl;                   // wave-uniform
+            const int f = s / 2, u = s % 2;
+            const bool live = grp * FR + f < nsrc;            // slots past the last source frame are repeats
+            float sinv[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float nn = rnv[0][sl][4 * (4 * g + j)];
+#pragma unroll
+                for (int w = 1; w < kWaves; ++w) nn += rnv[w][sl][4 * (4 * g + j)];
+                sinv[j] = nn > 0.f ? 1.0f / sqrtf(nn) : 0.f;
             }
-            __syncthreads();
-            if (wave == s) {
+            float best[4] = {kNegInf, kNegInf, kNegInf, kNegInf};
+            int arg[4] = {-1, -1, -1, -1};
+            const int ysrc = y0 + (CT == 1 ? u : 0);
+            const int xsrc0 = CT == 1 ? 0 : 16 * u;
 #pragma unroll
-                for (int u = 0; u < kGroup; ++u) {
-                    const int slot = base + u;
-                    if (slot > NPS) continue;
-                    f32x4 v = red[0][u][lane];
+            for (int q = 0; q < NPS; ++q) {
+                f32x4 v = red[0][sl][q][lane];
 #pragma unroll
-                    for (int w = 1; w < kWaves; ++w) {
-                        const f32x4 p = red[w][u][lane];
-                        v[0] += p[0]; v[1] += p[1]; v[2] += p[2]; v[3] += p[3];
-                    }
-                    if (slot == 0) {
-                        // ||x_{k,i}||^2 of token 4g+j sits on the diagonal: lane 16g + 4g + j, element j
+                for (int w = 1; w < kWaves; ++w) {
+                    const f32x4 p = red[w][sl][q][lane];
+                    v[0] += p[0]; v[1] += p[1]; v[2] += p[2]; v[3] += p[3];
+                }
+                // anchor tile of pair q: CT==1: row ysrc-RAD+q; CT==2: row ylo + q/2, column q%2
+                const int yy = CT == 1 ? ysrc - RAD + q : ylo + q / 2;
+                const int xa_col = (CT == 1 ? 0 : 16 * (q % 2)) + m;      // this lane's anchor column
+                const bool row_ok = yy >= 0 && yy < H;
+                const int ja = yy * W + xa_col;
+                const float ai = row_ok ? ainv[ja] : 0.f;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const float nn = __shfl(v[j], (lane & 48) + 4 * g + j, 64);
-                            sinv[j] = nn > 0.f ? 1.0f / sqrtf(nn) : 0.f;
-                        }
-                    } else {
-                        const int q = slot - 1;
-                        const int tile = S::pair_tile(s, q);
-                        const int yy = ylo + S::tile_row(tile);
-                        const int xa_col = 16 * S::tile_col(tile) + m;          // this lane's anchor column
-                        const bool row_ok = yy >= 0 && yy < H &&
-                                            yy >= y0 + S::src_row(s) - RAD && yy <= y0 + S::src_row(s) + RAD;
-                        const int ja = yy * W + xa_col;
-                        const float ai = row_ok ? ainv[ja] : 0.f;
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const int xs_col = 16 * S::src_col(s) + 4 * g + j;  // source token's column
-                            const int dx = xa_col - xs_col;
-                            if (row_ok && dx >= -RAD && dx <= RAD) {
-                                const float sim = v[j] * sinv[j] * ai;
-                                if (sim > best[j]) { best[j] = sim; arg[j] = ja; }   // ascending ja per lane
-                            }
-                        }
+                for (int j = 0; j < 4; ++j) {
+                    const int dx = xa_col - (xsrc0 + 4 * g + j);          // anchor column - source column
+                    if (row_ok && dx >= -RAD && dx <= RAD) {
+                        const float sim = v[j] * sinv[j] * ai;
+                        if (sim > best[j]) { best[j] = sim; arg[j] = ja; }   // ascending ja per lane
                     }
                 }
             }
-            __syncthreads();
-        }
-        if (wave == s) {
             // arg max across the 16 anchor columns held by the 16 lanes of a group; lowest index on ties
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -230,22 +254,28 @@ __global__ __launch_bounds__(kWaves * 64) void k_search_mfma(
                     }
                 }
             }
+            const int si = min(grp * FR + f, nsrc - 1);
+            const int k = si + (si >= a ? 1 : 0);
+            const size_t o0 = ((size_t)b * F + k) * N + i0 + 16 * u;
             unsigned keep = 0;
             if (m == 0) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const size_t o = o0 + 16 * s + 4 * g + j;
+                    const size_t o = o0 + 4 * g + j;
                     const bool fused = best[j] > t;                   // keep = 1[s^ <= t]
-                    fuse_map[o] = fused ? arg[j] : -1;
-                    if (best_sim) best_sim[o] = best[j];
-                    if (best_idx) best_idx[o] = arg[j];
+                    if (live) {
+                        fuse_map[o] = fused ? arg[j] : -1;
+                        if (best_sim) best_sim[o] = best[j];
+                        if (best_idx) best_idx[o] = arg[j];
+                    }
                     if (!fused) keep |= 1u << (4 * g + j);
                 }
             }
             keep |= __shfl_xor(keep, 16, 64);
             keep |= __shfl_xor(keep, 32, 64);
-            if (lane == 0) keep16[o0 / 16 + s] = (uint16_t)keep;
+            if (lane == 0 && live) keep16[o0 / 16] = (uint16_t)keep;
         }
+        __syncthreads();
     }
 }
 
@@ -253,33 +283,32 @@ template <int CT, int RAD>
 hipError_t launch_shape(const ttf_params& p, const void* x, const Workspace& w, const int32_t* anchor_index,
                         int32_t* fuse_map, float* best_sim, int32_t* best_idx, hipStream_t s)
 {
+    using S = Shape<CT, RAD>;
     const int N = p.H * p.W;
-    const unsigned grid = (unsigned)((size_t)p.B * p.F * (N / 32));
+    const int groups = (p.F - 1 + S::FR - 1) / S::FR;        // groups of source frames per clip
+    const unsigned grid = (unsigned)((size_t)p.B * (groups + 1) * (N / 32));
     const int ksw_total = p.C / (kWaves * 32);               // K-steps per wave
     const uint16_t* xs = static_cast<const uint16_t*>(x);
     uint16_t* keep16 = reinterpret_cast<uint16_t*>(w.keep_bits);
-#define TTF_LAUNCH(KSW)                                                                                   \
-    k_search_mfma<CT, RAD, KSW, Shape<CT, RAD>::PF><<<grid, kWaves * 64, 0, s>>>(xs, anchor_index, w.anchor_inv, fuse_map,    \
-                                                             best_sim, best_idx, keep16, p.F, p.H, p.C,   \
-                                                             p.t, ksw_total / KSW)
-    constexpr int MAXK = Shape<CT, RAD>::MAXK;
-    if (MAXK >= 16 && ksw_total % 16 == 0) TTF_LAUNCH(16);
-    else if (MAXK >= 8 && ksw_total % 8 == 0) TTF_LAUNCH(8);
-    else if (ksw_total % 4 == 0) TTF_LAUNCH(4);
-    else if (ksw_total % 2 == 0) TTF_LAUNCH(2);
-    else TTF_LAUNCH(1);
-#undef TTF_LAUNCH
+    if (ksw_total % 2 == 0)
+        k_search_mfma<CT, RAD, 2><<<grid, kWaves * 64, 0, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv,
+                                                               fuse_map, best_sim, best_idx, keep16, p.F, p.H,
+                                                               p.C, p.t, ksw_total / 2, groups);
+    else
+        k_search_mfma<CT, RAD, 1><<<grid, kWaves * 64, 0, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv,
+                                                               fuse_map, best_sim, best_idx, keep16, p.F, p.H,
+                                                               p.C, p.t, ksw_total, groups);
     return hipGetLastError();
 }
 
 }  // namespace
 
-// True when the matrix-core kernel covers this problem: bf16, grid width 16 (even height) or 32,
-// radius <= 2, channel count a multiple of 256 (8 wave slices of whole 32-channel K-steps), and a
-// token count per frame that is a multiple of 64 so keep words are whole.
+// True when the matrix-core kernels cover this problem: bf16, grid width 16 or 32, radius <= 2,
+// channel count a multiple of 128 (4 wave slices of whole 32-channel K-steps), and a token count
+// per frame that is a multiple of 64 so that 64-bit keep words are whole.
 bool mfma_search_supported(const ttf_params& p)
 {
-    if (p.dtype != TTF_BF16 || p.r > 2 || p.C % 256 != 0) return false;
+    if (p.dtype != TTF_BF16 || p.r > 2 || p.C % 128 != 0) return false;
     if (p.W == 16) return p.H % 4 == 0;
     if (p.W == 32) return p.H % 2 == 0;
     return false;

@@ -86,7 +86,14 @@ SHAPES = [
     (1, 4, 9, 9, 33, "f32", 2),          # odd C: scalar loads
     (3, 5, 10, 13, 72, "bf16", 1),       # N=130: two full words and a ragged one
     (2, 4, 6, 6, 50, "bf16", 0),         # C % 8 != 0: scalar bf16 loads, 1x1 window
-    (1, 6, 16, 16, 256, "bf16", 1),      # tile-aligned grid
+    (1, 6, 16, 16, 256, "bf16", 1),      # tile-aligned grid: matrix-core path, two K-steps per wave
+    (2, 5, 16, 16, 128, "bf16", 2),      # matrix-core path, one K-step per wave, 5x5 window
+    (1, 6, 16, 16, 384, "bf16", 0),      # matrix-core path, 1x1 window, last frame group partly empty
+    (1, 2, 16, 16, 128, "bf16", 1),      # one source frame only
+    (3, 3, 4, 16, 512, "bf16", 1),       # N = 64: a single keep word per frame
+    (2, 7, 8, 32, 128, "bf16", 1),       # 32-wide grid on the matrix-core path
+    (1, 4, 32, 32, 256, "bf16", 2),      # 32-wide grid, 5x5 window
+    (1, 5, 6, 32, 256, "bf16", 0),
     (2, 5, 16, 16, 96, "bf16", 2),
     (1, 3, 32, 32, 64, "bf16", 2),
     (1, 3, 32, 16, 128, "bf16", 3),
