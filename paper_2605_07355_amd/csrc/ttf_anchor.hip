@@ -31,10 +31,10 @@ __global__ __launch_bounds__(256) void k_frame_sums(const T* __restrict__ x, flo
         int i = wave;
         for (; i + 12 < N; i += 16) {          // four rows in flight per wave
             RowVec<T, V> r0, r1, r2, r3;
-            r0.load(base + (size_t)i * C);
-            r1.load(base + (size_t)(i + 4) * C);
-            r2.load(base + (size_t)(i + 8) * C);
-            r3.load(base + (size_t)(i + 12) * C);
+            r0.template load<true>(base + (size_t)i * C);
+            r1.template load<true>(base + (size_t)(i + 4) * C);
+            r2.template load<true>(base + (size_t)(i + 8) * C);
+            r3.template load<true>(base + (size_t)(i + 12) * C);
 #pragma unroll
             for (int e = 0; e < V; ++e) acc[e] += r0.v[e];
 #pragma unroll
@@ -46,7 +46,7 @@ __global__ __launch_bounds__(256) void k_frame_sums(const T* __restrict__ x, flo
         }
         for (; i < N; i += 4) {
             RowVec<T, V> r0;
-            r0.load(base + (size_t)i * C);
+            r0.template load<true>(base + (size_t)i * C);
 #pragma unroll
             for (int e = 0; e < V; ++e) acc[e] += r0.v[e];
         }

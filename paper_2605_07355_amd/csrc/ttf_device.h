@@ -9,6 +9,19 @@ namespace ttf {
 
 struct bf16_t { uint16_t bits; };
 
+// 16-byte accesses marked non-temporal: token rows are streamed (each byte is used once per pass),
+// so they should not displace the anchor data and small arrays that are re-read from cache.
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+__device__ __forceinline__ uint4 load16_stream(const void* p)
+{
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return uint4{v[0], v[1], v[2], v[3]};
+}
+__device__ __forceinline__ void store16_stream(void* p, uint4 v)
+{
+    __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4*>(p));
+}
+
 __device__ __forceinline__ float widen(bf16_t v)
 {
     return __builtin_bit_cast(float, static_cast<uint32_t>(v.bits) << 16);
@@ -20,13 +33,14 @@ __device__ __forceinline__ float widen(float v) { return v; }
 template <typename T, int V>
 struct RowVec {
     float v[V];
+    template <bool STREAM = false>
     __device__ __forceinline__ void load(const T* p)
     {
         if constexpr (V == 1) {
             v[0] = widen(p[0]);
         } else if constexpr (sizeof(T) == 2) {
             static_assert(V == 8, "bf16 vector path is 8 elements");
-            const uint4 q = *reinterpret_cast<const uint4*>(p);
+            const uint4 q = STREAM ? load16_stream(p) : *reinterpret_cast<const uint4*>(p);
             const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -35,7 +49,8 @@ struct RowVec {
             }
         } else {
             static_assert(V == 4, "fp32 vector path is 4 elements");
-            const float4 q = *reinterpret_cast<const float4*>(p);
+            const uint4 u = STREAM ? load16_stream(p) : *reinterpret_cast<const uint4*>(p);
+            const float4 q = __builtin_bit_cast(float4, u);
             v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
         }
     }

@@ -80,10 +80,12 @@ __device__ __forceinline__ void copy_row(const char* __restrict__ src, char* __r
         const int n = (int)(row_bytes / 16);
         int q = lane;
         for (; q + 192 < n; q += 256) {               // four 16-byte pieces in flight per lane
-            const uint4 v0 = s[q], v1 = s[q + 64], v2 = s[q + 128], v3 = s[q + 192];
-            d[q] = v0; d[q + 64] = v1; d[q + 128] = v2; d[q + 192] = v3;
+            const uint4 v0 = load16_stream(s + q), v1 = load16_stream(s + q + 64),
+                        v2 = load16_stream(s + q + 128), v3 = load16_stream(s + q + 192);
+            store16_stream(d + q, v0); store16_stream(d + q + 64, v1);
+            store16_stream(d + q + 128, v2); store16_stream(d + q + 192, v3);
         }
-        for (; q < n; q += 64) d[q] = s[q];
+        for (; q < n; q += 64) store16_stream(d + q, load16_stream(s + q));
     } else if constexpr (U == 4) {
         const uint32_t* s = reinterpret_cast<const uint32_t*>(src);
         uint32_t* d = reinterpret_cast<uint32_t*>(dst);

@@ -61,6 +61,22 @@ struct Shape {
     __device__ static constexpr int tile_col(int a) { return CT == 1 ? 0 : a % 2; }
 };
 
+constexpr int kNoArg = 0x7fffffff;       // "no candidate yet" while reducing (so that min() breaks ties)
+
+// One step of an arg max over the 16 lanes of a DPP row: every lane looks at the lane the DPP
+// control pairs it with and keeps the larger value, the lower index on equal values.  NaN never
+// wins a comparison, so it never displaces a number.
+template <int DPP_CTRL>
+__device__ __forceinline__ void row_argmax_step(float& best, int& arg)
+{
+    const float ob = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, best),
+                                                                           DPP_CTRL, 0xf, 0xf, false));
+    const int oa = __builtin_amdgcn_update_dpp(0, arg, DPP_CTRL, 0xf, 0xf, false);
+    const bool take = (ob > best) | ((ob == best) & (oa < arg));
+    best = take ? ob : best;
+    arg = take ? oa : arg;
+}
+
 __device__ __forceinline__ bf16x8 load_frag(const uint16_t* p)
 {
     return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p));
@@ -206,16 +222,18 @@ __global__ __launch_bounds__(kWaves * 64) void k_search_mfma(
             const int s = round * RT + sl;                   // wave-uniform
             const int f = s / 2, u = s % 2;
             const bool live = grp * FR + f < nsrc;            // slots past the last source frame are repeats
+            // (straight-line code from here on: one wave runs this while the others wait, so every
+            // divergent branch would be paid in full)
             float sinv[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 float nn = rnv[0][sl][4 * (4 * g + j)];
 #pragma unroll
                 for (int w = 1; w < kWaves; ++w) nn += rnv[w][sl][4 * (4 * g + j)];
-                sinv[j] = nn > 0.f ? 1.0f / sqrtf(nn) : 0.f;
+                sinv[j] = nn > 0.f ? __builtin_amdgcn_rsqf(nn) : 0.f;
             }
             float best[4] = {kNegInf, kNegInf, kNegInf, kNegInf};
-            int arg[4] = {-1, -1, -1, -1};
+            int arg[4] = {kNoArg, kNoArg, kNoArg, kNoArg};
             const int ysrc = y0 + (CT == 1 ? u : 0);
             const int xsrc0 = CT == 1 ? 0 : 16 * u;
 #pragma unroll
@@ -229,30 +247,27 @@ __global__ __launch_bounds__(kWaves * 64) void k_search_mfma(
                 // anchor tile of pair q: CT==1: row ysrc-RAD+q; CT==2: row ylo + q/2, column q%2
                 const int yy = CT == 1 ? ysrc - RAD + q : ylo + q / 2;
                 const int xa_col = (CT == 1 ? 0 : 16 * (q % 2)) + m;      // this lane's anchor column
-                const bool row_ok = yy >= 0 && yy < H;
-                const int ja = yy * W + xa_col;
-                const float ai = row_ok ? ainv[ja] : 0.f;
+                const bool row_ok = (yy >= 0) & (yy < H);
+                const int ja = min(max(yy, 0), H - 1) * W + xa_col;
+                const float ai = ainv[ja];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int dx = xa_col - (xsrc0 + 4 * g + j);          // anchor column - source column
-                    if (row_ok && dx >= -RAD && dx <= RAD) {
-                        const float sim = v[j] * sinv[j] * ai;
-                        if (sim > best[j]) { best[j] = sim; arg[j] = ja; }   // ascending ja per lane
-                    }
+                    const bool in_band = row_ok & (dx >= -RAD) & (dx <= RAD);
+                    const float sim = in_band ? v[j] * sinv[j] * ai : kNegInf;
+                    const bool take = sim > best[j];                      // ascending ja per lane: first maximum
+                    best[j] = take ? sim : best[j];
+                    arg[j] = take ? ja : arg[j];
                 }
             }
-            // arg max across the 16 anchor columns held by the 16 lanes of a group; lowest index on ties
+            // arg max across the 16 anchor columns held by the 16 lanes of a row; lowest index on ties
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-#pragma unroll
-                for (int d = 1; d < 16; d <<= 1) {
-                    const float ob = __shfl_xor(best[j], d, 64);
-                    const int oa = __shfl_xor(arg[j], d, 64);
-                    if (ob > best[j] || (ob == best[j] && oa >= 0 && (arg[j] < 0 || oa < arg[j]))) {
-                        best[j] = ob;
-                        arg[j] = oa;
-                    }
-                }
+                row_argmax_step<0xB1>(best[j], arg[j]);       // lanes i <-> i^1
+                row_argmax_step<0x4E>(best[j], arg[j]);       // lanes i <-> i^2
+                row_argmax_step<0x141>(best[j], arg[j]);      // mirror inside each half row (8 lanes)
+                row_argmax_step<0x140>(best[j], arg[j]);      // mirror inside the row (16 lanes)
+                arg[j] = arg[j] == kNoArg ? -1 : arg[j];
             }
             const int si = min(grp * FR + f, nsrc - 1);
             const int k = si + (si >= a ? 1 : 0);
