@@ -53,7 +53,7 @@ struct Shape {
     // (4*NPS VGPRs per source tile), source fragments (4 per tile and K-step) and the anchor
     // ring (4*NA per K-step) fit the 256 VGPRs of a wave at two waves per SIMD
     static constexpr int FR = NPS <= 3 ? 4 : (NPS <= 6 ? 2 : 1);
-    static constexpr int PF = NA <= 6 ? 2 : 1;
+    static constexpr int PF = 1;
     // source tiles whose partial products go through LDS together (<= 48 KiB)
     static constexpr int RT = NPS <= 3 ? 4 : (NPS <= 6 ? 2 : 1);
     __device__ static constexpr int pair_tile(int u, int q) { return CT == 1 ? u + q : q; }   // u = tile within frame
@@ -83,7 +83,7 @@ __device__ __forceinline__ bf16x8 load_frag(const uint16_t* p)
 }
 
 template <int CT, int RAD, int KSW>
-__global__ __launch_bounds__(kWaves * 64) void k_search_mfma(
+__global__ __launch_bounds__(kWaves * 64, 2) void k_search_mfma(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ anchor_frag,
     const int32_t* __restrict__ anchor_index, const float* __restrict__ anchor_inv,
     int32_t* __restrict__ fuse_map, float* __restrict__ best_sim, int32_t* __restrict__ best_idx,
