@@ -2,9 +2,9 @@
 //   a* = argmax_k cos( (1/N) sum_i x_{k,i} , (1/(FN)) sum_{k',i} x_{k',i} )
 // The cosine does not change when either argument is scaled, so the kernels work with plain
 // sums: frame sums in fp32 (one streaming pass over X, the only large read of this stage),
-// everything after that in fp64 on [B,F,C] numbers.  A last kernel picks the arg max (lowest
-// k on ties) and computes 1/||x_{a,j}|| for the anchor tokens, which the window search uses
-// as the anchor half of every cosine denominator.
+// everything after that in fp64 on [B,F,C] numbers.  The last kernel of the stage picks the arg
+// max (lowest k on ties) and computes 1/||x_{a,j}|| for the anchor tokens, which the window
+// search uses as the anchor half of every cosine denominator.
 #include <type_traits>
 
 #include "ttf_device.h"
@@ -63,60 +63,108 @@ __global__ __launch_bounds__(256) void k_frame_sums(const T* __restrict__ x, flo
     }
 }
 
-// clip_sum[b,c] = sum_k frame_sum[b,k,c], fp64, k ascending.
-__global__ __launch_bounds__(256) void k_clip_sum(const float* __restrict__ frame_sum,
-                                                  double* __restrict__ clip_sum, int F, int C)
+// Per clip and 256-channel slice, in fp64: the clip sum g = sum_k frame_sum[k] (k ascending inside
+// each of eight interleaved groups, groups added in order), then for every frame the slice's share
+// of <frame_sum_k, g> and |frame_sum_k|^2, and the slice's share of |g|^2.  The cosine of the
+// anchor rule is assembled from these shares by pick_anchor().
+__global__ __launch_bounds__(512) void k_anchor_partials(const float* __restrict__ frame_sum,
+                                                         double* __restrict__ score_part,
+                                                         double* __restrict__ clip_part, int F, int C, int S)
 {
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    const size_t b = blockIdx.y;
-    if (c >= C) return;
-    const float* fs = frame_sum + b * (size_t)F * C + c;
-    double g = 0.0;
-    for (int k = 0; k < F; ++k) g += (double)fs[(size_t)k * C];
-    clip_sum[b * (size_t)C + c] = g;
-}
-
-// frame_score[b,k] = cos(frame_sum[b,k,:], clip_sum[b,:]) in fp64; 0 when a norm is 0.
-__global__ __launch_bounds__(256) void k_frame_score(const float* __restrict__ frame_sum,
-                                                     const double* __restrict__ clip_sum,
-                                                     double* __restrict__ frame_score, int F, int C)
-{
-    const size_t frame = blockIdx.x;              // b*F + k
-    const size_t b = frame / F;
-    const float* fs = frame_sum + frame * (size_t)C;
-    const double* g = clip_sum + b * (size_t)C;
-    double uv = 0.0, uu = 0.0, vv = 0.0;
-    for (int c = threadIdx.x; c < C; c += 256) {
-        const double u = (double)fs[c], v = g[c];
-        uv += u * v;
-        uu += u * u;
-        vv += v * v;
-    }
-    uv = wave_sum(uv);
-    uu = wave_sum(uu);
-    vv = wave_sum(vv);
-    __shared__ double red[3][4];
+    constexpr int NWV = 8, UN = 4;                      // waves per block, frames in flight per wave
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (lane == 0) { red[0][wave] = uv; red[1][wave] = uu; red[2][wave] = vv; }
+    const int slice = blockIdx.x % S;
+    const size_t b = blockIdx.x / S;
+    const float* fs = frame_sum + b * (size_t)F * C;
+    __shared__ double gsh[NWV][256];
+    int c[4];
+    bool ok[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        c[e] = slice * 256 + lane + 64 * e;
+        ok[e] = c[e] < C;
+    }
+    double gp[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int k0 = wave; k0 < F; k0 += NWV * UN) {
+        float v[UN][4];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int k = k0 + NWV * u;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[u][e] = (k < F && ok[e]) ? fs[(size_t)k * C + c[e]] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) gp[e] += (double)v[u][e];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) gsh[wave][lane + 64 * e] = gp[e];
     __syncthreads();
-    if (threadIdx.x == 0) {
-        const double d  = ((red[0][0] + red[0][1]) + red[0][2]) + red[0][3];
-        const double nu = ((red[1][0] + red[1][1]) + red[1][2]) + red[1][3];
-        const double nv = ((red[2][0] + red[2][1]) + red[2][2]) + red[2][3];
-        const double den = sqrt(nu) * sqrt(nv);
-        frame_score[frame] = den > 0.0 ? d / den : 0.0;
+    double g[4], vv = 0.0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int q = lane + 64 * e;
+        double t = gsh[0][q];
+#pragma unroll
+        for (int w = 1; w < NWV; ++w) t += gsh[w][q];
+        g[e] = t;
+        vv += t * t;
+    }
+    vv = wave_sum(vv);
+    if (threadIdx.x == 0) clip_part[b * S + slice] = vv;
+    for (int k0 = wave; k0 < F; k0 += NWV * UN) {
+        float v[UN][4];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int k = k0 + NWV * u;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[u][e] = (k < F && ok[e]) ? fs[(size_t)k * C + c[e]] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int k = k0 + NWV * u;
+            double uv = 0.0, uu = 0.0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const double x = (double)v[u][e];
+                uv += x * g[e];
+                uu += x * x;
+            }
+            uv = wave_sum(uv);
+            uu = wave_sum(uu);
+            if (lane == 0 && k < F) {
+                double* o = score_part + ((b * S + slice) * (size_t)F + k) * 2;
+                o[0] = uv;
+                o[1] = uu;
+            }
+        }
     }
 }
 
-// Arg max of frame_score[b, 0..F) computed by one wave (every lane gets the result); lowest k on
-// ties; frame 0 if every score is NaN.
-__device__ __forceinline__ int pick_anchor(const double* __restrict__ frame_score, int b, int F, int lane)
+// Arg max over k of cos(frame_sum_k, clip_sum), assembled in fp64 from the per-slice shares
+// (slices added in order); 0 when a norm is 0.  Computed by one wave, every lane gets the result;
+// lowest k on ties; frame 0 if every score is NaN.
+__device__ __forceinline__ int pick_anchor(const double* __restrict__ score_part,
+                                           const double* __restrict__ clip_part, int b, int F, int S, int lane)
 {
+    double vv = 0.0;
+#pragma unroll 8
+    for (int s = 0; s < S; ++s) vv += clip_part[(size_t)b * S + s];
     double best = -1.0e300;
     int arg = 0x7fffffff;
     for (int k = lane; k < F; k += 64) {                // ascending k per lane: strict > keeps the lowest
-        const double s = frame_score[(size_t)b * F + k];
-        if (s > best) { best = s; arg = k; }
+        double uv = 0.0, uu = 0.0;
+#pragma unroll 8
+        for (int s = 0; s < S; ++s) {
+            const double2 o = *reinterpret_cast<const double2*>(score_part + (((size_t)b * S + s) * F + k) * 2);
+            uv += o.x;
+            uu += o.y;
+        }
+        const double den = sqrt(uu) * sqrt(vv);
+        const double score = den > 0.0 ? uv / den : 0.0;
+        if (score > best) { best = score; arg = k; }
     }
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) {
@@ -131,15 +179,16 @@ __device__ __forceinline__ int pick_anchor(const double* __restrict__ frame_scor
 // publishes it, and writes 1/||x_{a,j}|| for the anchor tokens.  One wave per anchor token.
 template <typename T, int V>
 __global__ __launch_bounds__(256) void k_anchor_norms(const T* __restrict__ x,
-                                                      const double* __restrict__ frame_score,
+                                                      const double* __restrict__ score_part,
+                                                      const double* __restrict__ clip_part,
                                                       int32_t* __restrict__ anchor_index,
                                                       float* __restrict__ anchor_inv,
-                                                      int F, int N, int C, int fixed_anchor, int groups)
+                                                      int F, int N, int C, int S, int fixed_anchor, int groups)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int b = blockIdx.x / groups;
     const int j = (blockIdx.x % groups) * 4 + wave;
-    const int a = fixed_anchor >= 0 ? fixed_anchor : pick_anchor(frame_score, b, F, lane);
+    const int a = fixed_anchor >= 0 ? fixed_anchor : pick_anchor(score_part, clip_part, b, F, S, lane);
     if (blockIdx.x % groups == 0 && threadIdx.x == 0) anchor_index[b] = a;
     if (j >= N) return;
     const T* row = x + (((size_t)b * F + a) * N + j) * (size_t)C;
@@ -161,16 +210,17 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 // norms, permutes every 16x64-byte block into MFMA operand order (lane = token + 16*chunk) and
 // stores it as one contiguous KiB: anchor_frag[b][tile][K-step][lane][8 bf16].
 __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restrict__ x,
-                                                        const double* __restrict__ frame_score,
+                                                        const double* __restrict__ score_part,
+                                                        const double* __restrict__ clip_part,
                                                         int32_t* __restrict__ anchor_index,
                                                         float* __restrict__ anchor_inv,
                                                         uint16_t* __restrict__ anchor_frag,
-                                                        int F, int N, int C, int fixed_anchor)
+                                                        int F, int N, int C, int S, int fixed_anchor)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int tiles = N / 16;
     const int b = blockIdx.x / tiles, tile = blockIdx.x % tiles;
-    const int a = fixed_anchor >= 0 ? fixed_anchor : pick_anchor(frame_score, b, F, lane);
+    const int a = fixed_anchor >= 0 ? fixed_anchor : pick_anchor(score_part, clip_part, b, F, S, lane);
     if (tile == 0 && threadIdx.x == 0) anchor_index[b] = a;
     const int KS = C / 32;
     const uint16_t* src = x + (((size_t)b * F + a) * N + 16 * tile + (lane >> 2)) * (size_t)C + (lane & 3) * 8;
@@ -241,11 +291,9 @@ hipError_t launch_frame_sums(const ttf_params& p, const void* x, const Workspace
 
 hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, hipStream_t s)
 {
-    dim3 g1((unsigned)((p.C + 255) / 256), (unsigned)p.B);
-    k_clip_sum<<<g1, 256, 0, s>>>(w.frame_sum, w.clip_sum, p.F, p.C);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    k_frame_score<<<(unsigned)(p.B * p.F), 256, 0, s>>>(w.frame_sum, w.clip_sum, w.frame_score, p.F, p.C);
+    const int S = (p.C + 255) / 256;
+    k_anchor_partials<<<(unsigned)((size_t)S * p.B), 512, 0, s>>>(w.frame_sum, w.score_part, w.clip_part,
+                                                                       p.F, p.C, S);
     return hipGetLastError();
 }
 
@@ -260,7 +308,8 @@ hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const Workspa
         using T = decltype(tag);
         constexpr int V = decltype(vtag)::value;
         k_anchor_norms<T, V><<<(unsigned)(p.B * groups), 256, 0, s>>>(
-            static_cast<const T*>(x), w.frame_score, anchor_index, w.anchor_inv, p.F, N, p.C, fixed, groups);
+            static_cast<const T*>(x), w.score_part, w.clip_part, anchor_index, w.anchor_inv, p.F, N, p.C,
+            (p.C + 255) / 256, fixed, groups);
         return hipGetLastError();
     });
 }
@@ -271,9 +320,9 @@ hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const 
     const int N = p.H * p.W;
     int fixed = -1;
     if (p.anchor_mode == TTF_ANCHOR_FIXED) fixed = p.anchor_index < 0 ? p.anchor_index + p.F : p.anchor_index;
-    k_anchor_prepare<<<(unsigned)(p.B * (N / 16)), 512, 0, s>>>(static_cast<const uint16_t*>(x), w.frame_score,
-                                                                anchor_index, w.anchor_inv, w.anchor_frag,
-                                                                p.F, N, p.C, fixed);
+    k_anchor_prepare<<<(unsigned)(p.B * (N / 16)), 512, 0, s>>>(static_cast<const uint16_t*>(x), w.score_part,
+                                                                w.clip_part, anchor_index, w.anchor_inv,
+                                                                w.anchor_frag, p.F, N, p.C, (p.C + 255) / 256, fixed);
     return hipGetLastError();
 }
 

@@ -56,7 +56,7 @@ ttf_status check_params(const ttf_params* p)
     if (p->B < 1 || p->F < 1 || p->H < 1 || p->W < 1 || p->C < 1) return TTF_ERR_INVALID_ARG;
     const long long tokens = (long long)p->B * p->F * p->H * p->W;
     if ((long long)p->H * p->W >= (1ll << 31) || tokens >= (1ll << 31)) return TTF_ERR_INVALID_ARG;
-    if (p->C > (1 << 22)) return TTF_ERR_INVALID_ARG;       // keeps every launch grid inside HIP limits
+    if (p->C > (1 << 21)) return TTF_ERR_INVALID_ARG;       // keeps every launch grid inside HIP limits
     if (p->r < 0) return TTF_ERR_INVALID_ARG;
     if (!std::isfinite(p->t)) return TTF_ERR_INVALID_ARG;
     if (p->anchor_mode != TTF_ANCHOR_AUTO && p->anchor_mode != TTF_ANCHOR_FIXED) return TTF_ERR_INVALID_ARG;

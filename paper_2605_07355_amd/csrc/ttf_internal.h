@@ -17,8 +17,8 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // Device scratch carved out of the caller's workspace.  All sections are 256-byte aligned.
 struct Workspace {
     float*    frame_sum;     // [B,F,C]  sum over the N tokens of every frame (anchor rule, inner sum)
-    double*   clip_sum;      // [B,C]    sum over all F*N tokens of a clip (anchor rule, outer sum)
-    double*   frame_score;   // [B,F]    cosine(frame mean, clip mean)
+    double*   score_part;    // [B,S,F,2] per 256-channel slice: <frame sum, clip sum> and |frame sum|^2
+    double*   clip_part;     // [B,S]    per slice: |clip sum|^2          (S = ceil(C/256))
     float*    anchor_inv;    // [B,N]    1/||x_{a,j}|| of every anchor token (0 for a zero token)
     uint16_t* anchor_frag;   // [B,N/16,C/32,64,8] bf16 anchor frame in MFMA fragment order (matrix-core path)
     uint64_t* keep_bits;     // [B,F,NW] bit i%64 of word i/64 set iff token i is kept (NW=ceil(N/64))
@@ -32,8 +32,9 @@ inline Workspace carve(const ttf_params& p, void* base)
     size_t off = 0;
     auto take = [&](size_t n) { size_t o = off; off = align_up(off + n, 256); return o; };
     const size_t o_fs = take(B * F * C * sizeof(float));
-    const size_t o_cs = take(B * C * sizeof(double));
-    const size_t o_sc = take(B * F * sizeof(double));
+    const size_t S = (C + 255) / 256;
+    const size_t o_sp = take(B * S * F * 2 * sizeof(double));
+    const size_t o_cp = take(B * S * sizeof(double));
     const size_t o_ai = take(B * N * sizeof(float));
     const size_t o_af = take(p.dtype == TTF_BF16 ? B * N * C * sizeof(uint16_t) : 0);
     const size_t o_kb = take(B * F * NW * sizeof(uint64_t));
@@ -41,8 +42,8 @@ inline Workspace carve(const ttf_params& p, void* base)
     char* c = static_cast<char*>(base);
     Workspace w;
     w.frame_sum   = reinterpret_cast<float*>(c + o_fs);
-    w.clip_sum    = reinterpret_cast<double*>(c + o_cs);
-    w.frame_score = reinterpret_cast<double*>(c + o_sc);
+    w.score_part  = reinterpret_cast<double*>(c + o_sp);
+    w.clip_part   = reinterpret_cast<double*>(c + o_cp);
     w.anchor_inv  = reinterpret_cast<float*>(c + o_ai);
     w.anchor_frag = reinterpret_cast<uint16_t*>(c + o_af);
     w.keep_bits   = reinterpret_cast<uint64_t*>(c + o_kb);
