@@ -79,7 +79,14 @@ __device__ __forceinline__ void copy_row(const char* __restrict__ src, char* __r
         uint4* d = reinterpret_cast<uint4*>(dst);
         const int n = (int)(row_bytes / 16);
         int q = lane;
-        for (; q + 192 < n; q += 256) {               // four 16-byte pieces in flight per lane
+        for (; q + 448 < n; q += 512) {                // eight 16-byte pieces in flight per lane
+            uint4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = load16_stream(s + q + 64 * u);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) store16_stream(d + q + 64 * u, v[u]);
+        }
+        for (; q + 192 < n; q += 256) {
             const uint4 v0 = load16_stream(s + q), v1 = load16_stream(s + q + 64),
                         v2 = load16_stream(s + q + 128), v3 = load16_stream(s + q + 192);
             store16_stream(d + q, v0); store16_stream(d + q + 64, v1);
@@ -99,7 +106,9 @@ __device__ __forceinline__ void copy_row(const char* __restrict__ src, char* __r
     }
 }
 
-// One block = one 64-token word of one frame; wave w copies the kept tokens among its 16.
+// One block = 16 tokens (a quarter of a 64-token keep word) of one frame; its kept tokens are dealt
+// to the four waves by rank.  Small blocks matter: a wave copies its rows one after the other, so
+// the fewer rows per wave, the more copies are in flight across the chip.
 template <int U>
 __global__ __launch_bounds__(256) void k_emit_rows(const char* __restrict__ x,
                                                    const uint64_t* __restrict__ keep_bits,
@@ -110,19 +119,24 @@ __global__ __launch_bounds__(256) void k_emit_rows(const char* __restrict__ x,
                                                    int F, int N, int W, int NW, size_t row_bytes, size_t cap)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int word = blockIdx.x % NW;
-    const size_t frame = blockIdx.x / NW;
+    const int quarter = blockIdx.x & 3;
+    const int word = (blockIdx.x >> 2) % NW;
+    const size_t frame = (blockIdx.x >> 2) / NW;
     const int k = (int)(frame % F);
     const uint64_t* kb = keep_bits + frame * (size_t)NW;
-    const uint64_t bits = kb[word];
+    const uint64_t wbits = kb[word];
+    const uint64_t bits = wbits & (0xffffull << (16 * quarter));
     if (bits == 0) return;
     int before = frame_base[frame];
     for (int q = 0; q < word; ++q) before += __popcll(kb[q]);
-    for (int q = 0; q < 16; ++q) {
-        const int bit = wave * 16 + q;
-        if (!((bits >> bit) & 1ull)) continue;
+    before += __popcll(wbits & ((1ull << (16 * quarter)) - 1ull));
+    uint64_t rem = bits;
+    for (int rank = 0; rem != 0; ++rank) {
+        const int bit = __ffsll((unsigned long long)rem) - 1;
+        rem &= rem - 1;
+        if ((rank & 3) != wave) continue;
         const int i = word * 64 + bit;
-        const size_t row = (size_t)before + __popcll(bits & ((1ull << bit) - 1ull));
+        const size_t row = (size_t)before + rank;
         copy_row<U>(x + (frame * (size_t)N + i) * row_bytes, tokens_out + row * row_bytes, row_bytes, lane);
         if (lane == 0) {
             pos_ids[row] = k;
@@ -152,7 +166,7 @@ hipError_t launch_emit_rows(const ttf_params& p, const void* x, const Workspace&
     const int N = p.H * p.W, NW = (N + 63) / 64;
     const size_t row_bytes = (size_t)p.C * (p.dtype == TTF_BF16 ? 2 : 4);
     const size_t cap = (size_t)p.B * p.F * N;
-    const unsigned grid = (unsigned)((size_t)p.B * p.F * NW);
+    const unsigned grid = (unsigned)((size_t)p.B * p.F * NW * 4);
     const char* xs = static_cast<const char*>(x);
     char* out = static_cast<char*>(tokens_out);
     if (row_bytes % 16 == 0)
