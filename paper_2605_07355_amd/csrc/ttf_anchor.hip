@@ -64,14 +64,14 @@ __global__ __launch_bounds__(256) void k_frame_sums(const T* __restrict__ x, flo
 }
 
 // Per clip and 256-channel slice, in fp64: the clip sum g = sum_k frame_sum[k] (k ascending inside
-// each of eight interleaved groups, groups added in order), then for every frame the slice's share
+// each of sixteen interleaved groups, groups added in order), then for every frame the slice's share
 // of <frame_sum_k, g> and |frame_sum_k|^2, and the slice's share of |g|^2.  The cosine of the
 // anchor rule is assembled from these shares by pick_anchor().
-__global__ __launch_bounds__(512) void k_anchor_partials(const float* __restrict__ frame_sum,
+__global__ __launch_bounds__(1024) void k_anchor_partials(const float* __restrict__ frame_sum,
                                                          double* __restrict__ score_part,
                                                          double* __restrict__ clip_part, int F, int C, int S)
 {
-    constexpr int NWV = 8, UN = 4;                      // waves per block, frames in flight per wave
+    constexpr int NWV = 16, UN = 8;                     // waves per block, frames in flight per wave
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int slice = blockIdx.x % S;
     const size_t b = blockIdx.x / S;
@@ -292,7 +292,7 @@ hipError_t launch_frame_sums(const ttf_params& p, const void* x, const Workspace
 hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, hipStream_t s)
 {
     const int S = (p.C + 255) / 256;
-    k_anchor_partials<<<(unsigned)((size_t)S * p.B), 512, 0, s>>>(w.frame_sum, w.score_part, w.clip_part,
+    k_anchor_partials<<<(unsigned)((size_t)S * p.B), 1024, 0, s>>>(w.frame_sum, w.score_part, w.clip_part,
                                                                        p.F, p.C, S);
     return hipGetLastError();
 }

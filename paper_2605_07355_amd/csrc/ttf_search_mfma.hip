@@ -52,7 +52,9 @@ struct Shape {
     // source frames per workgroup and anchor fragment prefetch distance: sized so accumulators
     // (4*NPS VGPRs per source tile), source fragments (4 per tile and K-step) and the anchor
     // ring (4*NA per K-step) fit the 256 VGPRs of a wave at two waves per SIMD
-    static constexpr int FR = NPS <= 3 ? 4 : (NPS <= 6 ? 2 : 1);
+    static constexpr int FR = NPS <= 3 ? 4 : 2;
+    // workgroups per CU the register budget is planned for (512 registers per lane and SIMD)
+    static constexpr int OCC = NPS <= 6 ? 2 : 1;
     static constexpr int PF = 1;
     // source tiles whose partial products go through LDS together (<= 48 KiB)
     static constexpr int RT = NPS <= 3 ? 4 : (NPS <= 6 ? 2 : 1);
@@ -83,7 +85,7 @@ __device__ __forceinline__ bf16x8 load_frag(const uint16_t* p)
 }
 
 template <int CT, int RAD, int KSW>
-__global__ __launch_bounds__(kWaves * 64, 2) void k_search_mfma(
+__global__ __launch_bounds__(kWaves * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ anchor_frag,
     const int32_t* __restrict__ anchor_index, const float* __restrict__ anchor_inv,
     int32_t* __restrict__ fuse_map, float* __restrict__ best_sim, int32_t* __restrict__ best_idx,
