@@ -65,11 +65,25 @@ __device__ __forceinline__ float wave_sum(float v)
         v += __shfl_xor(v, m, 64);
     return v;
 }
+// The lane each DPP control pairs a lane with inside its row of 16: i^1, i^2, mirror in the half
+// row (i <-> 7-i), mirror in the row (i <-> 15-i).  Four such steps leave every lane of a row with
+// the row's total; they run at VALU rate, unlike ds_bpermute.
+template <int DPP_CTRL>
+__device__ __forceinline__ double dpp_partner(double v)
+{
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)u, DPP_CTRL, 0xf, 0xf, false);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(u >> 32), DPP_CTRL, 0xf, 0xf, false);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
 __device__ __forceinline__ double wave_sum(double v)
 {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1)
-        v += __shfl_xor(v, m, 64);
+    v += dpp_partner<0xB1>(v);
+    v += dpp_partner<0x4E>(v);
+    v += dpp_partner<0x141>(v);
+    v += dpp_partner<0x140>(v);
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
     return v;
 }
 
