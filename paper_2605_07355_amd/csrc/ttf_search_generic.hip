@@ -5,8 +5,9 @@
 // cells [max(0,y-r), min(H-1,y+r)] x [max(0,x-r), min(W-1,x+r)], each counted once after the
 // duplicate masking the paper prescribes; walking those cells in ascending flat index and
 // keeping the first maximum is the row-major arg max over offsets.  One wavefront handles one
-// token: lanes stride over channels, products accumulate in fp32, a butterfly adds the lanes.
-// Candidates are taken in groups of G so the source row is read once per group.
+// token at a time (16 wavefronts per 64-token keep word): lanes stride over channels, products
+// accumulate in fp32, a butterfly adds the lanes.  Candidates are taken in groups of G so the
+// source row is read once per group.
 #include <type_traits>
 
 #include "ttf_device.h"
@@ -19,7 +20,7 @@ constexpr int G = 9;                 // candidates per pass over the channels (a
 constexpr float kNegInf = -__builtin_inff();
 
 template <typename T, int V>
-__global__ __launch_bounds__(256) void k_search_generic(
+__global__ __launch_bounds__(1024) void k_search_generic(
     const T* __restrict__ x, const int32_t* __restrict__ anchor_index, const float* __restrict__ anchor_inv,
     int32_t* __restrict__ fuse_map, float* __restrict__ best_sim, int32_t* __restrict__ best_idx,
     uint64_t* __restrict__ keep_bits, int F, int H, int W, int C, int r, float t, int NW)
@@ -37,8 +38,8 @@ __global__ __launch_bounds__(256) void k_search_generic(
     const T* anchor = x + ((size_t)b * F + a) * (size_t)N * C;
     const float* ainv = anchor_inv + (size_t)b * N;
 
-    for (int q = 0; q < 16; ++q) {
-        const int i = word * 64 + wave * 16 + q;      // wave-uniform
+    for (int q = 0; q < 4; ++q) {
+        const int i = word * 64 + wave * 4 + q;       // wave-uniform
         if (i >= N) break;
         const size_t o = frame * (size_t)N + i;
         if (k == a) {                                 // anchor tokens are always retained
@@ -120,7 +121,7 @@ hipError_t launch_window_search_generic(const ttf_params& p, const void* x, cons
     auto go = [&](auto tag, auto vtag) {
         using T = decltype(tag);
         constexpr int V = decltype(vtag)::value;
-        k_search_generic<T, V><<<grid, 256, 0, s>>>(static_cast<const T*>(x), anchor_index, w.anchor_inv,
+        k_search_generic<T, V><<<grid, 1024, 0, s>>>(static_cast<const T*>(x), anchor_index, w.anchor_inv,
                                                     fuse_map, best_sim, best_idx, w.keep_bits,
                                                     p.F, p.H, p.W, p.C, p.r, p.t, NW);
         return hipGetLastError();

@@ -90,6 +90,7 @@ SHAPES = [
     (2, 5, 16, 16, 128, "bf16", 2),      # matrix-core path, one K-step per wave, 5x5 window
     (1, 6, 16, 16, 384, "bf16", 0),      # matrix-core path, 1x1 window, last frame group partly empty
     (1, 2, 16, 16, 128, "bf16", 1),      # one source frame only
+    (2, 1, 16, 16, 128, "bf16", 1),      # no source frame at all on the matrix-core path
     (3, 3, 4, 16, 512, "bf16", 1),       # N = 64: a single keep word per frame
     (2, 7, 8, 32, 128, "bf16", 1),       # 32-wide grid on the matrix-core path
     (1, 4, 32, 32, 256, "bf16", 2),      # 32-wide grid, 5x5 window
@@ -189,9 +190,20 @@ def test_two_calls_are_bit_identical():
     assert torch.equal(a.buffers.best_sim.view(torch.int32), b.buffers.best_sim.view(torch.int32))
 
 
-def test_optional_outputs_and_host_counts(oracle):
+@pytest.mark.parametrize("t", [-1.0, 1.0])
+@pytest.mark.parametrize("C", [96, 128])
+def test_threshold_extremes(oracle, t, C):
+    """t = -1 fuses every source token, t = 1 fuses none (general and matrix-core kernels)."""
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=2, F=5, C=C)
+    res, _ = _direct(make_clip_batch(cfg, seed=14).x, 1, t, "auto", oracle)
+    want = cfg.N if t < 0 else cfg.F * cfg.N
+    assert (res.kept_count == want).all()
+
+
+@pytest.mark.parametrize("H,W,C", [(8, 8, 64), (16, 16, 256)])
+def test_optional_outputs_and_host_counts(oracle, H, W, C):
     import paper_2605_07355_amd as ttf
-    cfg = CONFIGS["qwen3vl_2b"].scaled(B=3, F=4, H=8, W=8, C=64)
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=3, F=4, H=H, W=W, C=C)
     batch, res = _prepared(cfg, seed=13)
     x = to_device(batch.x)
     buf = ttf.TTFBuffers.allocate(cfg.B, cfg.F, cfg.H, cfg.W, cfg.C, x.dtype, x.device, want_sim=False,
