@@ -385,3 +385,39 @@ def test_bf16_input_is_read_exactly(oracle):
     # rounding is to nearest even: 1 + 2^-8 is a tie between 1.0 and 1 + 2^-7 and goes to 1.0
     assert f32_to_bf16_bits(np.array([1 + 2.0 ** -8], np.float32))[0] == 0x3F80
     assert f32_to_bf16_bits(np.array([1 + 3 * 2.0 ** -8], np.float32))[0] == 0x3F82
+
+
+def test_match_tokens_against_bruteforce(oracle):
+    """The per-token entry point, pinned directly against the NumPy formulation (not via compress)."""
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=2, F=4, H=5, W=6, C=24, dtype="bf16")
+    x = make_clip_batch(cfg, seed=23).x
+    x64 = _as_f64(x).reshape(cfg.B, cfg.F, cfg.N, cfg.C)
+    anchors = [1, 3]
+    refs = [ttf_clip(x64[b], cfg.H, cfg.W, 2, 0.7, anchor=anchors[b]) for b in range(cfg.B)]
+    tok = np.array([(b, k, i) for b in range(cfg.B) for k in range(cfg.F) for i in range(0, cfg.N, 3)])
+    best, second, idx = oracle.match_tokens(x, 2, anchors, tok)
+    for (b, k, i), s, j in zip(tok, best, idx):
+        assert j == refs[b]["best_idx"][k, i]
+        assert s == pytest.approx(refs[b]["best_sim"][k, i], abs=1e-12)
+    src = tok[:, 1] != np.array(anchors)[tok[:, 0]]
+    assert (second[src] <= best[src]).all() and np.isneginf(second[~src]).all()
+
+
+def test_margin_helper_moves_every_decision_off_the_edge(oracle):
+    from oracle import margins
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=2, F=6, H=8, W=8, C=64)
+    batch = make_clip_batch(cfg, seed=24)
+    before = oracle.compress(batch.x, 1, 0.7, want_tokens=False)
+    ts = (0.7, 0.6)
+    n_bad = len(margins.violators(before, ts, 5e-3, 1e-3))
+    assert n_bad > 0                                   # wide margins: something has to move
+    res = margins.enforce_margins(batch, 1, ts, sim_margin=5e-3, top2_margin=1e-3, want_tokens=False)
+    assert len(margins.violators(res, ts, 5e-3, 1e-3)) == 0
+    again = oracle.compress(batch.x, 1, 0.7, want_tokens=False)       # the batch was edited in place
+    np.testing.assert_array_equal(again.fuse_map, res.fuse_map)
+    src = np.ones_like(res.best_sim, bool)
+    for b in range(cfg.B):
+        src[b, res.anchor_index[b]] = False
+    for t in ts:
+        assert (np.abs(res.best_sim[src] - np.float32(t)) >= 5e-3).all()
+    assert margins.anchor_gap(res) >= 1e-4
