@@ -18,12 +18,14 @@
 //  * Anchor tokens are re-used by every source frame, so their inverse norms and a copy of the
 //    anchor frame in fragment order (1 KiB per tile and K-step, lane-major) are prepared once
 //    per clip (ttf_anchor.hip); the search streams those fragments from L2 fully coalesced.
-//  * One workgroup (4 wavefronts) owns the same 32 grid cells (two source tiles) in FR
+//  * One workgroup owns the same 32 grid cells (two source tiles) in FR
 //    consecutive source frames, so every anchor fragment fetched from L2 feeds FR frames.
-//  * The channel axis is split across the 4 wavefronts; partial 16x16 products are added through
-//    LDS in wave order (fixed order: reproducible), then one wave per source tile forms the
-//    cosines, masks the band, takes the arg max (lowest anchor index on ties), applies the
-//    threshold and writes s^, dst, the fuse map and 16 keep bits.
+//  * Large problems: one wavefront per workgroup walks the whole channel axis, so its 16x16
+//    products are final and the epilogue is wave-local.  Small problems: the channel axis is split
+//    across 4 wavefronts and the partial products are added through LDS in wave order (fixed
+//    order: reproducible).  Either way one wave per source tile forms the cosines, masks the band,
+//    takes the arg max (lowest anchor index on ties), applies the threshold and writes s^, dst,
+//    the fuse map and 16 keep bits.
 //  * Source squared norms: v_dot2 on the loaded fragments (one VGPR per tile), reduced with the
 //    products.
 #include "ttf_device.h"
@@ -36,8 +38,8 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-constexpr int kWaves = 4;                 // wavefronts per workgroup = channel slices
 constexpr float kNegInf = -__builtin_inff();
+constexpr size_t kSimds = 256 * 4;             // SIMDs of the chip: wave slots per unit of occupancy
 
 // Geometry of one workgroup's problem.  CT = W/16 column tiles per grid row.
 template <int CT, int RAD>
@@ -53,7 +55,7 @@ struct Shape {
     // (4*NPS VGPRs per source tile), source fragments (4 per tile and K-step) and the anchor
     // ring (4*NA per K-step) fit the 256 VGPRs of a wave at two waves per SIMD
     static constexpr int FR = NPS <= 3 ? 4 : 2;
-    // workgroups per CU the register budget is planned for (512 registers per lane and SIMD)
+    // waves per SIMD the register budget is planned for (512 registers per lane and SIMD)
     static constexpr int OCC = NPS <= 6 ? 2 : 1;
     static constexpr int PF = 1;
     // source tiles whose partial products go through LDS together (<= 48 KiB)
@@ -84,8 +86,82 @@ __device__ __forceinline__ bf16x8 load_frag(const uint16_t* p)
     return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p));
 }
 
-template <int CT, int RAD, int KSW>
-__global__ __launch_bounds__(kWaves * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
+// Final step for one source tile (16 tokens of one frame): v[q] are the complete 16x16 products
+// with the NPS anchor tiles paired with it (MFMA result layout: lane = anchor column n + 16*g,
+// element j = source token 4g+j), nn[j] the squared norms of tokens 4g+j, ai_tile[a] this lane's
+// anchor inverse norm in anchor tile a.  Forms the cosines,
+// masks the band |dx| <= RAD and the rows outside the grid, takes the arg max (lowest anchor
+// index on ties), applies the threshold and writes s^, dst, the fuse map and the tile's 16 keep
+// bits.  Straight-line code: no divergent branches.
+template <int CT, int RAD>
+__device__ __forceinline__ void finish_tile(const f32x4* v, const float* nn, int s, bool live, int si, int a, int b,
+                                            int F, int H, int i0, float t, const float* ai_tile,
+                                            int32_t* __restrict__ fuse_map, float* __restrict__ best_sim,
+                                            int32_t* __restrict__ best_idx, uint16_t* __restrict__ keep16, int lane)
+{
+    using S = Shape<CT, RAD>;
+    constexpr int W = S::W, NPS = S::NPS;
+    const int N = H * W;
+    const int m = lane & 15, g = lane >> 4;
+    const int u = s % 2;                                     // tile within the frame
+    const int y0 = i0 / W, ylo = y0 - RAD;
+    float sinv[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) sinv[j] = nn[j] > 0.f ? __builtin_amdgcn_rsqf(nn[j]) : 0.f;
+    float best[4] = {kNegInf, kNegInf, kNegInf, kNegInf};
+    int arg[4] = {kNoArg, kNoArg, kNoArg, kNoArg};
+    const int ysrc = y0 + (CT == 1 ? u : 0);
+    const int xsrc0 = CT == 1 ? 0 : 16 * u;
+#pragma unroll
+    for (int q = 0; q < NPS; ++q) {
+        // anchor tile of pair q: CT==1: row ysrc-RAD+q; CT==2: row ylo + q/2, column q%2
+        const int yy = CT == 1 ? ysrc - RAD + q : ylo + q / 2;
+        const int xa_col = (CT == 1 ? 0 : 16 * (q % 2)) + m;      // this lane's anchor column
+        const bool row_ok = (yy >= 0) & (yy < H);
+        const int ja = min(max(yy, 0), H - 1) * W + xa_col;
+        const float ai = ai_tile[S::pair_tile(u, q)];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int dx = xa_col - (xsrc0 + 4 * g + j);          // anchor column - source column
+            const bool in_band = row_ok & (dx >= -RAD) & (dx <= RAD);
+            const float sim = in_band ? v[q][j] * sinv[j] * ai : kNegInf;
+            const bool take = sim > best[j];                      // ascending ja per lane: first maximum
+            best[j] = take ? sim : best[j];
+            arg[j] = take ? ja : arg[j];
+        }
+    }
+    // arg max across the 16 anchor columns held by the 16 lanes of a row; lowest index on ties
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        row_argmax_step<0xB1>(best[j], arg[j]);       // lanes i <-> i^1
+        row_argmax_step<0x4E>(best[j], arg[j]);       // lanes i <-> i^2
+        row_argmax_step<0x141>(best[j], arg[j]);      // mirror inside each half row (8 lanes)
+        row_argmax_step<0x140>(best[j], arg[j]);      // mirror inside the row (16 lanes)
+        arg[j] = arg[j] == kNoArg ? -1 : arg[j];
+    }
+    const int k = si + (si >= a ? 1 : 0);
+    const size_t o0 = ((size_t)b * F + k) * N + i0 + 16 * u;
+    unsigned keep = 0;
+    if (m == 0) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const size_t o = o0 + 4 * g + j;
+            const bool fused = best[j] > t;                   // keep = 1[s^ <= t]
+            if (live) {
+                fuse_map[o] = fused ? arg[j] : -1;
+                if (best_sim) best_sim[o] = best[j];
+                if (best_idx) best_idx[o] = arg[j];
+            }
+            if (!fused) keep |= 1u << (4 * g + j);
+        }
+    }
+    keep |= __shfl_xor(keep, 16, 64);
+    keep |= __shfl_xor(keep, 32, 64);
+    if (lane == 0 && live) keep16[o0 / 16] = (uint16_t)keep;
+}
+
+template <int CT, int RAD, int KSW, int NW>
+__global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ anchor_frag,
     const int32_t* __restrict__ anchor_index, const float* __restrict__ anchor_inv,
     int32_t* __restrict__ fuse_map, float* __restrict__ best_sim, int32_t* __restrict__ best_idx,
@@ -118,7 +194,7 @@ __global__ __launch_bounds__(kWaves * 64, (Shape<CT, RAD>::OCC)) void k_search_m
 
     const int y0 = i0 / W;                                   // first (or only) source row
     const int ylo = y0 - RAD;
-    const int slice = C / kWaves;                            // channels per wave
+    const int slice = C / NW;                                // channels per wave
     const int KS = C / 32;                                   // K-steps per token
     const int nsrc = F - 1;                                  // source frames of the clip (>= 1 here)
 
@@ -133,11 +209,13 @@ __global__ __launch_bounds__(kWaves * 64, (Shape<CT, RAD>::OCC)) void k_search_m
     }
     const int bperm = (4 * m + g) * 4;                       // operand lane (token m, chunk g) <- load lane 4m+g
     const uint16_t* ap[NA];
+    float ai_tile[NA];
 #pragma unroll
     for (int q = 0; q < NA; ++q) {
         const int yy = min(max(ylo + S::tile_row(q), 0), H - 1);      // rows outside the grid: clamped, masked later
         const int tile = yy * CT + S::tile_col(q);
         ap[q] = anchor_frag + (((size_t)b * (N / 16) + tile) * KS + wave * (slice / 32)) * 512 + lane * 8;
+        ai_tile[q] = anchor_inv[(size_t)b * N + 16 * tile + m];       // requested now, used in the epilogue
     }
 
     f32x4 acc[NS][NPS];
@@ -203,96 +281,57 @@ __global__ __launch_bounds__(kWaves * 64, (Shape<CT, RAD>::OCC)) void k_search_m
         nv[s] += __shfl_xor(nv[s], 1, 64);
         nv[s] += __shfl_xor(nv[s], 2, 64);
     }
-
-    // ---- add the channel slices through LDS (wave order), RT source tiles per round ----
-    __shared__ f32x4 red[kWaves][RT][NPS][64];
-    __shared__ float rnv[kWaves][RT][64];
-    const float* ainv = anchor_inv + (size_t)b * N;
-
+    if constexpr (NW == 1) {
+        // one wave owns the whole channel axis: its sums are final, the epilogue needs no LDS
 #pragma unroll
-    for (int round = 0; round < NS / RT; ++round) {
+        for (int s = 0; s < NS; ++s) {
+            float nn[4];
 #pragma unroll
-        for (int sl = 0; sl < RT; ++sl) {
-            const int s = round * RT + sl;
-            rnv[wave][sl][lane] = nv[s];
-#pragma unroll
-            for (int q = 0; q < NPS; ++q) red[wave][sl][q][lane] = acc[s][q];
+            for (int j = 0; j < 4; ++j) nn[j] = __shfl(nv[s], 4 * (4 * g + j), 64);
+            finish_tile<CT, RAD>(acc[s], nn, s, grp * S::FR + s / 2 < nsrc, min(grp * S::FR + s / 2, nsrc - 1), a, b,
+                                 F, H, i0, t, ai_tile, fuse_map, best_sim, best_idx, keep16, lane);
         }
-        __syncthreads();
-        if (wave < RT) {
-            const int sl = wave;
-            const int s = round * RT + sl;                   // wave-uniform
-            const int f = s / 2, u = s % 2;
-            const bool live = grp * FR + f < nsrc;            // slots past the last source frame are repeats
-            // (straight-line code from here on: one wave runs this while the others wait, so every
-            // divergent branch would be paid in full)
-            float sinv[4];
+    } else {
+        // ---- add the channel slices through LDS (wave order), RT source tiles per round ----
+        __shared__ f32x4 red[NW][RT][NPS][64];
+        __shared__ float rnv[NW][RT][64];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                float nn = rnv[0][sl][4 * (4 * g + j)];
+        for (int round = 0; round < NS / RT; ++round) {
 #pragma unroll
-                for (int w = 1; w < kWaves; ++w) nn += rnv[w][sl][4 * (4 * g + j)];
-                sinv[j] = nn > 0.f ? __builtin_amdgcn_rsqf(nn) : 0.f;
+            for (int sl = 0; sl < RT; ++sl) {
+                const int s = round * RT + sl;
+                rnv[wave][sl][lane] = nv[s];
+#pragma unroll
+                for (int q = 0; q < NPS; ++q) red[wave][sl][q][lane] = acc[s][q];
             }
-            float best[4] = {kNegInf, kNegInf, kNegInf, kNegInf};
-            int arg[4] = {kNoArg, kNoArg, kNoArg, kNoArg};
-            const int ysrc = y0 + (CT == 1 ? u : 0);
-            const int xsrc0 = CT == 1 ? 0 : 16 * u;
-#pragma unroll
-            for (int q = 0; q < NPS; ++q) {
-                f32x4 v = red[0][sl][q][lane];
-#pragma unroll
-                for (int w = 1; w < kWaves; ++w) {
-                    const f32x4 p = red[w][sl][q][lane];
-                    v[0] += p[0]; v[1] += p[1]; v[2] += p[2]; v[3] += p[3];
-                }
-                // anchor tile of pair q: CT==1: row ysrc-RAD+q; CT==2: row ylo + q/2, column q%2
-                const int yy = CT == 1 ? ysrc - RAD + q : ylo + q / 2;
-                const int xa_col = (CT == 1 ? 0 : 16 * (q % 2)) + m;      // this lane's anchor column
-                const bool row_ok = (yy >= 0) & (yy < H);
-                const int ja = min(max(yy, 0), H - 1) * W + xa_col;
-                const float ai = ainv[ja];
+            __syncthreads();
+            if (wave < RT) {
+                // (straight-line code from here on: one wave runs this while the others wait, so
+                // every divergent branch would be paid in full)
+                const int sl = wave;
+                const int s = round * RT + sl;                   // wave-uniform
+                float nn[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const int dx = xa_col - (xsrc0 + 4 * g + j);          // anchor column - source column
-                    const bool in_band = row_ok & (dx >= -RAD) & (dx <= RAD);
-                    const float sim = in_band ? v[j] * sinv[j] * ai : kNegInf;
-                    const bool take = sim > best[j];                      // ascending ja per lane: first maximum
-                    best[j] = take ? sim : best[j];
-                    arg[j] = take ? ja : arg[j];
+                    nn[j] = rnv[0][sl][4 * (4 * g + j)];
+#pragma unroll
+                    for (int w = 1; w < NW; ++w) nn[j] += rnv[w][sl][4 * (4 * g + j)];
                 }
-            }
-            // arg max across the 16 anchor columns held by the 16 lanes of a row; lowest index on ties
+                f32x4 v[NPS];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                row_argmax_step<0xB1>(best[j], arg[j]);       // lanes i <-> i^1
-                row_argmax_step<0x4E>(best[j], arg[j]);       // lanes i <-> i^2
-                row_argmax_step<0x141>(best[j], arg[j]);      // mirror inside each half row (8 lanes)
-                row_argmax_step<0x140>(best[j], arg[j]);      // mirror inside the row (16 lanes)
-                arg[j] = arg[j] == kNoArg ? -1 : arg[j];
-            }
-            const int si = min(grp * FR + f, nsrc - 1);
-            const int k = si + (si >= a ? 1 : 0);
-            const size_t o0 = ((size_t)b * F + k) * N + i0 + 16 * u;
-            unsigned keep = 0;
-            if (m == 0) {
+                for (int q = 0; q < NPS; ++q) {
+                    v[q] = red[0][sl][q][lane];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const size_t o = o0 + 4 * g + j;
-                    const bool fused = best[j] > t;                   // keep = 1[s^ <= t]
-                    if (live) {
-                        fuse_map[o] = fused ? arg[j] : -1;
-                        if (best_sim) best_sim[o] = best[j];
-                        if (best_idx) best_idx[o] = arg[j];
+                    for (int w = 1; w < NW; ++w) {
+                        const f32x4 p = red[w][sl][q][lane];
+                        v[q][0] += p[0]; v[q][1] += p[1]; v[q][2] += p[2]; v[q][3] += p[3];
                     }
-                    if (!fused) keep |= 1u << (4 * g + j);
                 }
+                finish_tile<CT, RAD>(v, nn, s, grp * S::FR + s / 2 < nsrc, min(grp * S::FR + s / 2, nsrc - 1), a, b,
+                                     F, H, i0, t, ai_tile, fuse_map, best_sim, best_idx, keep16, lane);
             }
-            keep |= __shfl_xor(keep, 16, 64);
-            keep |= __shfl_xor(keep, 32, 64);
-            if (lane == 0 && live) keep16[o0 / 16] = (uint16_t)keep;
+            __syncthreads();
         }
-        __syncthreads();
     }
 }
 
@@ -303,18 +342,23 @@ hipError_t launch_shape(const ttf_params& p, const void* x, const Workspace& w, 
     using S = Shape<CT, RAD>;
     const int N = p.H * p.W;
     const int groups = (p.F - 1 + S::FR - 1) / S::FR;        // groups of source frames per clip
-    const unsigned grid = (unsigned)((size_t)p.B * (groups + 1) * (N / 32));
-    const int ksw_total = p.C / (kWaves * 32);               // K-steps per wave
+    const size_t blocks = (size_t)p.B * (groups + 1) * (N / 32);
+    const unsigned grid = (unsigned)blocks;
+    const int ks_total = p.C / 32;                           // K-steps per token
     const uint16_t* xs = static_cast<const uint16_t*>(x);
     uint16_t* keep16 = reinterpret_cast<uint16_t*>(w.keep_bits);
-    if (ksw_total % 2 == 0)
-        k_search_mfma<CT, RAD, 2><<<grid, kWaves * 64, 0, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv,
-                                                               fuse_map, best_sim, best_idx, keep16, p.F, p.H,
-                                                               p.C, p.t, ksw_total / 2, groups);
-    else
-        k_search_mfma<CT, RAD, 1><<<grid, kWaves * 64, 0, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv,
-                                                               fuse_map, best_sim, best_idx, keep16, p.F, p.H,
-                                                               p.C, p.t, ksw_total, groups);
+#define TTF_LAUNCH(KSW, NW)                                                                                  \
+    k_search_mfma<CT, RAD, KSW, NW><<<grid, NW * 64, 0, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv,  \
+                                                             fuse_map, best_sim, best_idx, keep16, p.F, p.H, \
+                                                             p.C, p.t, ks_total / (NW * KSW), groups)
+    // With several rounds of workgroups per wave slot, one wave per workgroup walks the whole
+    // channel axis (no cross-wave sum, no LDS).  With fewer, such long-running single waves
+    // would leave SIMDs unevenly loaded (measured: 0.24 ms against 0.20 ms on 1152 workgroups),
+    // so the channels are split over four waves instead.
+    if (blocks >= 3 * kSimds * S::OCC && ks_total % 2 == 0) TTF_LAUNCH(2, 1);
+    else if (ks_total % 8 == 0) TTF_LAUNCH(2, 4);
+    else TTF_LAUNCH(1, 4);
+#undef TTF_LAUNCH
     return hipGetLastError();
 }
 
