@@ -206,7 +206,8 @@ __global__ __launch_bounds__(256) void k_anchor_norms(const T* __restrict__ x,
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 // Matrix-core path.  One workgroup (8 waves) per anchor tile of 16 tokens: picks the anchor,
-// reads the tile once with coalesced loads (lane l: chunk l%4 of token l/4), accumulates squared
+// writes the anchor-frame rows of the per-token outputs (never fused, all keep bits set), reads
+// the tile once with coalesced loads (lane l: chunk l%4 of token l/4), accumulates squared
 // norms, permutes every 16x64-byte block into MFMA operand order (lane = token + 16*chunk) and
 // stores it as one contiguous KiB: anchor_frag[b][tile][K-step][lane][8 bf16].
 __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restrict__ x,
@@ -215,6 +216,8 @@ __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restri
                                                         int32_t* __restrict__ anchor_index,
                                                         float* __restrict__ anchor_inv,
                                                         uint16_t* __restrict__ anchor_frag,
+                                                        int32_t* __restrict__ fuse_map, float* __restrict__ best_sim,
+                                                        int32_t* __restrict__ best_idx, uint16_t* __restrict__ keep16,
                                                         int F, int N, int C, int S, int fixed_anchor)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -222,6 +225,13 @@ __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restri
     const int b = blockIdx.x / tiles, tile = blockIdx.x % tiles;
     const int a = fixed_anchor >= 0 ? fixed_anchor : pick_anchor(score_part, clip_part, b, F, S, lane);
     if (tile == 0 && threadIdx.x == 0) anchor_index[b] = a;
+    if (threadIdx.x < 16) {                                  // anchor tokens are always retained
+        const size_t o = ((size_t)b * F + a) * N + 16 * tile + threadIdx.x;
+        fuse_map[o] = -1;
+        if (best_sim) best_sim[o] = 1.0f;
+        if (best_idx) best_idx[o] = 16 * tile + (int)threadIdx.x;
+        if (threadIdx.x == 0) keep16[o / 16] = 0xffffu;
+    }
     const int KS = C / 32;
     const uint16_t* src = x + (((size_t)b * F + a) * N + 16 * tile + (lane >> 2)) * (size_t)C + (lane & 3) * 8;
     uint16_t* dst = anchor_frag + ((size_t)b * tiles + tile) * (size_t)KS * 512 + lane * 8;
@@ -315,14 +325,17 @@ hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const Workspa
 }
 
 hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const Workspace& w,
-                                      int32_t* anchor_index, hipStream_t s)
+                                      int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
+                                      int32_t* best_idx, hipStream_t s)
 {
     const int N = p.H * p.W;
     int fixed = -1;
     if (p.anchor_mode == TTF_ANCHOR_FIXED) fixed = p.anchor_index < 0 ? p.anchor_index + p.F : p.anchor_index;
     k_anchor_prepare<<<(unsigned)(p.B * (N / 16)), 512, 0, s>>>(static_cast<const uint16_t*>(x), w.score_part,
                                                                 w.clip_part, anchor_index, w.anchor_inv,
-                                                                w.anchor_frag, p.F, N, p.C, (p.C + 255) / 256, fixed);
+                                                                w.anchor_frag, fuse_map, best_sim, best_idx,
+                                                                reinterpret_cast<uint16_t*>(w.keep_bits),
+                                                                p.F, N, p.C, (p.C + 255) / 256, fixed);
     return hipGetLastError();
 }
 

@@ -121,7 +121,9 @@ ttf_status ttf_compress(const ttf_params* params, const void* features, void* wo
     mark();
     if (p.anchor_mode == TTF_ANCHOR_AUTO) TTF_STEP(launch_anchor_scores(p, w, s));
     mark();
-    if (use_mfma_path(p)) TTF_STEP(launch_anchor_prepare_mfma(p, features, w, out->anchor_index, s));
+    if (use_mfma_path(p))
+        TTF_STEP(launch_anchor_prepare_mfma(p, features, w, out->anchor_index, out->fuse_map, out->best_sim,
+                                            out->best_idx, s));
     else TTF_STEP(launch_anchor_norms(p, features, w, out->anchor_index, s));
     mark();
     TTF_STEP(launch_window_search(p, features, w, out->anchor_index, out->fuse_map, out->best_sim,

@@ -57,9 +57,11 @@ hipError_t launch_frame_sums(const ttf_params& p, const void* x, const Workspace
 hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, hipStream_t s);
 hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const Workspace& w,
                                int32_t* anchor_index, hipStream_t s);
-// Matrix-core path: anchor choice, inverse norms and the anchor frame re-laid in fragment order.
+// Matrix-core path: anchor choice, inverse norms, the anchor frame re-laid in fragment order, and
+// the anchor-frame rows of fuse_map / best_sim / best_idx / keep bits.
 hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const Workspace& w,
-                                      int32_t* anchor_index, hipStream_t s);
+                                      int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
+                                      int32_t* best_idx, hipStream_t s);
 bool mfma_search_supported(const ttf_params& p);
 hipError_t launch_window_search(const ttf_params& p, const void* x, const Workspace& w,
                                 const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,

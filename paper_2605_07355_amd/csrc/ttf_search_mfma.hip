@@ -176,21 +176,10 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
     const int m = lane & 15, g = lane >> 4;
     const int tpf = N / 32;                                  // workgroups per frame group
     const int tp = blockIdx.x % tpf;
-    const int grp = (blockIdx.x / tpf) % (groups + 1);
-    const int b = blockIdx.x / tpf / (groups + 1);
+    const int grp = (blockIdx.x / tpf) % groups;
+    const int b = blockIdx.x / tpf / groups;
     const int a = anchor_index[b];
     const int i0 = tp * 32;                                  // first grid cell of this workgroup
-
-    if (grp == groups) {                                     // anchor tokens are always retained
-        const size_t o0 = ((size_t)b * F + a) * N + i0;
-        if (threadIdx.x < 32) {
-            fuse_map[o0 + threadIdx.x] = -1;
-            if (best_sim) best_sim[o0 + threadIdx.x] = 1.0f;
-            if (best_idx) best_idx[o0 + threadIdx.x] = i0 + threadIdx.x;
-        }
-        if (threadIdx.x < 2) keep16[o0 / 16 + threadIdx.x] = 0xffffu;
-        return;
-    }
 
     const int y0 = i0 / W;                                   // first (or only) source row
     const int ylo = y0 - RAD;
@@ -340,12 +329,13 @@ hipError_t launch_shape(const ttf_params& p, const void* x, const Workspace& w, 
                         int32_t* fuse_map, float* best_sim, int32_t* best_idx, hipStream_t s)
 {
     using S = Shape<CT, RAD>;
+    if (p.F < 2) return hipSuccess;                          // no source frame: the anchor rows are all there is
+    const uint16_t* xs = static_cast<const uint16_t*>(x);
     const int N = p.H * p.W;
     const int groups = (p.F - 1 + S::FR - 1) / S::FR;        // groups of source frames per clip
-    const size_t blocks = (size_t)p.B * (groups + 1) * (N / 32);
+    const size_t blocks = (size_t)p.B * groups * (N / 32);
     const unsigned grid = (unsigned)blocks;
     const int ks_total = p.C / 32;                           // K-steps per token
-    const uint16_t* xs = static_cast<const uint16_t*>(x);
     uint16_t* keep16 = reinterpret_cast<uint16_t*>(w.keep_bits);
 #define TTF_LAUNCH(KSW, NW)                                                                                  \
     k_search_mfma<CT, RAD, KSW, NW><<<grid, NW * 64, 0, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv,  \
@@ -353,8 +343,8 @@ hipError_t launch_shape(const ttf_params& p, const void* x, const Workspace& w, 
                                                              p.C, p.t, ks_total / (NW * KSW), groups)
     // With several rounds of workgroups per wave slot, one wave per workgroup walks the whole
     // channel axis (no cross-wave sum, no LDS).  With fewer, such long-running single waves
-    // would leave SIMDs unevenly loaded (measured: 0.24 ms against 0.20 ms on 1152 workgroups),
-    // so the channels are split over four waves instead.
+    // leave SIMDs unevenly loaded (measured: 0.24 ms against 0.20 ms on 1024 workgroups), so the
+    // channels are split over four waves instead.
     if (blocks >= 3 * kSimds * S::OCC && ks_total % 2 == 0) TTF_LAUNCH(2, 1);
     else if (ks_total % 8 == 0) TTF_LAUNCH(2, 4);
     else TTF_LAUNCH(1, 4);

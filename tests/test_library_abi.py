@@ -76,3 +76,33 @@ def test_generator_is_deterministic():
     c = make_clip_batch(cfg.scaled(B=1), seed=5)
     np.testing.assert_array_equal(a.x[0], c.x[0])          # clip b depends on (seed, b) only
     assert not np.array_equal(a.x, make_clip_batch(cfg, seed=6).x)
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/ttf.h must be usable from C: compile a translation unit that only includes it."""
+    import subprocess
+    src = tmp_path / "use_ttf.c"
+    src.write_text('#include "ttf.h"\n'
+                   'int probe(void) { ttf_params p; ttf_outputs o; (void)p; (void)o;\n'
+                   '  return (int)sizeof(ttf_params) + (int)sizeof(ttf_outputs) + TTF_NUM_STAGES; }\n')
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-c", str(src),
+                    "-I", os.path.join(ROOT, "include"), "-o", str(tmp_path / "use_ttf.o")], check=True)
+
+
+def test_struct_layout_matches_binding():
+    """The ctypes mirrors must have the sizes the C compiler gives the header's structs."""
+    import subprocess, tempfile
+    from paper_2605_07355_amd import binding
+    with tempfile.TemporaryDirectory() as d:
+        src = os.path.join(d, "sz.c")
+        with open(src, "w") as fh:
+            fh.write('#include <stdio.h>\n#include <stddef.h>\n#include "ttf.h"\n'
+                     'int main(void) { printf("%zu %zu %zu %zu\\n", sizeof(ttf_params), sizeof(ttf_outputs),\n'
+                     '  offsetof(ttf_params, t), offsetof(ttf_outputs, host_counts)); return 0; }\n')
+        exe = os.path.join(d, "sz")
+        subprocess.run(["gcc", "-std=c99", src, "-I", os.path.join(ROOT, "include"), "-o", exe], check=True)
+        out = subprocess.run([exe], check=True, capture_output=True, text=True).stdout.split()
+    assert int(out[0]) == ctypes.sizeof(binding._Params)
+    assert int(out[1]) == ctypes.sizeof(binding._Outputs)
+    assert int(out[2]) == binding._Params.t.offset
+    assert int(out[3]) == binding._Outputs.host_counts.offset
