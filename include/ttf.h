@@ -115,6 +115,67 @@ ttf_status ttf_compress(const ttf_params* params, const void* features,
                         void* workspace, size_t workspace_bytes,
                         const ttf_outputs* out, void* hip_stream);
 
+/*
+ * Restoration (Discussion D4, token restoration through the map dst(k,i) of the matching step).
+ *
+ * ttf_restore_map: for every original token, the row of the compressed sequence that stands for
+ * it -- its own row if it was retained (anchor tokens included), the anchor row
+ * row_offsets[b] + dst(k,i) if it was fused.
+ *   fuse_map, row_offsets, src_index   DEVICE, as written by ttf_compress for the same params
+ *   restore_map                        DEVICE int32 [B,F,N], every entry written
+ * ttf_restore: the full layout rebuilt from the compressed rows,
+ *   restored[b,k,i,:] = tokens[restore_map[b,k,i], :]   (bit-exact row copies).
+ *   tokens       DEVICE [rows, C] dtype, 16-byte aligned (ttf_compress's tokens_out, or rows of the
+ *                same shape computed from it, e.g. after further layers)
+ *   rows         number of valid rows in `tokens`; map entries outside [0, rows) give a zero row
+ *   restored     DEVICE [B,F,N,C] dtype, 16-byte aligned
+ * Errors: INVALID_ARG (NULL pointer, bad sizes, rows < 0), UNSUPPORTED (dtype, alignment), HIP.
+ */
+ttf_status ttf_restore_map(const ttf_params* params, const int32_t* fuse_map, const int32_t* row_offsets,
+                           const int32_t* src_index, int32_t* restore_map, void* hip_stream);
+ttf_status ttf_restore(const ttf_params* params, const void* tokens, int64_t rows,
+                       const int32_t* restore_map, void* restored, void* hip_stream);
+
+/*
+ * Cache-aware decode alignment (Section 3; prefill-length and decode-position equations), host
+ * arithmetic on HOST integers: with L' compressed visual tokens and T text tokens the cache holds
+ * L_pre = L' + T pairs; decode step l = 0,1,... gets position L_pre + l and an attention mask of
+ * length L_pre + l + 1.  Output pointers may be NULL.  INVALID_ARG on a negative input.
+ */
+ttf_status ttf_decode_alignment(int64_t l_prime, int64_t text_tokens, int64_t step,
+                                int64_t* l_pre, int64_t* position, int64_t* mask_length);
+
+/*
+ * Video-adaptive threshold (Discussion D1: t calibrated from the empirical distribution of the
+ * best-match similarities of the current clip).  The paper leaves the rule open; this library
+ * uses an order statistic.  For a requested fused fraction phi in [0,1] of the M = (F-1)*N source
+ * tokens of a clip:  rank = clamp(ceil((1 - phi) * M), 1, M)  (formed in double precision), and
+ * thresholds[b] = the rank-th smallest s^ of clip b.  Tokens strictly above it fuse, so at most
+ * floor(phi*M) do, exactly that many when the values next to the rank are distinct.  F = 1 gives
+ * thresholds[b] = 1.  Values are ordered as real numbers (-0 just below +0; a NaN with the sign
+ * bit clear sorts above +inf, with it set below -inf).
+ *   best_sim, anchor_index   DEVICE, as written by ttf_compress (best_sim requested there)
+ *   thresholds               DEVICE float [B]
+ * Errors: INVALID_ARG (NULL pointer, bad sizes, phi outside [0,1] or NaN), HIP.
+ */
+ttf_status ttf_select_threshold(const ttf_params* params, const float* best_sim,
+                                const int32_t* anchor_index, float fused_fraction,
+                                float* thresholds, void* hip_stream);
+
+/*
+ * Gate, offsets and row emission redone from stored matches (threshold-gating equation and the
+ * compaction that follows it), without a window search: the result is what ttf_compress gives
+ * for the same features with clip b gated at thresholds[b] (or at params->t for every clip when
+ * thresholds is NULL) and its anchor fixed to anchor_index[b].
+ *   out->anchor_index, out->best_sim, out->best_idx   INPUTS here: DEVICE arrays a previous
+ *       ttf_compress on the same features and params (r included) wrote; all three required
+ *   out->fuse_map, tokens_out, pos_ids, src_index, row_offsets, kept_count, host_counts   written
+ *   thresholds   DEVICE float [B] or NULL
+ * params->anchor_mode / anchor_index / r are not used.  Workspace as for ttf_compress.
+ */
+ttf_status ttf_regate(const ttf_params* params, const void* features, const float* thresholds,
+                      void* workspace, size_t workspace_bytes, const ttf_outputs* out, void* hip_stream);
+
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char* ttf_status_string(ttf_status status);
 

@@ -16,6 +16,11 @@ from .binding import (  # noqa: F401
     ttf_workspace_size,
     ttf_status_string,
     ttf_last_hip_error,
+    ttf_restore_map,
+    ttf_restore,
+    ttf_decode_alignment,
+    ttf_select_threshold,
+    ttf_regate,
     ttf_profile_enable,
     ttf_profile_read,
 )

@@ -56,6 +56,18 @@ def load_library() -> ctypes.CDLL:
         lib.ttf_compress.restype = ctypes.c_int
         lib.ttf_compress.argtypes = [ctypes.POINTER(_Params), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                                      ctypes.POINTER(_Outputs), ctypes.c_void_p]
+        vp, i64 = ctypes.c_void_p, ctypes.c_int64
+        lib.ttf_restore_map.restype = ctypes.c_int
+        lib.ttf_restore_map.argtypes = [ctypes.POINTER(_Params), vp, vp, vp, vp, vp]
+        lib.ttf_restore.restype = ctypes.c_int
+        lib.ttf_restore.argtypes = [ctypes.POINTER(_Params), vp, i64, vp, vp, vp]
+        lib.ttf_decode_alignment.restype = ctypes.c_int
+        lib.ttf_decode_alignment.argtypes = [i64, i64, i64] + [ctypes.POINTER(i64)] * 3
+        lib.ttf_select_threshold.restype = ctypes.c_int
+        lib.ttf_select_threshold.argtypes = [ctypes.POINTER(_Params), vp, vp, ctypes.c_float, vp, vp]
+        lib.ttf_regate.restype = ctypes.c_int
+        lib.ttf_regate.argtypes = [ctypes.POINTER(_Params), vp, vp, vp, ctypes.c_size_t,
+                                   ctypes.POINTER(_Outputs), vp]
         lib.ttf_status_string.restype = ctypes.c_char_p
         lib.ttf_status_string.argtypes = [ctypes.c_int]
         lib.ttf_last_hip_error.restype = ctypes.c_int
@@ -211,6 +223,100 @@ def ttf_compress(features: torch.Tensor, r: int = 1, t: float = 0.70, anchor: Un
         _check(load_library().ttf_compress(ctypes.byref(p), features.data_ptr(), ws_ptr, ws_bytes,
                                            ctypes.byref(o), ctypes.c_void_p(s.cuda_stream)))
     return TTFOutput(buffers, B, F, H, W, C)
+
+
+def _stream_ptr(stream, device):
+    s = stream if stream is not None else torch.cuda.current_stream(device)
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _outputs_of(buffers: TTFBuffers) -> _Outputs:
+    return _Outputs(_ptr(buffers.tokens_out), _ptr(buffers.pos_ids), _ptr(buffers.src_index),
+                    _ptr(buffers.row_offsets), _ptr(buffers.kept_count), _ptr(buffers.anchor_index),
+                    _ptr(buffers.fuse_map), _ptr(buffers.best_sim), _ptr(buffers.best_idx),
+                    _ptr(buffers.host_counts))
+
+
+def ttf_restore_map(out: TTFOutput, restore_map: Optional[torch.Tensor] = None,
+                    stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """int32 [B,F,N]: the compressed row that stands for every original token."""
+    b = out.buffers
+    dev = b.fuse_map.device
+    if restore_map is None:
+        restore_map = torch.empty((out.B, out.F, out.H * out.W), dtype=torch.int32, device=dev)
+    p = _make_params(out.B, out.F, out.H, out.W, out.C, _dtype_code(b.tokens_out.dtype), 0, 0.0, "auto")
+    with torch.cuda.device(dev):
+        _check(load_library().ttf_restore_map(ctypes.byref(p), b.fuse_map.data_ptr(), b.row_offsets.data_ptr(),
+                                              b.src_index.data_ptr(), restore_map.data_ptr(),
+                                              _stream_ptr(stream, dev)))
+    return restore_map
+
+
+def ttf_restore(tokens: torch.Tensor, rows: int, restore_map: torch.Tensor, H: int, W: int,
+                restored: Optional[torch.Tensor] = None,
+                stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """[B,F,H,W,C]: ``tokens[restore_map]`` -- the full layout rebuilt from compressed rows."""
+    B, F, N = (int(v) for v in restore_map.shape)
+    C = int(tokens.shape[-1])
+    if N != H * W:
+        raise ValueError("restore_map does not match the grid")
+    if not tokens.is_contiguous() or not restore_map.is_contiguous() or restore_map.dtype != torch.int32:
+        raise ValueError("tokens and restore_map must be contiguous, restore_map int32")
+    if rows > tokens.shape[0]:
+        raise ValueError("rows exceeds the token buffer")
+    if restored is None:
+        restored = torch.empty((B, F, H, W, C), dtype=tokens.dtype, device=tokens.device)
+    p = _make_params(B, F, H, W, C, _dtype_code(tokens.dtype), 0, 0.0, "auto")
+    with torch.cuda.device(tokens.device):
+        _check(load_library().ttf_restore(ctypes.byref(p), tokens.data_ptr(), int(rows), restore_map.data_ptr(),
+                                          restored.data_ptr(), _stream_ptr(stream, tokens.device)))
+    return restored
+
+
+def ttf_decode_alignment(l_prime: int, text_tokens: int, step: int):
+    """(L_pre, position of decode step ``step``, attention-mask length at that step)."""
+    v = [ctypes.c_int64(0) for _ in range(3)]
+    _check(load_library().ttf_decode_alignment(int(l_prime), int(text_tokens), int(step),
+                                               *(ctypes.byref(x) for x in v)))
+    return tuple(int(x.value) for x in v)
+
+
+def ttf_select_threshold(out: TTFOutput, fused_fraction: float, thresholds: Optional[torch.Tensor] = None,
+                         stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """float32 [B]: per-clip threshold that fuses at most ``fused_fraction`` of the source tokens."""
+    b = out.buffers
+    if b.best_sim is None:
+        raise ValueError("threshold selection needs best_sim (want_sim=True)")
+    dev = b.best_sim.device
+    if thresholds is None:
+        thresholds = torch.empty((out.B,), dtype=torch.float32, device=dev)
+    p = _make_params(out.B, out.F, out.H, out.W, out.C, _dtype_code(b.tokens_out.dtype), 0, 0.0, "auto")
+    with torch.cuda.device(dev):
+        _check(load_library().ttf_select_threshold(ctypes.byref(p), b.best_sim.data_ptr(),
+                                                   b.anchor_index.data_ptr(), float(fused_fraction),
+                                                   thresholds.data_ptr(), _stream_ptr(stream, dev)))
+    return thresholds
+
+
+def ttf_regate(features: torch.Tensor, out: TTFOutput, thresholds: Optional[torch.Tensor] = None,
+               t: float = 0.70, stream: Optional[torch.cuda.Stream] = None) -> TTFOutput:
+    """Redo gate, offsets and rows of ``out`` (in place) from its stored matches, at per-clip
+    ``thresholds`` (float32 [B] on the GPU) or at ``t`` for every clip."""
+    b = out.buffers
+    if b.best_sim is None or b.best_idx is None:
+        raise ValueError("regating needs best_sim and best_idx (want_sim=True)")
+    if tuple(features.shape) != (out.B, out.F, out.H, out.W, out.C) or not features.is_contiguous():
+        raise ValueError("features must be the contiguous tensor the matches were computed from")
+    if thresholds is not None and (thresholds.dtype != torch.float32 or thresholds.numel() != out.B
+                                   or not thresholds.is_cuda):
+        raise ValueError("thresholds must be float32 [B] on the GPU")
+    p = _make_params(out.B, out.F, out.H, out.W, out.C, _dtype_code(features.dtype), 0, t, "auto")
+    ws_ptr, ws_bytes = _aligned_workspace(b.workspace)
+    o = _outputs_of(b)
+    with torch.cuda.device(features.device):
+        _check(load_library().ttf_regate(ctypes.byref(p), features.data_ptr(), _ptr(thresholds), ws_ptr, ws_bytes,
+                                         ctypes.byref(o), _stream_ptr(stream, features.device)))
+    return out
 
 
 def ttf_profile_enable(slots: int) -> None:

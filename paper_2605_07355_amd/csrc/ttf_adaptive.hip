@@ -1,0 +1,124 @@
+// Video-adaptive threshold (Discussion D1): the threshold of a clip is read off the empirical
+// distribution of its best-match similarities {s^(k,i)}, and the gate, the offsets and the row
+// emission are redone at the new threshold from the stored s^ and dst, without another window
+// search.
+//
+// The selection rule is an order statistic: for a requested fused fraction phi of the
+// M = (F-1) N source tokens, t = the rank-th smallest s^ with rank = clamp(ceil((1-phi) M), 1, M);
+// only tokens strictly above it are fused, so at most floor(phi M) are.  It is found exactly by a
+// most-significant-digit-first radix selection over an order-preserving integer image of the
+// floats: four passes of 256-bin counting, one workgroup per clip, integer LDS atomics only
+// (counts do not depend on the order of the additions).
+#include "ttf_device.h"
+#include "ttf_internal.h"
+
+namespace ttf {
+namespace {
+
+// Monotone map float -> uint32: a < b as reals  <=>  key(a) < key(b)  (-0 sorts just below +0).
+__device__ __forceinline__ uint32_t order_key(float v)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, v);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key_value(uint32_t k)
+{
+    const uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+    return __builtin_bit_cast(float, u);
+}
+
+__global__ __launch_bounds__(1024) void k_select_threshold(const float* __restrict__ best_sim,
+                                                           const int32_t* __restrict__ anchor_index,
+                                                           float* __restrict__ thresholds,
+                                                           int F, int N, long long rank)
+{
+    const int b = blockIdx.x;
+    const int a = anchor_index[b];
+    const float* sim = best_sim + (size_t)b * F * N;
+    const long long FN = (long long)F * N;
+    const long long skip_lo = (long long)a * N, skip_hi = skip_lo + N;   // the anchor frame is not a source
+    __shared__ unsigned hist[256];
+    __shared__ uint32_t s_prefix;
+    __shared__ long long s_k;
+    if (threadIdx.x == 0) { s_prefix = 0u; s_k = rank - 1; }
+    uint32_t mask = 0u;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        if (threadIdx.x < 256) hist[threadIdx.x] = 0u;
+        __syncthreads();
+        const uint32_t prefix = s_prefix;
+        for (long long j = threadIdx.x; j < FN; j += 1024) {
+            if (j >= skip_lo && j < skip_hi) continue;
+            const uint32_t key = order_key(sim[j]);
+            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {                     // 256 bins: a serial walk is short next to the counting pass
+            long long k = s_k;
+            int d = 0;
+            while (d < 255 && k >= (long long)hist[d]) { k -= hist[d]; ++d; }
+            s_k = k;
+            s_prefix = prefix | ((uint32_t)d << shift);
+        }
+        mask |= 255u << shift;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) thresholds[b] = key_value(s_prefix);
+}
+
+__global__ __launch_bounds__(64) void k_fill_thresholds(float* __restrict__ thresholds, int B, float v)
+{
+    for (int b = threadIdx.x; b < B; b += 64) thresholds[b] = v;
+}
+
+// Gate from stored similarities: one wave per 64-token keep word.
+__global__ __launch_bounds__(256) void k_regate(const float* __restrict__ best_sim,
+                                                const int32_t* __restrict__ best_idx,
+                                                const int32_t* __restrict__ anchor_index,
+                                                const float* __restrict__ thresholds, float t_all,
+                                                int32_t* __restrict__ fuse_map, uint64_t* __restrict__ keep_bits,
+                                                int F, int N, int NW, size_t words)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t wd = (size_t)blockIdx.x * 4 + wave;          // global keep word
+    if (wd >= words) return;
+    const int word = (int)(wd % NW);
+    const size_t frame = wd / NW;
+    const int b = (int)(frame / F), k = (int)(frame % F);
+    const float t = thresholds ? thresholds[b] : t_all;
+    const int i = word * 64 + lane;
+    bool keep = false;
+    if (i < N) {
+        const size_t o = frame * (size_t)N + i;
+        const bool fused = k != anchor_index[b] && best_sim[o] > t;   // keep = 1[s^ <= t]
+        fuse_map[o] = fused ? best_idx[o] : -1;
+        keep = !fused;
+    }
+    const uint64_t bits = __ballot(keep);
+    if (lane == 0) keep_bits[wd] = bits;
+}
+
+}  // namespace
+
+hipError_t launch_select_threshold(const ttf_params& p, const float* best_sim, const int32_t* anchor_index,
+                                   long long rank, float* thresholds, hipStream_t s)
+{
+    const int N = p.H * p.W;
+    if (p.F < 2) {                                            // no source tokens: the documented default
+        k_fill_thresholds<<<1, 64, 0, s>>>(thresholds, p.B, 1.0f);
+        return hipGetLastError();
+    }
+    k_select_threshold<<<(unsigned)p.B, 1024, 0, s>>>(best_sim, anchor_index, thresholds, p.F, N, rank);
+    return hipGetLastError();
+}
+
+hipError_t launch_regate(const ttf_params& p, const Workspace& w, const float* best_sim, const int32_t* best_idx,
+                         const int32_t* anchor_index, const float* thresholds, int32_t* fuse_map, hipStream_t s)
+{
+    const int N = p.H * p.W, NW = (N + 63) / 64;
+    const size_t words = (size_t)p.B * p.F * NW;
+    k_regate<<<(unsigned)((words + 3) / 4), 256, 0, s>>>(best_sim, best_idx, anchor_index, thresholds, p.t,
+                                                         fuse_map, w.keep_bits, p.F, N, NW, words);
+    return hipGetLastError();
+}
+
+}  // namespace ttf

@@ -149,6 +149,101 @@ ttf_status ttf_compress(const ttf_params* params, const void* features, void* wo
     return TTF_OK;
 }
 
+ttf_status ttf_restore_map(const ttf_params* params, const int32_t* fuse_map, const int32_t* row_offsets,
+                           const int32_t* src_index, int32_t* restore_map, void* hip_stream)
+{
+    const ttf_status st = check_params(params);
+    if (st != TTF_OK) return st;
+    if (!fuse_map || !row_offsets || !src_index || !restore_map) return TTF_ERR_INVALID_ARG;
+    const hipError_t e = launch_restore_map(*params, fuse_map, row_offsets, src_index, restore_map,
+                                            static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) {
+        g_last_hip_error = static_cast<int>(e);
+        return TTF_ERR_HIP;
+    }
+    return TTF_OK;
+}
+
+ttf_status ttf_restore(const ttf_params* params, const void* tokens, int64_t rows,
+                       const int32_t* restore_map, void* restored, void* hip_stream)
+{
+    const ttf_status st = check_params(params);
+    if (st != TTF_OK) return st;
+    if (!tokens || !restore_map || !restored || rows < 0) return TTF_ERR_INVALID_ARG;
+    if (!aligned(tokens, 16) || !aligned(restored, 16)) return TTF_ERR_UNSUPPORTED;
+    const hipError_t e = launch_restore_rows(*params, tokens, rows, restore_map, restored,
+                                             static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) {
+        g_last_hip_error = static_cast<int>(e);
+        return TTF_ERR_HIP;
+    }
+    return TTF_OK;
+}
+
+ttf_status ttf_decode_alignment(int64_t l_prime, int64_t text_tokens, int64_t step,
+                                int64_t* l_pre, int64_t* position, int64_t* mask_length)
+{
+    if (l_prime < 0 || text_tokens < 0 || step < 0) return TTF_ERR_INVALID_ARG;
+    const int64_t pre = l_prime + text_tokens;
+    if (l_pre) *l_pre = pre;
+    if (position) *position = pre + step;
+    if (mask_length) *mask_length = pre + step + 1;
+    return TTF_OK;
+}
+
+ttf_status ttf_select_threshold(const ttf_params* params, const float* best_sim,
+                                const int32_t* anchor_index, float fused_fraction,
+                                float* thresholds, void* hip_stream)
+{
+    const ttf_status st = check_params(params);
+    if (st != TTF_OK) return st;
+    if (!best_sim || !anchor_index || !thresholds) return TTF_ERR_INVALID_ARG;
+    if (!(fused_fraction >= 0.0f && fused_fraction <= 1.0f)) return TTF_ERR_INVALID_ARG;
+    const long long M = (long long)(params->F - 1) * params->H * params->W;
+    long long rank = (long long)std::ceil((1.0 - (double)fused_fraction) * (double)M);
+    rank = rank < 1 ? 1 : (rank > M ? M : rank);
+    const hipError_t e = launch_select_threshold(*params, best_sim, anchor_index, rank, thresholds,
+                                                 static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) {
+        g_last_hip_error = static_cast<int>(e);
+        return TTF_ERR_HIP;
+    }
+    return TTF_OK;
+}
+
+ttf_status ttf_regate(const ttf_params* params, const void* features, const float* thresholds,
+                      void* workspace, size_t workspace_bytes, const ttf_outputs* out, void* hip_stream)
+{
+    const ttf_status st = check_params(params);
+    if (st != TTF_OK) return st;
+    if (!features || !workspace || !out) return TTF_ERR_INVALID_ARG;
+    if (!out->tokens_out || !out->pos_ids || !out->src_index || !out->row_offsets || !out->kept_count ||
+        !out->anchor_index || !out->fuse_map || !out->best_sim || !out->best_idx)
+        return TTF_ERR_INVALID_ARG;
+    if (!aligned(features, 16) || !aligned(out->tokens_out, 16) || !aligned(workspace, 256))
+        return TTF_ERR_UNSUPPORTED;
+    const ttf_params& p = *params;
+    const Workspace w = carve(p, workspace);
+    if (workspace_bytes < w.bytes) return TTF_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = launch_regate(p, w, out->best_sim, out->best_idx, out->anchor_index, thresholds,
+                                 out->fuse_map, s);
+    if (e == hipSuccess) e = launch_offsets_scan(p, w, out->anchor_index, out->kept_count, out->row_offsets, s);
+    if (e == hipSuccess)
+        e = launch_emit_rows(p, features, w, out->anchor_index, out->tokens_out, out->pos_ids, out->src_index, s);
+    if (e == hipSuccess && out->host_counts) {
+        e = hipMemcpyAsync(out->host_counts, out->kept_count, sizeof(int32_t) * p.B, hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(out->host_counts + p.B, out->row_offsets, sizeof(int32_t) * (p.B + 1),
+                               hipMemcpyDeviceToHost, s);
+    }
+    if (e != hipSuccess) {
+        g_last_hip_error = static_cast<int>(e);
+        return TTF_ERR_HIP;
+    }
+    return TTF_OK;
+}
+
 const char* ttf_status_string(ttf_status status)
 {
     switch (status) {

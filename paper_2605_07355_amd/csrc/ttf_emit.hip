@@ -69,43 +69,6 @@ __global__ __launch_bounds__(1024) void k_offsets_scan(const uint64_t* __restric
     for (int b = tid; b < B; b += 1024) kept_count[b] = row_offsets[b + 1] - row_offsets[b];
 }
 
-// U = bytes moved per lane per step: 16 (row bytes % 16 == 0), 4 or 2.
-template <int U>
-__device__ __forceinline__ void copy_row(const char* __restrict__ src, char* __restrict__ dst,
-                                         size_t row_bytes, int lane)
-{
-    if constexpr (U == 16) {
-        const uint4* s = reinterpret_cast<const uint4*>(src);
-        uint4* d = reinterpret_cast<uint4*>(dst);
-        const int n = (int)(row_bytes / 16);
-        int q = lane;
-        for (; q + 448 < n; q += 512) {                // eight 16-byte pieces in flight per lane
-            uint4 v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = load16_stream(s + q + 64 * u);
-#pragma unroll
-            for (int u = 0; u < 8; ++u) store16_stream(d + q + 64 * u, v[u]);
-        }
-        for (; q + 192 < n; q += 256) {
-            const uint4 v0 = load16_stream(s + q), v1 = load16_stream(s + q + 64),
-                        v2 = load16_stream(s + q + 128), v3 = load16_stream(s + q + 192);
-            store16_stream(d + q, v0); store16_stream(d + q + 64, v1);
-            store16_stream(d + q + 128, v2); store16_stream(d + q + 192, v3);
-        }
-        for (; q < n; q += 64) store16_stream(d + q, load16_stream(s + q));
-    } else if constexpr (U == 4) {
-        const uint32_t* s = reinterpret_cast<const uint32_t*>(src);
-        uint32_t* d = reinterpret_cast<uint32_t*>(dst);
-        const int n = (int)(row_bytes / 4);
-        for (int q = lane; q < n; q += 64) d[q] = s[q];
-    } else {
-        const uint16_t* s = reinterpret_cast<const uint16_t*>(src);
-        uint16_t* d = reinterpret_cast<uint16_t*>(dst);
-        const int n = (int)(row_bytes / 2);
-        for (int q = lane; q < n; q += 64) d[q] = s[q];
-    }
-}
-
 // One block = 16 tokens (a quarter of a 64-token keep word) of one frame; its kept tokens are dealt
 // to the four waves by rank.  Small blocks matter: a wave copies its rows one after the other, so
 // the fewer rows per wave, the more copies are in flight across the chip.

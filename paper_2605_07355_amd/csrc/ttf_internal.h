@@ -72,4 +72,17 @@ hipError_t launch_emit_rows(const ttf_params& p, const void* x, const Workspace&
                             const int32_t* anchor_index, void* tokens_out, int32_t* pos_ids,
                             int32_t* src_index, hipStream_t s);
 
+// Restoration: map from every original token to the compressed row that stands for it, and the
+// gather that rebuilds the full layout.
+hipError_t launch_restore_map(const ttf_params& p, const int32_t* fuse_map, const int32_t* row_offsets,
+                              const int32_t* src_index, int32_t* restore_map, hipStream_t s);
+hipError_t launch_restore_rows(const ttf_params& p, const void* tokens, long long rows,
+                               const int32_t* restore_map, void* restored, hipStream_t s);
+// Adaptive threshold: exact order statistic of the source similarities per clip, and the gate
+// redone from stored similarities (fills fuse_map and the keep bits).
+hipError_t launch_select_threshold(const ttf_params& p, const float* best_sim, const int32_t* anchor_index,
+                                   long long rank, float* thresholds, hipStream_t s);
+hipError_t launch_regate(const ttf_params& p, const Workspace& w, const float* best_sim, const int32_t* best_idx,
+                         const int32_t* anchor_index, const float* thresholds, int32_t* fuse_map, hipStream_t s);
+
 }  // namespace ttf

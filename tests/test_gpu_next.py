@@ -1,0 +1,226 @@
+"""GPU parity of the follow-on entry points (restoration, decode alignment, adaptive threshold
+and re-gating) against the oracle modules, through the C ABI.  Integer and byte outputs bit for
+bit; a selected threshold is an order statistic of float32 inputs and must match exactly when
+both sides are given the same array."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from workloads import CONFIGS, make_clip_batch, similarity_field
+
+from helpers import SENTINEL, compare_with_oracle, rows_as_bits, run_gpu, to_device
+
+pytestmark = pytest.mark.gpu
+
+ANCHOR_AUTO, ANCHOR_FIXED = 0, 1
+
+
+def _prepared(cfg, ts, r=None):
+    from oracle import margins
+    r = cfg.r if r is None else r
+    for attempt in range(4):
+        batch = make_clip_batch(cfg, seed=cfg.seed + 1000 * attempt)
+        try:
+            return batch, margins.enforce_margins(batch, r, ts, ANCHOR_AUTO, 0, want_tokens=True)
+        except margins.MarginError:
+            continue
+    raise RuntimeError("no seed met the margins")
+
+
+SMALL = [
+    ("tiny", {}),
+    ("qwen3vl_2b", dict(B=2, F=6)),                                    # matrix-core search path, 16x16 grid
+    ("tiny", dict(B=3, F=5, H=7, W=9, C=40, dtype="f32")),             # ragged keep words, scalar rows
+    ("tiny", dict(B=2, F=4, H=5, W=13, C=129, dtype="bf16")),          # odd row length (2-byte copies)
+]
+
+
+# ------------------------------------------------------------------------------ restoration
+@pytest.mark.parametrize("name,scale", SMALL)
+def test_restore_map_and_rows(name, scale):
+    import paper_2605_07355_amd as ttf
+    from oracle import restore as R
+    cfg = CONFIGS[name].scaled(**scale)
+    batch, res = _prepared(cfg, (cfg.t[0],))
+    x, out = run_gpu(batch.x, cfg.r, cfg.t[0])
+    compare_with_oracle(batch.x, out, res)
+    want_map = R.restore_map(res.fuse_map, res.anchor_index, res.row_offsets, res.src_index)
+    rmap = torch.full((cfg.B, cfg.F, cfg.H * cfg.W), SENTINEL, dtype=torch.int32, device="cuda")
+    ttf.ttf_restore_map(out, rmap)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(rmap.cpu().numpy(), want_map)
+    full = torch.empty_like(x)
+    full.view(torch.uint8).fill_(0x5B)
+    ttf.ttf_restore(out.buffers.tokens_out, res.total_rows, rmap, cfg.H, cfg.W, full)
+    torch.cuda.synchronize()
+    want = R.restore(res.tokens_out, want_map)                         # [B,F,N,C] in the input's bit type
+    np.testing.assert_array_equal(rows_as_bits(full).reshape(want.shape),
+                                  want.view(np.uint16 if want.dtype == np.uint16 else np.uint32))
+
+
+def test_restore_at_full_size_by_property():
+    """Headline workload: the map against the oracle's in full; the restored tensor through what
+    it must equal at any size -- the input itself at retained positions, the matched anchor token
+    at fused ones (indices taken from the oracle's fuse_map)."""
+    import paper_2605_07355_amd as ttf
+    from oracle import restore as R
+    cfg = CONFIGS["qwen3vl_8b_batched"]
+    batch, res = _prepared(cfg, (cfg.t[0],))
+    x, out = run_gpu(batch.x, cfg.r, cfg.t[0])
+    rmap = ttf.ttf_restore_map(out)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(rmap.cpu().numpy(),
+                                  R.restore_map(res.fuse_map, res.anchor_index, res.row_offsets, res.src_index))
+    full = ttf.ttf_restore(out.buffers.tokens_out, res.total_rows, rmap, cfg.H, cfg.W)
+    torch.cuda.synchronize()
+    B, F, N, C = cfg.B, cfg.F, cfg.H * cfg.W, cfg.C
+    fm = torch.from_numpy(res.fuse_map).cuda().long()                  # [B,F,N]
+    a = torch.from_numpy(res.anchor_index).cuda().long()
+    xv = x.view(B, F, N, C).view(torch.int16)
+    fv = full.view(B, F, N, C).view(torch.int16)
+    for b in range(B):
+        fused = fm[b] >= 0
+        assert torch.equal(fv[b][~fused], xv[b][~fused])
+        assert torch.equal(fv[b][fused], xv[b, a[b]][fm[b][fused]])
+
+
+def test_restore_map_entries_outside_the_rows_give_zero_rows():
+    import paper_2605_07355_amd as ttf
+    tokens = torch.arange(6 * 8, dtype=torch.float32, device="cuda").view(6, 8) + 1.0
+    rmap = torch.tensor([[[0, 5, -1, 6]]], dtype=torch.int32, device="cuda")       # B=1,F=1,N=4 ; rows = 6
+    full = ttf.ttf_restore(tokens, 6, rmap, 2, 2)
+    torch.cuda.synchronize()
+    got = full.view(4, 8).cpu().numpy()
+    np.testing.assert_array_equal(got[0], tokens[0].cpu().numpy())
+    np.testing.assert_array_equal(got[1], tokens[5].cpu().numpy())
+    assert (got[2] == 0).all() and (got[3] == 0).all()
+    full = ttf.ttf_restore(tokens, 3, rmap, 2, 2)                      # fewer valid rows: entry 5 is now outside
+    torch.cuda.synchronize()
+    assert (full.view(4, 8)[1] == 0).all()
+
+
+def test_decode_alignment_matches_the_oracle():
+    import paper_2605_07355_amd as ttf
+    from oracle import restore as R
+    for args in [(0, 0, 0), (256 + 91, 33, 0), (256 + 91, 33, 17), (2 ** 31, 2 ** 20, 5)]:
+        assert ttf.ttf_decode_alignment(*args) == R.decode_alignment(*args)
+    with pytest.raises(ttf.TTFError):
+        ttf.ttf_decode_alignment(-1, 0, 0)
+
+
+# ------------------------------------------------------------------------ adaptive threshold
+class _FakeOut:
+    """Minimal stand-in carrying device arrays for the selection call."""
+    def __init__(self, sim, anchor, H, W):
+        import paper_2605_07355_amd as ttf
+        B, F, N = sim.shape
+        self.B, self.F, self.H, self.W, self.C = B, F, H, W, 8
+        self.buffers = ttf.TTFBuffers.allocate(B, F, H, W, 8, torch.float32, "cuda")
+        self.buffers.best_sim.copy_(torch.from_numpy(sim).cuda())
+        self.buffers.anchor_index.copy_(torch.from_numpy(anchor).cuda())
+
+
+@pytest.mark.parametrize("fraction", [0.0, 0.05, 0.5, 0.67, 0.95, 1.0])
+@pytest.mark.parametrize("B,F,H,W,ties", [(3, 5, 7, 9, False), (2, 9, 16, 16, True), (1, 2, 1, 1, False),
+                                           (16, 32, 16, 16, False)])
+def test_selected_threshold_is_exact(B, F, H, W, ties, fraction):
+    import paper_2605_07355_amd as ttf
+    from oracle import adaptive as A
+    sim, anchor = similarity_field(B, F, H * W, seed=B * 100 + F, ties=ties)
+    out = _FakeOut(sim, anchor, H, W)
+    t = ttf.ttf_select_threshold(out, fraction)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(t.cpu().numpy(), A.select_threshold(sim, anchor, fraction))
+
+
+def test_selected_threshold_without_source_frames():
+    import paper_2605_07355_amd as ttf
+    sim, anchor = similarity_field(4, 1, 12, seed=3)
+    t = ttf.ttf_select_threshold(_FakeOut(sim, anchor, 3, 4), 0.5)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(t.cpu().numpy(), np.ones(4, np.float32))
+
+
+@pytest.mark.parametrize("name,scale", SMALL + [("qwen3vl_8b_batched", {})])
+def test_regate_per_clip_thresholds(name, scale):
+    """Search once at the workload's threshold, then re-gate at a different threshold per clip:
+    every output must equal the oracle run clip by clip at those thresholds."""
+    import paper_2605_07355_amd as ttf
+    from oracle import adaptive as A
+    cfg = CONFIGS[name].scaled(**scale)
+    ts = [float(np.float32(0.45 + 0.5 * (b % 4) / 4)) for b in range(cfg.B)]     # 0.45, 0.575, 0.70, 0.825
+    batch, res = _prepared(cfg, (cfg.t[0],) + tuple(sorted(set(ts) - {cfg.t[0]})))
+    x, out = run_gpu(batch.x, cfg.r, cfg.t[0])
+    compare_with_oracle(batch.x, out, res)
+    buf = out.buffers
+    buf.tokens_out.view(torch.uint8).fill_(0x7A)
+    for tns in (buf.pos_ids, buf.src_index, buf.row_offsets, buf.kept_count, buf.fuse_map):
+        tns.fill_(SENTINEL)
+    buf.workspace.fill_(0xEE)
+    ttf.ttf_regate(x, out, torch.tensor(ts, dtype=torch.float32, device="cuda"))
+    torch.cuda.synchronize()
+    want = A.compress_per_clip(batch.x, cfg.r, ts, res.anchor_index)
+    compare_with_oracle(batch.x, out, want)
+    if cfg.B > 1:
+        assert len(set(want.kept_count.tolist())) > 1                 # the thresholds really differ in effect
+
+
+def test_regate_with_one_threshold_equals_a_fresh_pass():
+    import paper_2605_07355_amd as ttf
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=2, F=5)
+    batch, res = _prepared(cfg, (0.6, 0.8))
+    x, out = run_gpu(batch.x, cfg.r, 0.6)
+    ttf.ttf_regate(x, out, None, t=0.8)
+    torch.cuda.synchronize()
+    from oracle import ttf_oracle as T
+    compare_with_oracle(batch.x, out, T.compress(batch.x, cfg.r, 0.8))
+
+
+def test_adaptive_end_to_end():
+    """Selection on the library's own float32 similarities: the threshold is within the similarity
+    tolerance of the oracle's (an order statistic moves by at most the largest perturbation), and
+    the re-gated pass fuses exactly the tokens above it, at most the requested share."""
+    import paper_2605_07355_amd as ttf
+    from oracle import adaptive as A
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=3, F=8)
+    batch = make_clip_batch(cfg)
+    from oracle import ttf_oracle as T
+    res = T.compress(batch.x, cfg.r, cfg.t[0], want_tokens=False)
+    x, out = run_gpu(batch.x, cfg.r, cfg.t[0])
+    phi = 0.4
+    t = ttf.ttf_select_threshold(out, phi)
+    ttf.ttf_regate(x, out, t)
+    torch.cuda.synchronize()
+    t_ref = A.select_threshold(res.best_sim, res.anchor_index, phi)
+    assert np.abs(t.cpu().numpy().astype(np.float64) - t_ref).max() <= 1e-5
+    M = (cfg.F - 1) * cfg.H * cfg.W
+    sim = out.buffers.best_sim
+    for b in range(cfg.B):
+        src = torch.ones(cfg.F, dtype=torch.bool, device="cuda")
+        src[int(out.buffers.anchor_index[b])] = False
+        fused = (out.buffers.fuse_map[b] >= 0)
+        assert torch.equal(fused[src], sim[b][src] > t[b])
+        assert not fused[~src].any()
+        n = int(fused.sum())
+        assert n <= int(np.floor(float(np.float32(phi)) * M)) and n >= int(0.39 * M)
+        assert int(out.buffers.kept_count[b]) == cfg.H * cfg.W + M - n
+
+
+def test_new_entry_points_reject_bad_arguments():
+    import paper_2605_07355_amd as ttf
+    from paper_2605_07355_amd import binding as bd
+    lib = ttf.load_library()
+    p = bd._make_params(1, 2, 2, 2, 8, bd.TTF_F32, 1, 0.7, "auto")
+    buf = torch.zeros(64, dtype=torch.int32, device="cuda")
+    q = buf.data_ptr()
+    assert lib.ttf_restore_map(ctypes.byref(p), None, q, q, q, None) == bd.TTF_ERR_INVALID_ARG
+    assert lib.ttf_restore(ctypes.byref(p), q, -1, q, q, None) == bd.TTF_ERR_INVALID_ARG
+    assert lib.ttf_restore(ctypes.byref(p), q + 4, 1, q, q, None) == bd.TTF_ERR_UNSUPPORTED
+    assert lib.ttf_select_threshold(ctypes.byref(p), q, q, ctypes.c_float(1.5), q, None) == bd.TTF_ERR_INVALID_ARG
+    assert lib.ttf_select_threshold(ctypes.byref(p), q, q, ctypes.c_float(float("nan")), q, None) == bd.TTF_ERR_INVALID_ARG
+    o = bd._Outputs(q, q, q, q, q, q, q, None, q, None)                # best_sim missing
+    assert lib.ttf_regate(ctypes.byref(p), q, None, q, 1 << 20, ctypes.byref(o), None) == bd.TTF_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert int(buf.abs().sum()) == 0

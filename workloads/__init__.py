@@ -11,4 +11,5 @@ from .ttf_gen import (  # noqa: F401
     bf16_bits_to_f32,
     f32_to_bf16_bits,
     make_clip_batch,
+    similarity_field,
 )

@@ -288,3 +288,24 @@ def translated_frames(cfg: WorkloadConfig, shifts: Sequence[Tuple[int, int]], se
         ys, xs = _moved_coords(cfg, off)
         frames.append(f0[ys, xs])
     return np.stack(frames)[None]
+
+
+def similarity_field(B: int, F: int, N: int, seed: int = 0, ties: bool = False) -> Tuple[np.ndarray, np.ndarray]:
+    """Stand-alone input for threshold selection: a float32 array [B,F,N] shaped like a field of
+    best-match similarities (a fused mode near 0.9 and a changed mode near 0.35, clipped to
+    [-1,1], a few exact zeros of either sign) and an int32 anchor frame per clip whose rows are set
+    to 1.  With ``ties`` the values are rounded to two decimals so that many coincide."""
+    rng = _rng(seed, _STREAM_META, 77)
+    hi = rng.normal(0.9, 0.04, size=(B, F, N))
+    lo = rng.normal(0.35, 0.15, size=(B, F, N))
+    field = np.where(rng.random((B, F, N)) < 0.67, hi, lo).clip(-1.0, 1.0).astype(np.float32)
+    if ties:
+        field = np.round(field, 2).astype(np.float32)
+    flat = field.reshape(-1)
+    pick = rng.choice(flat.size, size=min(6, flat.size), replace=False)
+    flat[pick[::2]] = np.float32(0.0)
+    flat[pick[1::2]] = np.float32(-0.0)
+    anchor = rng.integers(0, F, size=B).astype(np.int32)
+    for b in range(B):
+        field[b, anchor[b]] = 1.0
+    return field, anchor
