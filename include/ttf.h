@@ -116,6 +116,28 @@ ttf_status ttf_compress(const ttf_params* params, const void* features,
                         const ttf_outputs* out, void* hip_stream);
 
 /*
+ * One segment of a stream (Discussion D3: the last frame of each segment is the rolling anchor of
+ * the next; new frames are compressed against it and only the short result is appended).
+ * Every one of the F frames of `features` is a source frame matched against `anchor_frame`; the
+ * output holds only the preserved source rows, in ascending flat order k*N+i, so it is what
+ * ttf_compress gives for the (F+1)-frame clip [anchor_frame ; features] with its anchor fixed to
+ * frame 0, without the N anchor rows.  To chain segments pass the previous segment's last frame
+ * (features + (F-1)*N*C elements of each clip, gathered to [B,H,W,C]) as the next anchor_frame.
+ *   anchor_frame  DEVICE [B,H,W,C] dtype, 16-byte aligned, read only; may alias no output
+ *   frame_offset  added to the temporal plane of pos_ids: frame k of the segment reports
+ *                 frame_offset + k (its index in the stream); frame_offset + F must fit int32
+ *   out           as for ttf_compress, except: kept_count[b] = P_b (no anchor rows),
+ *                 anchor_index[b] = -1, best_idx / fuse_map index cells of anchor_frame,
+ *                 src_index = k*N+i inside the segment
+ * params->anchor_mode and anchor_index are not used.  Errors as for ttf_compress; a NULL or
+ * misaligned anchor_frame is INVALID_ARG / UNSUPPORTED.  ttf_restore_map does not apply to
+ * segment outputs (their anchor rows live in an earlier segment's output).
+ */
+ttf_status ttf_compress_segment(const ttf_params* params, const void* features, const void* anchor_frame,
+                                int32_t frame_offset, void* workspace, size_t workspace_bytes,
+                                const ttf_outputs* out, void* hip_stream);
+
+/*
  * Restoration (Discussion D4, token restoration through the map dst(k,i) of the matching step).
  *
  * ttf_restore_map: for every original token, the row of the compressed sequence that stands for

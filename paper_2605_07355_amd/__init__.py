@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     ttf_workspace_size,
     ttf_status_string,
     ttf_last_hip_error,
+    ttf_compress_segment,
     ttf_restore_map,
     ttf_restore,
     ttf_decode_alignment,

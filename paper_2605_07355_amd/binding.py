@@ -57,6 +57,9 @@ def load_library() -> ctypes.CDLL:
         lib.ttf_compress.argtypes = [ctypes.POINTER(_Params), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                                      ctypes.POINTER(_Outputs), ctypes.c_void_p]
         vp, i64 = ctypes.c_void_p, ctypes.c_int64
+        lib.ttf_compress_segment.restype = ctypes.c_int
+        lib.ttf_compress_segment.argtypes = [ctypes.POINTER(_Params), vp, vp, ctypes.c_int32, vp, ctypes.c_size_t,
+                                             ctypes.POINTER(_Outputs), vp]
         lib.ttf_restore_map.restype = ctypes.c_int
         lib.ttf_restore_map.argtypes = [ctypes.POINTER(_Params), vp, vp, vp, vp, vp]
         lib.ttf_restore.restype = ctypes.c_int
@@ -235,6 +238,29 @@ def _outputs_of(buffers: TTFBuffers) -> _Outputs:
                     _ptr(buffers.row_offsets), _ptr(buffers.kept_count), _ptr(buffers.anchor_index),
                     _ptr(buffers.fuse_map), _ptr(buffers.best_sim), _ptr(buffers.best_idx),
                     _ptr(buffers.host_counts))
+
+
+def ttf_compress_segment(features: torch.Tensor, anchor_frame: torch.Tensor, frame_offset: int = 0,
+                         r: int = 1, t: float = 0.70, buffers: Optional[TTFBuffers] = None,
+                         want_sim: bool = True, stream: Optional[torch.cuda.Stream] = None) -> TTFOutput:
+    """One stream segment ``features`` [B,F,H,W,C] against the rolling ``anchor_frame`` [B,H,W,C]:
+    only preserved source rows are emitted; temporal ids start at ``frame_offset``."""
+    if features.dim() != 5 or not features.is_cuda or not features.is_contiguous():
+        raise ValueError("features must be a contiguous [B,F,H,W,C] GPU tensor")
+    B, F, H, W, C = (int(v) for v in features.shape)
+    if (tuple(anchor_frame.shape) != (B, H, W, C) or anchor_frame.dtype != features.dtype
+            or anchor_frame.device != features.device or not anchor_frame.is_contiguous()):
+        raise ValueError("anchor_frame must be a contiguous [B,H,W,C] tensor like one frame of features")
+    p = _make_params(B, F, H, W, C, _dtype_code(features.dtype), r, t, "auto")
+    if buffers is None:
+        buffers = TTFBuffers.allocate(B, F, H, W, C, features.dtype, features.device, want_sim=want_sim)
+    ws_ptr, ws_bytes = _aligned_workspace(buffers.workspace)
+    o = _outputs_of(buffers)
+    with torch.cuda.device(features.device):
+        _check(load_library().ttf_compress_segment(ctypes.byref(p), features.data_ptr(), anchor_frame.data_ptr(),
+                                                   int(frame_offset), ws_ptr, ws_bytes, ctypes.byref(o),
+                                                   _stream_ptr(stream, features.device)))
+    return TTFOutput(buffers, B, F, H, W, C)
 
 
 def ttf_restore_map(out: TTFOutput, restore_map: Optional[torch.Tensor] = None,

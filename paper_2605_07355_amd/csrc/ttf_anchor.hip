@@ -178,7 +178,7 @@ __device__ __forceinline__ int pick_anchor(const double* __restrict__ score_part
 // Picks the anchor of clip b (arg max of frame_score, lowest k on ties, or the fixed frame),
 // publishes it, and writes 1/||x_{a,j}|| for the anchor tokens.  One wave per anchor token.
 template <typename T, int V>
-__global__ __launch_bounds__(256) void k_anchor_norms(const T* __restrict__ x,
+__global__ __launch_bounds__(256) void k_anchor_norms(const T* __restrict__ x, const T* __restrict__ ext_anchor,
                                                       const double* __restrict__ score_part,
                                                       const double* __restrict__ clip_part,
                                                       int32_t* __restrict__ anchor_index,
@@ -188,10 +188,12 @@ __global__ __launch_bounds__(256) void k_anchor_norms(const T* __restrict__ x,
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int b = blockIdx.x / groups;
     const int j = (blockIdx.x % groups) * 4 + wave;
-    const int a = fixed_anchor >= 0 ? fixed_anchor : pick_anchor(score_part, clip_part, b, F, S, lane);
+    // the anchor is a frame of x (fixed or picked), or frame b of ext_anchor (published as -1)
+    const int a = ext_anchor ? -1
+                : fixed_anchor >= 0 ? fixed_anchor : pick_anchor(score_part, clip_part, b, F, S, lane);
     if (blockIdx.x % groups == 0 && threadIdx.x == 0) anchor_index[b] = a;
     if (j >= N) return;
-    const T* row = x + (((size_t)b * F + a) * N + j) * (size_t)C;
+    const T* row = (ext_anchor ? ext_anchor + (size_t)b * N * C : x + ((size_t)b * F + a) * N * C) + (size_t)j * C;
     float ss = 0.f;
     for (int c = lane * V; c < C; c += 64 * V) {
         RowVec<T, V> r;
@@ -211,6 +213,7 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 // norms, permutes every 16x64-byte block into MFMA operand order (lane = token + 16*chunk) and
 // stores it as one contiguous KiB: anchor_frag[b][tile][K-step][lane][8 bf16].
 __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restrict__ x,
+                                                        const uint16_t* __restrict__ ext_anchor,
                                                         const double* __restrict__ score_part,
                                                         const double* __restrict__ clip_part,
                                                         int32_t* __restrict__ anchor_index,
@@ -223,9 +226,11 @@ __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restri
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int tiles = N / 16;
     const int b = blockIdx.x / tiles, tile = blockIdx.x % tiles;
-    const int a = fixed_anchor >= 0 ? fixed_anchor : pick_anchor(score_part, clip_part, b, F, S, lane);
+    // the anchor is a frame of x (fixed or picked), or frame b of ext_anchor (published as -1)
+    const int a = ext_anchor ? -1
+                : fixed_anchor >= 0 ? fixed_anchor : pick_anchor(score_part, clip_part, b, F, S, lane);
     if (tile == 0 && threadIdx.x == 0) anchor_index[b] = a;
-    if (threadIdx.x < 16) {                                  // anchor tokens are always retained
+    if (a >= 0 && threadIdx.x < 16) {                        // anchor tokens are always retained
         const size_t o = ((size_t)b * F + a) * N + 16 * tile + threadIdx.x;
         fuse_map[o] = -1;
         if (best_sim) best_sim[o] = 1.0f;
@@ -233,7 +238,8 @@ __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restri
         if (threadIdx.x == 0) keep16[o / 16] = 0xffffu;
     }
     const int KS = C / 32;
-    const uint16_t* src = x + (((size_t)b * F + a) * N + 16 * tile + (lane >> 2)) * (size_t)C + (lane & 3) * 8;
+    const uint16_t* frame = ext_anchor ? ext_anchor + (size_t)b * N * C : x + ((size_t)b * F + a) * N * C;
+    const uint16_t* src = frame + (size_t)(16 * tile + (lane >> 2)) * C + (lane & 3) * 8;
     uint16_t* dst = anchor_frag + ((size_t)b * tiles + tile) * (size_t)KS * 512 + lane * 8;
     const int bperm = (4 * (lane & 15) + (lane >> 4)) * 4;
     float nn = 0.f;
@@ -307,7 +313,7 @@ hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, hipStre
     return hipGetLastError();
 }
 
-hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const Workspace& w,
+hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                int32_t* anchor_index, hipStream_t s)
 {
     const int N = p.H * p.W;
@@ -318,20 +324,22 @@ hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const Workspa
         using T = decltype(tag);
         constexpr int V = decltype(vtag)::value;
         k_anchor_norms<T, V><<<(unsigned)(p.B * groups), 256, 0, s>>>(
-            static_cast<const T*>(x), w.score_part, w.clip_part, anchor_index, w.anchor_inv, p.F, N, p.C,
+            static_cast<const T*>(x), static_cast<const T*>(ext_anchor), w.score_part, w.clip_part, anchor_index,
+            w.anchor_inv, p.F, N, p.C,
             (p.C + 255) / 256, fixed, groups);
         return hipGetLastError();
     });
 }
 
-hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const Workspace& w,
+hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                       int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                       int32_t* best_idx, hipStream_t s)
 {
     const int N = p.H * p.W;
     int fixed = -1;
     if (p.anchor_mode == TTF_ANCHOR_FIXED) fixed = p.anchor_index < 0 ? p.anchor_index + p.F : p.anchor_index;
-    k_anchor_prepare<<<(unsigned)(p.B * (N / 16)), 512, 0, s>>>(static_cast<const uint16_t*>(x), w.score_part,
+    k_anchor_prepare<<<(unsigned)(p.B * (N / 16)), 512, 0, s>>>(static_cast<const uint16_t*>(x),
+                                                                static_cast<const uint16_t*>(ext_anchor), w.score_part,
                                                                 w.clip_part, anchor_index, w.anchor_inv,
                                                                 w.anchor_frag, fuse_map, best_sim, best_idx,
                                                                 reinterpret_cast<uint16_t*>(w.keep_bits),

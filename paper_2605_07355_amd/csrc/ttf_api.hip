@@ -9,11 +9,11 @@
 
 namespace ttf {
 
-hipError_t launch_window_search_generic(const ttf_params& p, const void* x, const Workspace& w,
+hipError_t launch_window_search_generic(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                         const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                         int32_t* best_idx, hipStream_t s);
 
-hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, const Workspace& w,
+hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,
                                      const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                      int32_t* best_idx, hipStream_t s);
 
@@ -27,13 +27,13 @@ bool use_mfma_path(const ttf_params& p)
     return !general && mfma_search_supported(p);
 }
 
-hipError_t launch_window_search(const ttf_params& p, const void* x, const Workspace& w,
+hipError_t launch_window_search(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                 const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                 int32_t* best_idx, hipStream_t s)
 {
     if (use_mfma_path(p))
-        return launch_window_search_mfma(p, x, w, anchor_index, fuse_map, best_sim, best_idx, s);
-    return launch_window_search_generic(p, x, w, anchor_index, fuse_map, best_sim, best_idx, s);
+        return launch_window_search_mfma(p, x, ext_anchor != nullptr, w, anchor_index, fuse_map, best_sim, best_idx, s);
+    return launch_window_search_generic(p, x, ext_anchor, w, anchor_index, fuse_map, best_sim, best_idx, s);
 }
 
 namespace {
@@ -84,8 +84,10 @@ ttf_status ttf_workspace_size(const ttf_params* params, size_t* bytes)
     return TTF_OK;
 }
 
-ttf_status ttf_compress(const ttf_params* params, const void* features, void* workspace,
-                        size_t workspace_bytes, const ttf_outputs* out, void* hip_stream)
+// The launch sequence behind ttf_compress (ext_anchor == nullptr) and ttf_compress_segment.
+static ttf_status run_pass(const ttf_params* params, const void* features, const void* ext_anchor,
+                           int frame_offset, void* workspace, size_t workspace_bytes, const ttf_outputs* out,
+                           void* hip_stream)
 {
     const ttf_status st = check_params(params);
     if (st != TTF_OK) return st;
@@ -95,11 +97,13 @@ ttf_status ttf_compress(const ttf_params* params, const void* features, void* wo
         return TTF_ERR_INVALID_ARG;
     if (!aligned(features, 16) || !aligned(out->tokens_out, 16) || !aligned(workspace, 256))
         return TTF_ERR_UNSUPPORTED;
+    if (ext_anchor && !aligned(ext_anchor, 16)) return TTF_ERR_UNSUPPORTED;
 
     ttf_params p = *params;
     p.r = p.r > (p.H > p.W ? p.H : p.W) ? (p.H > p.W ? p.H : p.W) : p.r;   // beyond the grid = whole grid
     const Workspace w = carve(p, workspace);
     if (workspace_bytes < w.bytes) return TTF_ERR_WORKSPACE_TOO_SMALL;
+    const bool pick = !ext_anchor && p.anchor_mode == TTF_ANCHOR_AUTO;       // the automatic anchor rule runs
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     Profile& prof = g_prof;
@@ -117,22 +121,22 @@ ttf_status ttf_compress(const ttf_params* params, const void* features, void* wo
     } while (0)
 
     mark();                                                    // start of stage 0
-    if (p.anchor_mode == TTF_ANCHOR_AUTO) TTF_STEP(launch_frame_sums(p, features, w, s));
+    if (pick) TTF_STEP(launch_frame_sums(p, features, w, s));
     mark();
-    if (p.anchor_mode == TTF_ANCHOR_AUTO) TTF_STEP(launch_anchor_scores(p, w, s));
+    if (pick) TTF_STEP(launch_anchor_scores(p, w, s));
     mark();
     if (use_mfma_path(p))
-        TTF_STEP(launch_anchor_prepare_mfma(p, features, w, out->anchor_index, out->fuse_map, out->best_sim,
-                                            out->best_idx, s));
-    else TTF_STEP(launch_anchor_norms(p, features, w, out->anchor_index, s));
+        TTF_STEP(launch_anchor_prepare_mfma(p, features, ext_anchor, w, out->anchor_index, out->fuse_map,
+                                            out->best_sim, out->best_idx, s));
+    else TTF_STEP(launch_anchor_norms(p, features, ext_anchor, w, out->anchor_index, s));
     mark();
-    TTF_STEP(launch_window_search(p, features, w, out->anchor_index, out->fuse_map, out->best_sim,
+    TTF_STEP(launch_window_search(p, features, ext_anchor, w, out->anchor_index, out->fuse_map, out->best_sim,
                                   out->best_idx, s));
     mark();
     TTF_STEP(launch_offsets_scan(p, w, out->anchor_index, out->kept_count, out->row_offsets, s));
     mark();
     TTF_STEP(launch_emit_rows(p, features, w, out->anchor_index, out->tokens_out, out->pos_ids,
-                              out->src_index, s));
+                              out->src_index, frame_offset, s));
     mark();                                                    // end of stage 5
     if (out->host_counts) {
         TTF_STEP(hipMemcpyAsync(out->host_counts, out->kept_count, sizeof(int32_t) * p.B,
@@ -147,6 +151,21 @@ ttf_status ttf_compress(const ttf_params* params, const void* features, void* wo
     }
     if (timing) ++prof.calls;
     return TTF_OK;
+}
+
+ttf_status ttf_compress(const ttf_params* params, const void* features, void* workspace,
+                        size_t workspace_bytes, const ttf_outputs* out, void* hip_stream)
+{
+    return run_pass(params, features, nullptr, 0, workspace, workspace_bytes, out, hip_stream);
+}
+
+ttf_status ttf_compress_segment(const ttf_params* params, const void* features, const void* anchor_frame,
+                                int32_t frame_offset, void* workspace, size_t workspace_bytes,
+                                const ttf_outputs* out, void* hip_stream)
+{
+    if (!anchor_frame) return TTF_ERR_INVALID_ARG;
+    if (params && (long long)frame_offset + params->F > 0x7fffffffll) return TTF_ERR_INVALID_ARG;
+    return run_pass(params, features, anchor_frame, frame_offset, workspace, workspace_bytes, out, hip_stream);
 }
 
 ttf_status ttf_restore_map(const ttf_params* params, const int32_t* fuse_map, const int32_t* row_offsets,
@@ -230,7 +249,7 @@ ttf_status ttf_regate(const ttf_params* params, const void* features, const floa
                                  out->fuse_map, s);
     if (e == hipSuccess) e = launch_offsets_scan(p, w, out->anchor_index, out->kept_count, out->row_offsets, s);
     if (e == hipSuccess)
-        e = launch_emit_rows(p, features, w, out->anchor_index, out->tokens_out, out->pos_ids, out->src_index, s);
+        e = launch_emit_rows(p, features, w, out->anchor_index, out->tokens_out, out->pos_ids, out->src_index, 0, s);
     if (e == hipSuccess && out->host_counts) {
         e = hipMemcpyAsync(out->host_counts, out->kept_count, sizeof(int32_t) * p.B, hipMemcpyDeviceToHost, s);
         if (e == hipSuccess)

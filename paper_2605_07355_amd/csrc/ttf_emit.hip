@@ -33,9 +33,9 @@ __global__ __launch_bounds__(1024) void k_offsets_scan(const uint64_t* __restric
         if (e < E) {
             b = (int)(e / (F + 1));
             s = (int)(e % (F + 1));
-            a = anchor_index[b];
+            a = anchor_index[b];                       // < 0: the anchor frame is not part of the clip
             if (s == 0) {
-                v = N;
+                v = a < 0 ? 0 : N;
             } else if (s - 1 != a) {
                 const uint64_t* kb = keep_bits + ((size_t)b * F + (s - 1)) * NW;
                 for (int q = 0; q < NW; ++q) v += __popcll(kb[q]);
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(1024) void k_offsets_scan(const uint64_t* __restric
         if (e < E) {
             if (s == 0) {
                 row_offsets[b] = excl;
-                frame_base[(size_t)b * F + a] = excl;
+                if (a >= 0) frame_base[(size_t)b * F + a] = excl;
             } else if (s - 1 != a) {
                 frame_base[(size_t)b * F + (s - 1)] = excl;
             }
@@ -79,7 +79,8 @@ __global__ __launch_bounds__(256) void k_emit_rows(const char* __restrict__ x,
                                                    char* __restrict__ tokens_out,
                                                    int32_t* __restrict__ pos_ids,
                                                    int32_t* __restrict__ src_index,
-                                                   int F, int N, int W, int NW, size_t row_bytes, size_t cap)
+                                                   int F, int N, int W, int NW, size_t row_bytes, size_t cap,
+                                                   int frame_offset)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int quarter = blockIdx.x & 3;
@@ -102,7 +103,7 @@ __global__ __launch_bounds__(256) void k_emit_rows(const char* __restrict__ x,
         const size_t row = (size_t)before + rank;
         copy_row<U>(x + (frame * (size_t)N + i) * row_bytes, tokens_out + row * row_bytes, row_bytes, lane);
         if (lane == 0) {
-            pos_ids[row] = k;
+            pos_ids[row] = k + frame_offset;
             pos_ids[cap + row] = i / W;
             pos_ids[2 * cap + row] = i % W;
             src_index[row] = k * N + i;
@@ -123,7 +124,7 @@ hipError_t launch_offsets_scan(const ttf_params& p, const Workspace& w, const in
 
 hipError_t launch_emit_rows(const ttf_params& p, const void* x, const Workspace& w,
                             const int32_t* anchor_index, void* tokens_out, int32_t* pos_ids,
-                            int32_t* src_index, hipStream_t s)
+                            int32_t* src_index, int frame_offset, hipStream_t s)
 {
     (void)anchor_index;
     const int N = p.H * p.W, NW = (N + 63) / 64;
@@ -134,13 +135,13 @@ hipError_t launch_emit_rows(const ttf_params& p, const void* x, const Workspace&
     char* out = static_cast<char*>(tokens_out);
     if (row_bytes % 16 == 0)
         k_emit_rows<16><<<grid, 256, 0, s>>>(xs, w.keep_bits, w.frame_base, out, pos_ids, src_index,
-                                             p.F, N, p.W, NW, row_bytes, cap);
+                                             p.F, N, p.W, NW, row_bytes, cap, frame_offset);
     else if (row_bytes % 4 == 0)
         k_emit_rows<4><<<grid, 256, 0, s>>>(xs, w.keep_bits, w.frame_base, out, pos_ids, src_index,
-                                            p.F, N, p.W, NW, row_bytes, cap);
+                                            p.F, N, p.W, NW, row_bytes, cap, frame_offset);
     else
         k_emit_rows<2><<<grid, 256, 0, s>>>(xs, w.keep_bits, w.frame_base, out, pos_ids, src_index,
-                                            p.F, N, p.W, NW, row_bytes, cap);
+                                            p.F, N, p.W, NW, row_bytes, cap, frame_offset);
     return hipGetLastError();
 }
 

@@ -55,22 +55,25 @@ inline Workspace carve(const ttf_params& p, void* base)
 // Stage launchers.  Each enqueues on `s` and returns the launch status.
 hipError_t launch_frame_sums(const ttf_params& p, const void* x, const Workspace& w, hipStream_t s);
 hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, hipStream_t s);
-hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const Workspace& w,
+// `ext_anchor` (here and below): nullptr when the anchor is a frame of x; otherwise the anchor
+// frames [B,N,C] of a segment, in which case anchor_index is written as -1 and every frame of x
+// is a source frame.
+hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                int32_t* anchor_index, hipStream_t s);
 // Matrix-core path: anchor choice, inverse norms, the anchor frame re-laid in fragment order, and
 // the anchor-frame rows of fuse_map / best_sim / best_idx / keep bits.
-hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const Workspace& w,
+hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                       int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                       int32_t* best_idx, hipStream_t s);
 bool mfma_search_supported(const ttf_params& p);
-hipError_t launch_window_search(const ttf_params& p, const void* x, const Workspace& w,
+hipError_t launch_window_search(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                 const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                 int32_t* best_idx, hipStream_t s);
 hipError_t launch_offsets_scan(const ttf_params& p, const Workspace& w, const int32_t* anchor_index,
                                int32_t* kept_count, int32_t* row_offsets, hipStream_t s);
 hipError_t launch_emit_rows(const ttf_params& p, const void* x, const Workspace& w,
                             const int32_t* anchor_index, void* tokens_out, int32_t* pos_ids,
-                            int32_t* src_index, hipStream_t s);
+                            int32_t* src_index, int frame_offset, hipStream_t s);
 
 // Restoration: map from every original token to the compressed row that stands for it, and the
 // gather that rebuilds the full layout.

@@ -21,7 +21,8 @@ constexpr float kNegInf = -__builtin_inff();
 
 template <typename T, int V>
 __global__ __launch_bounds__(1024) void k_search_generic(
-    const T* __restrict__ x, const int32_t* __restrict__ anchor_index, const float* __restrict__ anchor_inv,
+    const T* __restrict__ x, const T* __restrict__ ext_anchor, const int32_t* __restrict__ anchor_index,
+    const float* __restrict__ anchor_inv,
     int32_t* __restrict__ fuse_map, float* __restrict__ best_sim, int32_t* __restrict__ best_idx,
     uint64_t* __restrict__ keep_bits, int F, int H, int W, int C, int r, float t, int NW)
 {
@@ -30,12 +31,12 @@ __global__ __launch_bounds__(1024) void k_search_generic(
     const int word = blockIdx.x % NW;                 // 64-token group inside the frame
     const size_t frame = blockIdx.x / NW;             // b*F + k
     const int b = (int)(frame / F), k = (int)(frame % F);
-    const int a = anchor_index[b];
+    const int a = anchor_index[b];                    // < 0: the anchor frames are in ext_anchor [B,N,C]
     __shared__ unsigned long long keep_word;
     if (threadIdx.x == 0) keep_word = 0ull;
     __syncthreads();
 
-    const T* anchor = x + ((size_t)b * F + a) * (size_t)N * C;
+    const T* anchor = a < 0 ? ext_anchor + (size_t)b * N * C : x + ((size_t)b * F + a) * (size_t)N * C;
     const float* ainv = anchor_inv + (size_t)b * N;
 
     for (int q = 0; q < 4; ++q) {
@@ -112,7 +113,7 @@ __global__ __launch_bounds__(1024) void k_search_generic(
 
 }  // namespace
 
-hipError_t launch_window_search_generic(const ttf_params& p, const void* x, const Workspace& w,
+hipError_t launch_window_search_generic(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                         const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                         int32_t* best_idx, hipStream_t s)
 {
@@ -121,7 +122,8 @@ hipError_t launch_window_search_generic(const ttf_params& p, const void* x, cons
     auto go = [&](auto tag, auto vtag) {
         using T = decltype(tag);
         constexpr int V = decltype(vtag)::value;
-        k_search_generic<T, V><<<grid, 1024, 0, s>>>(static_cast<const T*>(x), anchor_index, w.anchor_inv,
+        k_search_generic<T, V><<<grid, 1024, 0, s>>>(static_cast<const T*>(x), static_cast<const T*>(ext_anchor),
+                                                    anchor_index, w.anchor_inv,
                                                     fuse_map, best_sim, best_idx, w.keep_bits,
                                                     p.F, p.H, p.W, p.C, p.r, p.t, NW);
         return hipGetLastError();

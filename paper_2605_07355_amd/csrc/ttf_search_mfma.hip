@@ -178,14 +178,15 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
     const int tp = blockIdx.x % tpf;
     const int grp = (blockIdx.x / tpf) % groups;
     const int b = blockIdx.x / tpf / groups;
-    const int a = anchor_index[b];
+    const int a_in = anchor_index[b];                        // < 0: the anchor frame lies outside x (segment mode)
+    const int a = a_in < 0 ? F : a_in;                       // then no frame of x is skipped
     const int i0 = tp * 32;                                  // first grid cell of this workgroup
 
     const int y0 = i0 / W;                                   // first (or only) source row
     const int ylo = y0 - RAD;
     const int slice = C / NW;                                // channels per wave
     const int KS = C / 32;                                   // K-steps per token
-    const int nsrc = F - 1;                                  // source frames of the clip (>= 1 here)
+    const int nsrc = a_in < 0 ? F : F - 1;                   // source frames of the clip (>= 1 here)
 
     // source frame of slot f: the f-th source frame of this group, the last one repeated past the end
     const uint16_t* sp[NS];                                  // load order: lane -> token lane/4, chunk lane%4
@@ -325,14 +326,16 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
 }
 
 template <int CT, int RAD>
-hipError_t launch_shape(const ttf_params& p, const void* x, const Workspace& w, const int32_t* anchor_index,
-                        int32_t* fuse_map, float* best_sim, int32_t* best_idx, hipStream_t s)
+hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,
+                        const int32_t* anchor_index, int32_t* fuse_map, float* best_sim, int32_t* best_idx,
+                        hipStream_t s)
 {
     using S = Shape<CT, RAD>;
-    if (p.F < 2) return hipSuccess;                          // no source frame: the anchor rows are all there is
+    const int nsrc = external_anchor ? p.F : p.F - 1;        // source frames per clip
+    if (nsrc < 1) return hipSuccess;                         // no source frame: the anchor rows are all there is
     const uint16_t* xs = static_cast<const uint16_t*>(x);
     const int N = p.H * p.W;
-    const int groups = (p.F - 1 + S::FR - 1) / S::FR;        // groups of source frames per clip
+    const int groups = (nsrc + S::FR - 1) / S::FR;           // groups of source frames per clip
     const size_t blocks = (size_t)p.B * groups * (N / 32);
     const unsigned grid = (unsigned)blocks;
     const int ks_total = p.C / 32;                           // K-steps per token
@@ -365,12 +368,13 @@ bool mfma_search_supported(const ttf_params& p)
     return false;
 }
 
-hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, const Workspace& w,
+hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,
                                      const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                      int32_t* best_idx, hipStream_t s)
 {
-#define TTF_CASE(CT, RAD) \
-    if (p.W == 16 * CT && p.r == RAD) return launch_shape<CT, RAD>(p, x, w, anchor_index, fuse_map, best_sim, best_idx, s)
+#define TTF_CASE(CT, RAD)             \
+    if (p.W == 16 * CT && p.r == RAD) \
+    return launch_shape<CT, RAD>(p, x, external_anchor, w, anchor_index, fuse_map, best_sim, best_idx, s)
     TTF_CASE(1, 0);
     TTF_CASE(1, 1);
     TTF_CASE(1, 2);

@@ -224,3 +224,133 @@ def test_new_entry_points_reject_bad_arguments():
     assert lib.ttf_regate(ctypes.byref(p), q, None, q, 1 << 20, ctypes.byref(o), None) == bd.TTF_ERR_INVALID_ARG
     torch.cuda.synchronize()
     assert int(buf.abs().sum()) == 0
+
+
+# ------------------------------------------------------------------------ streaming segments
+def _segment_case(cfg, t, anchor_override=None):
+    """A clip of cfg.F frames whose frame 0 plays the external anchor (or is replaced by
+    `anchor_override` [B,H,W,C]); margins enforced against that anchor."""
+    from oracle import margins
+    for attempt in range(4):
+        batch = make_clip_batch(cfg, seed=cfg.seed + 1000 * attempt)
+        if anchor_override is not None:
+            batch.x[:, 0] = anchor_override
+        try:
+            margins.enforce_margins(batch, cfg.r, (t,), ANCHOR_FIXED, 0, want_tokens=False)
+            return batch
+        except margins.MarginError:
+            continue
+    raise RuntimeError("no seed met the margins")
+
+
+def _run_segment(seg_np, anchor_np, frame_offset, r, t):
+    import paper_2605_07355_amd as ttf
+    x, a = to_device(np.ascontiguousarray(seg_np)), to_device(np.ascontiguousarray(anchor_np))
+    B, F, H, W, C = x.shape
+    buf = ttf.TTFBuffers.allocate(B, F, H, W, C, x.dtype, x.device)
+    buf.tokens_out.view(torch.uint8).fill_(0x7A)
+    for tns in (buf.pos_ids, buf.src_index, buf.row_offsets, buf.kept_count, buf.anchor_index, buf.fuse_map,
+                buf.best_idx):
+        tns.fill_(SENTINEL)
+    buf.best_sim.fill_(float("nan"))
+    buf.workspace.fill_(0xCD)
+    out = ttf.ttf_compress_segment(x, a, frame_offset, r=r, t=t, buffers=buf)
+    torch.cuda.synchronize()
+    return out
+
+
+def _compare_segment(seg_np, out, want):
+    """Segment outputs against the oracle's SegmentResult (same bar as the whole pass)."""
+    from types import SimpleNamespace
+    B = seg_np.shape[0]
+    shim = SimpleNamespace(anchor_index=np.full(B, -1, np.int32), fuse_map=want.fuse_map, kept_count=want.kept_count,
+                           row_offsets=want.row_offsets, src_index=want.src_index, pos_ids=want.pos_ids,
+                           best_idx=want.best_idx, best_sim=want.best_sim, total_rows=want.total_rows)
+    compare_with_oracle(seg_np, out, shim)
+
+
+SEGMENTS = [
+    ("tiny", {}, 1),
+    ("qwen3vl_2b", dict(B=2, F=6), 1),                                 # matrix-core path, 5 source frames
+    ("qwen3vl_2b", dict(B=1, F=2), 1),                                 # one-frame segment
+    ("qwen3vl_2b", dict(B=2, F=10, C=256), 2),                         # more frames than one workgroup group
+    ("highres_wide", dict(B=1, F=4, H=8, C=128), 2),                   # 32-wide grid
+    ("tiny", dict(B=3, F=5, H=7, W=9, C=40, dtype="f32"), 1),          # general kernels, ragged keep words
+    ("tiny", dict(B=2, F=3, H=5, W=13, C=129, dtype="bf16"), 3),
+]
+
+
+@pytest.mark.parametrize("name,scale,r", SEGMENTS)
+def test_segment_against_external_anchor(name, scale, r):
+    from oracle import streaming as S
+    cfg = CONFIGS[name].scaled(**{**scale, "r": r})
+    t = cfg.t[0]
+    batch = _segment_case(cfg, t)
+    anchor, seg = batch.x[:, 0], batch.x[:, 1:]
+    want = S.compress_segment(seg, anchor, r, t, frame_offset=40)
+    out = _run_segment(seg, anchor, 40, r, t)
+    _compare_segment(np.ascontiguousarray(seg), out, want)
+    assert 0 < (want.fuse_map >= 0).mean() < 1
+
+
+def test_segment_at_headline_size():
+    """31 source frames per clip of the headline workload against its first frame."""
+    from oracle import streaming as S
+    cfg = CONFIGS["qwen3vl_8b_batched"]
+    t = cfg.t[0]
+    batch = _segment_case(cfg, t)
+    anchor, seg = batch.x[:, 0], np.ascontiguousarray(batch.x[:, 1:])
+    want = S.compress_segment(seg, anchor, cfg.r, t, frame_offset=1)
+    out = _run_segment(seg, anchor, 1, cfg.r, t)
+    _compare_segment(seg, out, want)
+
+
+def test_rolling_anchor_chain():
+    """Two segments of one stream: the second is matched against the last frame of the first, and
+    the appended rows carry stream-wide frame numbers."""
+    from oracle import streaming as S
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=2, F=5, C=512)
+    t = cfg.t[0]
+    first = _segment_case(cfg, t)
+    second = _segment_case(cfg, t, anchor_override=first.x[:, -1])
+    stream_rows = 0
+    anchor = first.x[:, 0]
+    for n, batch in enumerate((first, second)):
+        seg = np.ascontiguousarray(batch.x[:, 1:])
+        off = 1 + n * (cfg.F - 1)
+        want = S.compress_segment(seg, anchor, cfg.r, t, frame_offset=off)
+        out = _run_segment(seg, anchor, off, cfg.r, t)
+        _compare_segment(seg, out, want)
+        pos = out.buffers.pos_ids[0, :want.total_rows]
+        assert int(pos.min()) >= off and int(pos.max()) < off + cfg.F - 1
+        stream_rows += want.total_rows
+        anchor = seg[:, -1]                                            # rolling anchor for the next segment
+    assert 0 < stream_rows < 2 * cfg.B * (cfg.F - 1) * cfg.H * cfg.W
+
+
+def test_static_stream_appends_nothing():
+    import paper_2605_07355_amd as ttf
+    from workloads.ttf_gen import identical_frames, f32_to_bf16_bits
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=2, F=4, C=256)
+    x = f32_to_bf16_bits(identical_frames(cfg, seed=5))
+    out = _run_segment(x[:, 1:], x[:, 0], 1, 1, 0.9)
+    assert out.total_rows == 0
+    np.testing.assert_array_equal(out.buffers.kept_count.cpu().numpy(), [0, 0])
+    np.testing.assert_array_equal(out.buffers.anchor_index.cpu().numpy(), [-1, -1])
+    fm = out.buffers.fuse_map.cpu().numpy()
+    np.testing.assert_array_equal(fm, np.broadcast_to(np.arange(cfg.H * cfg.W), fm.shape))
+
+
+def test_segment_rejects_bad_arguments():
+    import paper_2605_07355_amd as ttf
+    from paper_2605_07355_amd import binding as bd
+    lib = ttf.load_library()
+    p = bd._make_params(1, 2, 2, 2, 8, bd.TTF_F32, 1, 0.7, "auto")
+    buf = torch.zeros(4096, dtype=torch.int32, device="cuda")
+    q = buf.data_ptr()
+    o = bd._Outputs(q, q, q, q, q, q, q, None, None, None)
+    assert lib.ttf_compress_segment(ctypes.byref(p), q, None, 0, q, 1 << 20, ctypes.byref(o), None) == bd.TTF_ERR_INVALID_ARG
+    assert lib.ttf_compress_segment(ctypes.byref(p), q, q + 4, 0, q, 1 << 20, ctypes.byref(o), None) == bd.TTF_ERR_UNSUPPORTED
+    assert lib.ttf_compress_segment(ctypes.byref(p), q, q, 2 ** 31 - 2, q, 1 << 20, ctypes.byref(o), None) == bd.TTF_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert int(buf.abs().sum()) == 0
