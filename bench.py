@@ -54,6 +54,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="qwen3vl_8b_batched")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extensions", action="store_true",
+                    help="skip the timings of restoration, adaptive threshold and streaming segments")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; clips shard across GPUs with no communication, "
@@ -167,6 +169,58 @@ def main() -> int:
         "reduction_ratio": round(1.0 - kappa, 4),
     }
 
+    # The entry points built on top of the pass, timed with events on the same stream.  Each
+    # figure is the mean of `reps` back-to-back calls; GB/s counts algorithmic bytes only.
+    extensions = None
+    if not args.no_extensions:
+        reps = 10
+
+        def timed(fn):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                fn()
+            e1.record(stream)
+            e1.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        def entry(ms, nbytes, **kw):
+            return {"ms": round(ms, 4), "algorithmic_bytes": int(nbytes),
+                    "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                    "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), **kw}
+
+        out = ttf.TTFOutput(buf, cfg.B, cfg.F, cfg.H, cfg.W, cfg.C)
+        rmap = torch.empty((cfg.B, cfg.F, cfg.N), dtype=torch.int32, device=dev)
+        full = torch.empty_like(x)
+        extensions = {}
+        ms = timed(lambda: ttf.ttf_restore_map(out, rmap))
+        extensions["restore_map"] = entry(ms, 8 * tokens + 4 * rows)            # fuse_map in, map out, src_index in
+        ms = timed(lambda: ttf.ttf_restore(buf.tokens_out, rows, rmap, cfg.H, cfg.W, full))
+        extensions["restore"] = entry(ms, (tokens + rows) * row_bytes + 4 * tokens)   # unique rows in, full layout out
+        del full
+        thr = torch.empty((cfg.B,), dtype=torch.float32, device=dev)
+        ms = timed(lambda: ttf.ttf_select_threshold(out, 0.67, thr))
+        extensions["select_threshold"] = entry(ms, 4 * tokens, fused_fraction_requested=0.67)
+        ms = timed(lambda: ttf.ttf_regate(x, out, thr))
+        rows_rg = int(buf.kept_count.sum().item())
+        extensions["regate"] = entry(ms, 12 * tokens + rows_rg * (2 * row_bytes + 16), rows=rows_rg)
+        # one stream segment: frames 1..F-1 of every clip against frame 0 as the rolling anchor
+        if cfg.F > 1:
+            seg = x[:, 1:].contiguous()
+            anc = x[:, 0].contiguous()
+            sbuf = ttf.TTFBuffers.allocate(cfg.B, cfg.F - 1, cfg.H, cfg.W, cfg.C, x.dtype, dev, want_sim=True)
+            ms = timed(lambda: ttf.ttf_compress_segment(seg, anc, 1, r=r, t=t, buffers=sbuf))
+            seg_tokens = cfg.B * (cfg.F - 1) * cfg.N
+            seg_rows = int(sbuf.kept_count.sum().item())
+            nbytes = seg_tokens * (row_bytes + 12) + cfg.B * cfg.N * row_bytes + seg_rows * (2 * row_bytes + 16)
+            extensions["compress_segment"] = entry(ms, nbytes, source_tokens=seg_tokens, rows=seg_rows,
+                                                   GTok_per_s=round(seg_tokens / (ms * 1e-3) / 1e9, 4))
+            del seg, anc, sbuf
+        ttf.ttf_compress(x, r=r, t=t, anchor="auto", buffers=buf, stream=stream)   # leave buf as the pass wrote it
+        torch.cuda.synchronize()
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         from oracle import ttf_oracle as orc
@@ -191,7 +245,7 @@ def main() -> int:
         "config": {"workload": cfg.name, "B": cfg.B, "F": cfg.F, "H": cfg.H, "W": cfg.W, "C": cfg.C,
                    "r": r, "t": t, "anchor": "auto", "tokens": tokens, "input_bytes": tokens * row_bytes,
                    "inputs": "resident in HBM before the timed region"},
-        "roofline": roofline, "path": path, "cpu_baseline": cpu_baseline,
+        "roofline": roofline, "path": path, "cpu_baseline": cpu_baseline, "extensions": extensions,
         "context": "paper reports ~67% of tokens removed at t=0.70 and ~0.16 GFLOPs matching cost on an "
                    "A100 40GB; no timing of the pass itself",
     }

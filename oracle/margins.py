@@ -71,3 +71,31 @@ def enforce_margins(batch, r: int, ts: Sequence[float], anchor_mode: int = orc.A
     if anchor_mode == orc.ANCHOR_AUTO and anchor_gap(final) < gap:
         raise MarginError(f"anchor score gap {anchor_gap(final):.3g} below {gap:g}")
     return final
+
+
+def enforce_tied_margins(batch, r: int, ts: Sequence[float], anchor_mode: int = orc.ANCHOR_AUTO,
+                         anchor_index: int = 0, sim_margin: float = 1e-3, top2_margin: float = 1e-4,
+                         gap: float = 1e-4, max_rounds: int = 8, want_tokens: bool = True):
+    """Tied-batch counterpart of enforce_margins: a source position is redrawn (in every batch
+    element) while its two best batch-mean similarities are closer than ``top2_margin`` or any
+    element's similarity at the shared offset is within ``sim_margin`` of a threshold.  Returns
+    the final TiedResult for ts[0]."""
+    B = batch.x.shape[0]
+    for rounds in range(max_rounds + 1):
+        res = orc.compress_tied(batch.x, r, ts[0], anchor_mode, anchor_index, want_tokens=False)
+        F, N = res.fuse_map.shape
+        bad = (res.mean_sim - res.second_mean) < top2_margin
+        for t in ts:
+            bad |= (np.abs(res.best_sim - float(np.float32(t))) < sim_margin).any(axis=0)
+        bad[res.anchor_index] = False
+        todo = np.argwhere(bad)
+        if len(todo) == 0:
+            break
+        if rounds == max_rounds:
+            raise MarginError(f"{len(todo)} positions still inside the margins after {rounds} rounds")
+        batch.redraw([(b, int(k), int(i)) for (k, i) in todo for b in range(B)], batch.redraw_rounds)
+    if anchor_mode == orc.ANCHOR_AUTO and F > 1:
+        s = np.sort(res.anchor_score)
+        if s[-1] - s[-2] < gap:
+            raise MarginError(f"anchor score gap {s[-1] - s[-2]:.3g} below {gap:g}")
+    return orc.compress_tied(batch.x, r, ts[0], anchor_mode, anchor_index, want_tokens=want_tokens)

@@ -10,7 +10,7 @@
  * Every clip of the batch is an independent instance of the paper's single-clip problem
  * (own anchor, own matches, own mask, own compressed length); for one clip this is exactly
  * Section 3.  The paper's tied-batch rule (one offset from the batch-mean similarity, keep
- * as a union over the batch) is a different mode and is not implemented here.
+ * as a union over the batch) is a different mode: ttf_oracle_compress_tied at the end.
  *
  * Readings taken where the text leaves a choice (all stated with the function they affect):
  *   - search window is (2r+1) x (2r+1)  (Section 3 "Pointwise Matching"; the introduction's
@@ -303,5 +303,152 @@ int ttf_oracle_match_tokens(const void *x, int dtype, int B, int F, int H, int W
         }
         free(stamp);
     }
+    return 0;
+}
+
+/*
+ * Tied-batch mode (Section 3, the remark after the s^/dst equations and the wording of the
+ * gating paragraph): for B > 1 one offset is chosen per source position (k,i) by maximising
+ * the MEAN similarity over the batch elements, every element reads its own s^ at that offset,
+ * and the position is preserved if ANY element has s^ <= t (the keep masks are united), so all
+ * elements keep the same index set and the output is rectangular [B, N+P, C].
+ *
+ * Readings (the text does not spell these out):
+ *   - the anchor frame is shared: with the automatic rule it is the frame whose anchor score,
+ *     averaged over the batch elements, is largest (lowest k on ties); a fixed frame otherwise;
+ *   - the mean is the plain arithmetic mean of the B cosines of one candidate cell, summed in
+ *     ascending b; candidates are the distinct clamped cells in row-major offset order and the
+ *     first maximum wins, exactly as in the single-clip search.
+ *
+ *   anchor_index  [1]         shared anchor frame
+ *   anchor_score  [F]         batch-mean anchor score per frame (0 when FIXED)
+ *   mean_sim      [F,N]       largest batch-mean similarity; 1.0 on anchor rows
+ *   second_mean   [F,N]       runner-up batch-mean similarity (-inf if none)
+ *   best_sim      [B,F,N]     s^ of every element at the shared offset; 1.0 on anchor rows
+ *   best_idx      [F,N]       shared dst(k,i); i on anchor rows
+ *   fuse_map      [F,N]       dst(k,i) if every element has s^ > t, else -1
+ *   kept_count    [1]         L' = N + P
+ *   src_index     [F*N]       flat k*N+i of every output row
+ *   pos_ids       [3, F*N]    planes k, y, x
+ *   tokens_out    [B, F*N, C] rows of every element, first L' valid; or NULL
+ */
+int ttf_oracle_compress_tied(const void *x, int dtype, int B, int F, int H, int W, int C,
+                             int r, float t, int anchor_mode, int anchor_fixed,
+                             int32_t *anchor_index, double *anchor_score,
+                             double *mean_sim, double *second_mean, double *best_sim,
+                             int32_t *best_idx, int32_t *fuse_map, int32_t *kept_count,
+                             int32_t *src_index, int32_t *pos_ids, void *tokens_out)
+{
+    if (B < 1 || F < 1 || H < 1 || W < 1 || C < 1 || r < 0)
+        return 1;
+    if (dtype != ORACLE_BF16 && dtype != ORACLE_F32)
+        return 1;
+    if (anchor_mode == ORACLE_ANCHOR_FIXED && (anchor_fixed < -F || anchor_fixed >= F))
+        return 1;
+    const int N = H * W;
+    const size_t esz = dtype == ORACLE_F32 ? 4 : 2;
+    const size_t clip_elems = (size_t)F * N * C;
+    const size_t cap = (size_t)F * N;
+    const double thr = (double)t;
+
+    int a;
+    for (int k = 0; k < F; ++k)
+        anchor_score[k] = 0.0;
+    if (anchor_mode == ORACLE_ANCHOR_FIXED) {
+        a = anchor_fixed < 0 ? anchor_fixed + F : anchor_fixed;
+    } else {
+        double *score = (double *)calloc((size_t)F, sizeof(double));
+        for (int b = 0; b < B; ++b) {
+            select_anchor((const char *)x + (size_t)b * clip_elems * esz, dtype, F, N, C, score);
+            for (int k = 0; k < F; ++k)
+                anchor_score[k] += score[k];
+        }
+        free(score);
+        a = 0;
+        for (int k = 0; k < F; ++k) {
+            anchor_score[k] /= (double)B;
+            if (anchor_score[k] > anchor_score[a])
+                a = k;
+        }
+    }
+    anchor_index[0] = a;
+
+#pragma omp parallel
+    {
+        int32_t *stamp = (int32_t *)calloc((size_t)N, sizeof(int32_t));
+#pragma omp for schedule(dynamic, 16)
+        for (int ki = 0; ki < F * N; ++ki) {
+            const int k = ki / N, i = ki % N;
+            if (k == a) {
+                mean_sim[ki] = 1.0;
+                second_mean[ki] = -INFINITY;
+                best_idx[ki] = i;
+                fuse_map[ki] = -1;
+                for (int b = 0; b < B; ++b)
+                    best_sim[(size_t)b * F * N + ki] = 1.0;
+                continue;
+            }
+            const int yi = i / W, xi = i % W;
+            double m_hat = -INFINITY, m_2nd = -INFINITY;
+            int32_t j_hat = -1;
+            const int32_t tag = ki + 1;
+            for (int dy = -r; dy <= r; ++dy) {
+                for (int dx = -r; dx <= r; ++dx) {
+                    int j = proj(yi + dy, 0, H - 1) * W + proj(xi + dx, 0, W - 1);
+                    if (stamp[j] == tag)
+                        continue;             /* duplicate of an earlier offset: masked */
+                    stamp[j] = tag;
+                    double sum = 0.0;
+                    for (int b = 0; b < B; ++b)
+                        sum += cosine_rows((const char *)x + (size_t)b * clip_elems * esz, dtype,
+                                           (size_t)k * N + i, (size_t)a * N + j, C);
+                    double m = sum / (double)B;
+                    if (m > m_hat) {
+                        m_2nd = m_hat;
+                        m_hat = m;
+                        j_hat = j;
+                    } else if (m > m_2nd) {
+                        m_2nd = m;
+                    }
+                }
+            }
+            mean_sim[ki] = m_hat;
+            second_mean[ki] = m_2nd;
+            best_idx[ki] = j_hat;
+            int all_above = 1;
+            for (int b = 0; b < B; ++b) {
+                double s = cosine_rows((const char *)x + (size_t)b * clip_elems * esz, dtype,
+                                       (size_t)k * N + i, (size_t)a * N + j_hat, C);
+                best_sim[(size_t)b * F * N + ki] = s;
+                if (!(s > thr))
+                    all_above = 0;            /* this element keeps the position: union of keeps */
+            }
+            fuse_map[ki] = all_above ? j_hat : -1;
+        }
+        free(stamp);
+    }
+
+    size_t row = 0;
+    for (int pass = 0; pass < 2; ++pass) {
+        for (int k = 0; k < F; ++k) {
+            if ((pass == 0) != (k == a))
+                continue;
+            for (int i = 0; i < N; ++i) {
+                const size_t o = (size_t)k * N + i;
+                if (k != a && fuse_map[o] >= 0)
+                    continue;
+                src_index[row] = k * N + i;
+                pos_ids[0 * cap + row] = k;
+                pos_ids[1 * cap + row] = i / W;
+                pos_ids[2 * cap + row] = i % W;
+                if (tokens_out)
+                    for (int b = 0; b < B; ++b)
+                        memcpy((char *)tokens_out + ((size_t)b * cap + row) * (size_t)C * esz,
+                               (const char *)x + ((size_t)b * cap + o) * (size_t)C * esz, (size_t)C * esz);
+                ++row;
+            }
+        }
+    }
+    kept_count[0] = (int32_t)row;
     return 0;
 }

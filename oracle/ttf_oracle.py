@@ -46,6 +46,9 @@ def _load() -> ctypes.CDLL:
         lib.ttf_oracle_compress.restype = ci
         lib.ttf_oracle_compress.argtypes = [vp, ci, ci, ci, ci, ci, ci, ci, ctypes.c_float, ci, ci,
                                             ip, dp, dp, dp, ip, ip, ip, ip, ip, ip, ip, vp]
+        lib.ttf_oracle_compress_tied.restype = ci
+        lib.ttf_oracle_compress_tied.argtypes = [vp, ci, ci, ci, ci, ci, ci, ci, ctypes.c_float, ci, ci,
+                                                 ip, dp, dp, dp, dp, ip, ip, ip, ip, ip, vp]
         lib.ttf_oracle_match_tokens.restype = ci
         lib.ttf_oracle_match_tokens.argtypes = [vp, ci, ci, ci, ci, ci, ci, ci, ip, ip, ci, dp, dp, ip]
         _lib = lib
@@ -145,3 +148,45 @@ def match_tokens(x: np.ndarray, r: int, anchor_index: Sequence[int], tokens: np.
     if rc != 0:
         raise ValueError("ttf_oracle_match_tokens rejected its arguments")
     return best, second, idx
+
+
+@dataclass
+class TiedResult:
+    anchor_index: int          # shared anchor frame
+    anchor_score: np.ndarray   # [F]      batch-mean anchor score
+    mean_sim: np.ndarray       # [F,N]    largest batch-mean similarity
+    second_mean: np.ndarray    # [F,N]    runner-up batch-mean similarity
+    best_sim: np.ndarray       # [B,F,N]  per-element s^ at the shared offset
+    best_idx: np.ndarray       # [F,N]    shared dst
+    fuse_map: np.ndarray       # [F,N]
+    kept_count: int            # L'
+    src_index: np.ndarray      # [F*N]
+    pos_ids: np.ndarray        # [3,F*N]
+    tokens_out: Optional[np.ndarray]   # [B,F*N,C]
+
+
+def compress_tied(x: np.ndarray, r: int, t: float, anchor_mode: int = ANCHOR_AUTO,
+                  anchor_index: int = 0, want_tokens: bool = True) -> TiedResult:
+    """The tied-batch pass on ``x`` [B,F,H,W,C]: one offset per position from the batch-mean
+    similarity, keep masks united over the batch, rectangular output."""
+    x = np.ascontiguousarray(x)
+    B, F, H, W, C = (int(v) for v in x.shape)
+    N = H * W
+    a = np.zeros(1, np.int32)
+    kept = np.zeros(1, np.int32)
+    res = TiedResult(
+        anchor_index=0, anchor_score=np.zeros(F, np.float64), mean_sim=np.zeros((F, N), np.float64),
+        second_mean=np.zeros((F, N), np.float64), best_sim=np.zeros((B, F, N), np.float64),
+        best_idx=np.zeros((F, N), np.int32), fuse_map=np.zeros((F, N), np.int32), kept_count=0,
+        src_index=np.full(F * N, -1, np.int32), pos_ids=np.full((3, F * N), -1, np.int32),
+        tokens_out=np.zeros((B, F * N, C), x.dtype) if want_tokens else None)
+    rc = _load().ttf_oracle_compress_tied(
+        x.ctypes.data, _dtype_code(x), B, F, H, W, C, int(r), float(np.float32(t)),
+        int(anchor_mode), int(anchor_index), _ip(a), _dp(res.anchor_score), _dp(res.mean_sim),
+        _dp(res.second_mean), _dp(res.best_sim), _ip(res.best_idx), _ip(res.fuse_map), _ip(kept),
+        _ip(res.src_index), _ip(res.pos_ids), res.tokens_out.ctypes.data if want_tokens else None)
+    if rc != 0:
+        raise ValueError("ttf_oracle_compress_tied rejected its arguments")
+    res.anchor_index = int(a[0])
+    res.kept_count = int(kept[0])
+    return res

@@ -46,10 +46,21 @@ __global__ __launch_bounds__(1024) void k_select_threshold(const float* __restri
         if (threadIdx.x < 256) hist[threadIdx.x] = 0u;
         __syncthreads();
         const uint32_t prefix = s_prefix;
-        for (long long j = threadIdx.x; j < FN; j += 1024) {
-            if (j >= skip_lo && j < skip_hi) continue;
-            const uint32_t key = order_key(sim[j]);
-            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        // eight independent loads in flight per thread before their counts are added
+        for (long long j0 = threadIdx.x; j0 < FN; j0 += 8 * 1024) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const long long j = j0 + 1024 * u;
+                v[u] = j < FN ? sim[j] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const long long j = j0 + 1024 * u;
+                const uint32_t key = order_key(v[u]);
+                if (j < FN && (j < skip_lo || j >= skip_hi) && (key & mask) == prefix)
+                    atomicAdd(&hist[(key >> shift) & 255u], 1u);
+            }
         }
         __syncthreads();
         if (threadIdx.x == 0) {                     // 256 bins: a serial walk is short next to the counting pass

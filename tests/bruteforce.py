@@ -56,3 +56,34 @@ def ttf_clip(clip: np.ndarray, H: int, W: int, r: int, t: float, anchor=None):
     pos = np.stack([src_index // N, (src_index % N) // W, (src_index % N) % W], axis=1)
     return dict(anchor=a, scores=scores, best_sim=best_sim, best_idx=best_idx, fuse_map=fuse,
                 src_index=src_index, pos=pos)
+
+
+def ttf_tied(x: np.ndarray, H: int, W: int, r: int, t: float, anchor=None):
+    """Tied-batch pass, x [B,F,N,C] float64: per candidate cell the mean over the batch of the
+    cosines, arg max of the mean inside the window, every element's own cosine at that cell, and a
+    position fused only if all elements exceed t.  Returns a dict like ttf_clip's."""
+    B, F, N, C = x.shape
+    scores = np.mean([anchor_scores(x[b]) for b in range(B)], axis=0)
+    a = int(np.argmax(scores)) if anchor is None else int(anchor) % F
+    mask = window_mask(H, W, r)
+    thr = float(np.float32(t))
+    mean_sim = np.ones((F, N))
+    best_idx = np.tile(np.arange(N), (F, 1))
+    best_sim = np.ones((B, F, N))
+    fuse = np.full((F, N), -1, dtype=np.int64)
+    for k in range(F):
+        if k == a:
+            continue
+        s = np.stack([cos_matrix(x[b, k], x[b, a]) for b in range(B)])          # [B,N,N]
+        m = np.where(mask, s.sum(axis=0) / B, -np.inf)
+        best_idx[k] = np.argmax(m, axis=1)
+        mean_sim[k] = m[np.arange(N), best_idx[k]]
+        best_sim[:, k] = s[:, np.arange(N), best_idx[k]]
+        fused = np.all(best_sim[:, k] > thr, axis=0)
+        fuse[k] = np.where(fused, best_idx[k], -1)
+    keep = fuse < 0
+    keep[a] = False
+    src_index = np.concatenate([a * N + np.arange(N), np.flatnonzero(keep.reshape(-1))])
+    pos = np.stack([src_index // N, (src_index % N) // W, (src_index % N) % W], axis=1)
+    return dict(anchor=a, scores=scores, mean_sim=mean_sim, best_sim=best_sim, best_idx=best_idx,
+                fuse_map=fuse, src_index=src_index, pos=pos)

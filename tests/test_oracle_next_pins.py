@@ -264,3 +264,103 @@ def test_one_frame_segments_with_rolling_anchor_are_frame_differencing(oracle):
         ref = ttf_clip(x64[0, k - 1:k + 1], H, W, 1, 0.6, anchor=0)
         np.testing.assert_array_equal(res.fuse_map[0, 0], ref["fuse_map"][1])
         assert np.all(res.pos_ids[0, :res.total_rows] == k)
+
+
+# ------------------------------------------------------------------------------ tied batch
+def _tied_cfg(**kw):
+    return CONFIGS["qwen3vl_2b"].scaled(**{**dict(B=3, F=5, H=5, W=6, C=24, dtype="f32", seed=41,
+                                                   shared_motion=True), **kw})
+
+
+def test_tied_hand_example(oracle):
+    with open(os.path.join(GOLD, "hand_example_tied.txt")) as fh:
+        rows = [[float(v) for v in ln.split()] for ln in fh if ln.strip() and not ln.startswith("#")]
+    e0 = [[[1, 0], [0, 1], [4, 3]], [[3, 4], [0, 2], [-1, 0]]]
+    e1 = [[[1, 0], [0, 1], [3, 4]], [[1, 0], [3, 4], [0, -1]]]
+    x = np.array([e0, e1], dtype=np.float32).reshape(2, 2, 1, 3, 2)
+    res = oracle.compress_tied(x, 1, 0.70, 1, 0)
+    for tok, dst, mean, s0, s1, fused in rows:
+        tok = int(tok)
+        assert res.best_idx[1, tok] == int(dst)
+        assert res.mean_sim[1, tok] == pytest.approx(mean, abs=1e-15)
+        assert res.best_sim[0, 1, tok] == pytest.approx(s0, abs=1e-15)
+        assert res.best_sim[1, 1, tok] == pytest.approx(s1, abs=1e-15)
+        assert res.fuse_map[1, tok] == (int(dst) if fused else -1)
+    assert res.kept_count == 5
+    np.testing.assert_array_equal(res.src_index[:5], [0, 1, 2, 3, 5])
+    np.testing.assert_array_equal(res.pos_ids[:, :5], [[0, 0, 0, 1, 1], [0] * 5, [0, 1, 2, 0, 2]])
+    np.testing.assert_array_equal(res.tokens_out[0, :5], [[1, 0], [0, 1], [4, 3], [3, 4], [-1, 0]])
+    np.testing.assert_array_equal(res.tokens_out[1, :5], [[1, 0], [0, 1], [3, 4], [1, 0], [0, -1]])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("r", [0, 1, 2])
+def test_tied_matches_bruteforce(oracle, dtype, r):
+    from bruteforce import ttf_tied
+    cfg = _tied_cfg(dtype=dtype)
+    x = make_clip_batch(cfg).x
+    B, F, H, W, C = x.shape
+    N = H * W
+    t = 0.55
+    res = oracle.compress_tied(x, r, t)
+    ref = ttf_tied(_as_f64(x).reshape(B, F, N, C), H, W, r, t)
+    assert res.anchor_index == ref["anchor"]
+    np.testing.assert_allclose(res.anchor_score, ref["scores"], rtol=0, atol=1e-12)
+    np.testing.assert_array_equal(res.best_idx, ref["best_idx"])
+    np.testing.assert_allclose(res.mean_sim, ref["mean_sim"], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(res.best_sim, ref["best_sim"], rtol=0, atol=1e-12)
+    np.testing.assert_array_equal(res.fuse_map, ref["fuse_map"])
+    n = len(ref["src_index"])
+    assert res.kept_count == n
+    np.testing.assert_array_equal(res.src_index[:n], ref["src_index"])
+    np.testing.assert_array_equal(res.pos_ids[:, :n].T, ref["pos"])
+    xin = x.reshape(B, F * N, C)
+    for b in range(B):
+        np.testing.assert_array_equal(res.tokens_out[b, :n], xin[b][ref["src_index"]])
+    fused = (res.fuse_map >= 0).mean()
+    assert 0.05 < fused < 0.95                      # both outcomes occur
+
+
+def test_tied_with_one_element_is_the_plain_pass(oracle):
+    cfg, batch = _small("bf16", seed=43, B=1)
+    one = oracle.compress(batch.x, 1, 0.6)
+    tied = oracle.compress_tied(batch.x, 1, 0.6)
+    assert tied.anchor_index == one.anchor_index[0] and tied.kept_count == one.kept_count[0]
+    np.testing.assert_array_equal(tied.fuse_map, one.fuse_map[0])
+    np.testing.assert_array_equal(tied.best_idx, one.best_idx[0])
+    np.testing.assert_array_equal(tied.best_sim[0], one.best_sim[0])
+    np.testing.assert_array_equal(tied.mean_sim, one.best_sim[0])
+    n = tied.kept_count
+    np.testing.assert_array_equal(tied.src_index[:n], one.src_index[:n])
+    np.testing.assert_array_equal(tied.tokens_out[0, :n], one.tokens_out[:n])
+
+
+def test_tied_copies_of_one_clip_behave_like_that_clip(oracle):
+    """B identical elements: the mean equals each element's similarity, so every decision is the
+    single clip's and all elements emit the same rows."""
+    cfg, batch = _small("f32", seed=44, B=1)
+    x = np.repeat(batch.x, 3, axis=0)
+    one = oracle.compress(batch.x, 2, 0.6)
+    tied = oracle.compress_tied(x, 2, 0.6)
+    np.testing.assert_array_equal(tied.fuse_map, one.fuse_map[0])
+    np.testing.assert_allclose(tied.mean_sim, one.best_sim[0], rtol=0, atol=1e-15)
+    for b in range(3):
+        np.testing.assert_array_equal(tied.tokens_out[b, :tied.kept_count], one.tokens_out[:one.kept_count[0]])
+
+
+def test_tied_union_rule_and_fixed_anchor(oracle):
+    cfg = _tied_cfg(seed=45)
+    x = make_clip_batch(cfg).x
+    t = 0.6
+    res = oracle.compress_tied(x, 1, t, 1, -1)
+    assert res.anchor_index == cfg.F - 1
+    src = np.ones(cfg.F, bool)
+    src[res.anchor_index] = False
+    fused = res.fuse_map >= 0
+    above = np.all(res.best_sim > float(np.float32(t)), axis=0)
+    np.testing.assert_array_equal(fused[src], above[src])        # fused iff every element exceeds t
+    assert not fused[~src].any()
+    # a position one element alone would fuse can still be kept because another element objects
+    some = (res.best_sim > float(np.float32(t)))[:, src]
+    assert (some.any(axis=0) & ~some.all(axis=0)).any()
+    np.testing.assert_allclose(res.mean_sim[src] >= res.second_mean[src], True)

@@ -421,3 +421,14 @@ def test_margin_helper_moves_every_decision_off_the_edge(oracle):
     for t in ts:
         assert (np.abs(res.best_sim[src] - np.float32(t)) >= 5e-3).all()
     assert margins.anchor_gap(res) >= 1e-4
+
+
+def test_tied_margin_helper_moves_every_decision_off_the_edge(oracle):
+    from oracle import margins
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=3, F=5, H=6, W=6, C=32, dtype="bf16", shared_motion=True)
+    batch = make_clip_batch(cfg)
+    res = margins.enforce_tied_margins(batch, 1, (0.7,), want_tokens=False)
+    src = np.ones(cfg.F, bool)
+    src[res.anchor_index] = False
+    assert np.all((res.mean_sim - res.second_mean)[src] >= 1e-4)
+    assert np.all(np.abs(res.best_sim[:, src] - float(np.float32(0.7))) >= 1e-3)

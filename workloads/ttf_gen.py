@@ -52,6 +52,9 @@ class WorkloadConfig:
     region: int = 4               # motion offsets are constant on region x region cells
     scene_len: Optional[int] = None   # frames per scene (None: one scene per clip)
     clean_sigma: float = 0.3      # noise of the designated low-noise frame (anchored mode)
+    shared_motion: bool = False   # every clip of the batch uses clip 0's motion, noise amplitudes, change mask
+                                  # and low-noise frame (content and noise stay independent): views of one
+                                  # scene dynamics, the input the tied-batch mode is meant for
 
     @property
     def N(self) -> int:
@@ -186,7 +189,7 @@ def _emit(cfg: WorkloadConfig, frame: np.ndarray) -> np.ndarray:
 
 
 def _gen_clip(cfg: WorkloadConfig, seed: int, b: int, out: ClipBatch) -> None:
-    meta = _rng(seed, b, _STREAM_META)
+    meta = _rng(seed, 0 if cfg.shared_motion else b, _STREAM_META)
     H, W, C = cfg.H, cfg.W, cfg.C
     n_scenes = 1 if cfg.scene_len is None else -(-cfg.F // cfg.scene_len)
     if cfg.mode == "anchored":
