@@ -22,8 +22,8 @@
  *
  * A batch holds B independent clips: every clip gets its own anchor, matches, mask and
  * L'; outputs are packed clip after clip.  (The paper's tied-batch rule -- one offset from
- * the batch-mean similarity, keep = union over the batch -- is a different mode and is
- * not offered by this entry point.)
+ * the batch-mean similarity, keep = union over the batch -- is a different mode, offered by
+ * ttf_compress_tied.)
  *
  * General conventions
  *   - All data pointers are DEVICE pointers unless a field says HOST.  Every buffer is
@@ -136,6 +136,40 @@ ttf_status ttf_compress(const ttf_params* params, const void* features,
 ttf_status ttf_compress_segment(const ttf_params* params, const void* features, const void* anchor_frame,
                                 int32_t frame_offset, void* workspace, size_t workspace_bytes,
                                 const ttf_outputs* out, void* hip_stream);
+
+/*
+ * Tied-batch mode (Section 3: for B > 1 the same offset is chosen for all batch elements by
+ * maximising the mean similarity at each (k,i), s^ is read per element at that offset, and the
+ * preserve rule unites the keep masks over the batch).  All B elements therefore keep the same
+ * index set and the output is rectangular.  Choices the text leaves open: the anchor frame is
+ * shared -- under the automatic rule the frame with the largest batch-mean anchor score (lowest
+ * k on ties), else the fixed frame; the mean is the arithmetic mean of the B cosines of one
+ * candidate cell; first maximum in row-major offset order.  Radius r <= 3 (UNSUPPORTED beyond).
+ *
+ * cap = F*N rows.
+ */
+typedef struct {
+    void*    tokens_out;    /* [B, cap, C] dtype: element b's rows start at row b*cap; rows
+                               0..L'-1 of every element are valid, the rest untouched            */
+    int32_t* pos_ids;       /* [3, cap] planes k, y, x of the shared rows                         */
+    int32_t* src_index;     /* [cap] flat k*N+i of the shared rows                                */
+    int32_t* kept_count;    /* [1] L' = N + P                                                     */
+    int32_t* anchor_index;  /* [B] every entry = the shared anchor frame                          */
+    int32_t* fuse_map;      /* [F,N] shared: dst(k,i) if every element has s^ > t, else -1        */
+    float*   best_sim;      /* optional [B,F,N]: s^ of every element at the shared offset (1 on
+                               anchor rows)                                                      */
+    int32_t* best_idx;      /* optional [F,N]: shared dst(k,i) (i on anchor rows)                 */
+    float*   mean_sim;      /* optional [F,N]: the maximal batch-mean similarity (1 on anchor
+                               rows)                                                             */
+    int32_t* host_counts;   /* optional HOST pinned [1]: copy of kept_count                       */
+} ttf_tied_outputs;
+
+/* Workspace bytes of ttf_compress_tied (depends on B,F,H,W,C,dtype and r). */
+ttf_status ttf_tied_workspace_size(const ttf_params* params, size_t* bytes);
+
+/* Arguments and errors as for ttf_compress; workspace of ttf_tied_workspace_size() bytes. */
+ttf_status ttf_compress_tied(const ttf_params* params, const void* features, void* workspace,
+                             size_t workspace_bytes, const ttf_tied_outputs* out, void* hip_stream);
 
 /*
  * Restoration (Discussion D4, token restoration through the map dst(k,i) of the matching step).

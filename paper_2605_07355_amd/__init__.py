@@ -17,6 +17,9 @@ from .binding import (  # noqa: F401
     ttf_status_string,
     ttf_last_hip_error,
     ttf_compress_segment,
+    TTFTiedBuffers,
+    ttf_compress_tied,
+    ttf_tied_workspace_size,
     ttf_restore_map,
     ttf_restore,
     ttf_decode_alignment,

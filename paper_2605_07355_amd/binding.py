@@ -35,6 +35,12 @@ class _Outputs(ctypes.Structure):
                  "fuse_map", "best_sim", "best_idx", "host_counts")]
 
 
+class _TiedOutputs(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("tokens_out", "pos_ids", "src_index", "kept_count", "anchor_index", "fuse_map",
+                 "best_sim", "best_idx", "mean_sim", "host_counts")]
+
+
 _lib: Optional[ctypes.CDLL] = None
 
 
@@ -60,6 +66,11 @@ def load_library() -> ctypes.CDLL:
         lib.ttf_compress_segment.restype = ctypes.c_int
         lib.ttf_compress_segment.argtypes = [ctypes.POINTER(_Params), vp, vp, ctypes.c_int32, vp, ctypes.c_size_t,
                                              ctypes.POINTER(_Outputs), vp]
+        lib.ttf_tied_workspace_size.restype = ctypes.c_int
+        lib.ttf_tied_workspace_size.argtypes = [ctypes.POINTER(_Params), ctypes.POINTER(ctypes.c_size_t)]
+        lib.ttf_compress_tied.restype = ctypes.c_int
+        lib.ttf_compress_tied.argtypes = [ctypes.POINTER(_Params), vp, vp, ctypes.c_size_t,
+                                          ctypes.POINTER(_TiedOutputs), vp]
         lib.ttf_restore_map.restype = ctypes.c_int
         lib.ttf_restore_map.argtypes = [ctypes.POINTER(_Params), vp, vp, vp, vp, vp]
         lib.ttf_restore.restype = ctypes.c_int
@@ -261,6 +272,66 @@ def ttf_compress_segment(features: torch.Tensor, anchor_frame: torch.Tensor, fra
                                                    int(frame_offset), ws_ptr, ws_bytes, ctypes.byref(o),
                                                    _stream_ptr(stream, features.device)))
     return TTFOutput(buffers, B, F, H, W, C)
+
+
+@dataclass
+class TTFTiedBuffers:
+    """Caller-owned device buffers of the tied-batch mode."""
+    tokens_out: torch.Tensor     # [B, F*N, C]
+    pos_ids: torch.Tensor        # [3, F*N] int32
+    src_index: torch.Tensor      # [F*N] int32
+    kept_count: torch.Tensor     # [1] int32
+    anchor_index: torch.Tensor   # [B] int32
+    fuse_map: torch.Tensor       # [F,N] int32
+    best_sim: Optional[torch.Tensor]   # [B,F,N] float32
+    best_idx: Optional[torch.Tensor]   # [F,N] int32
+    mean_sim: Optional[torch.Tensor]   # [F,N] float32
+    workspace: torch.Tensor
+
+    @staticmethod
+    def allocate(B, F, H, W, C, dtype, device, r=1, want_sim=True) -> "TTFTiedBuffers":
+        N = H * W
+        i32 = dict(dtype=torch.int32, device=device)
+        f32 = dict(dtype=torch.float32, device=device)
+        return TTFTiedBuffers(
+            tokens_out=torch.empty((B, F * N, C), dtype=dtype, device=device),
+            pos_ids=torch.empty((3, F * N), **i32), src_index=torch.empty((F * N,), **i32),
+            kept_count=torch.empty((1,), **i32), anchor_index=torch.empty((B,), **i32),
+            fuse_map=torch.empty((F, N), **i32),
+            best_sim=torch.empty((B, F, N), **f32) if want_sim else None,
+            best_idx=torch.empty((F, N), **i32) if want_sim else None,
+            mean_sim=torch.empty((F, N), **f32) if want_sim else None,
+            workspace=torch.empty((ttf_tied_workspace_size(B, F, H, W, C, dtype, r) + 256,),
+                                  dtype=torch.uint8, device=device))
+
+
+def ttf_tied_workspace_size(B: int, F: int, H: int, W: int, C: int, dtype: torch.dtype = torch.bfloat16,
+                            r: int = 1) -> int:
+    p = _make_params(B, F, H, W, C, _dtype_code(dtype), r, 0.7, "auto")
+    n = ctypes.c_size_t(0)
+    _check(load_library().ttf_tied_workspace_size(ctypes.byref(p), ctypes.byref(n)))
+    return int(n.value)
+
+
+def ttf_compress_tied(features: torch.Tensor, r: int = 1, t: float = 0.70, anchor: Union[str, int] = "auto",
+                      buffers: Optional[TTFTiedBuffers] = None, want_sim: bool = True,
+                      stream: Optional[torch.cuda.Stream] = None) -> TTFTiedBuffers:
+    """Tied-batch pass on ``features`` [B,F,H,W,C]: one shared offset and one shared keep mask for
+    all B elements; rectangular output (see ``TTFTiedBuffers``)."""
+    if features.dim() != 5 or not features.is_cuda or not features.is_contiguous():
+        raise ValueError("features must be a contiguous [B,F,H,W,C] GPU tensor")
+    B, F, H, W, C = (int(v) for v in features.shape)
+    p = _make_params(B, F, H, W, C, _dtype_code(features.dtype), r, t, anchor)
+    if buffers is None:
+        buffers = TTFTiedBuffers.allocate(B, F, H, W, C, features.dtype, features.device, r=r, want_sim=want_sim)
+    ws_ptr, ws_bytes = _aligned_workspace(buffers.workspace)
+    o = _TiedOutputs(_ptr(buffers.tokens_out), _ptr(buffers.pos_ids), _ptr(buffers.src_index),
+                     _ptr(buffers.kept_count), _ptr(buffers.anchor_index), _ptr(buffers.fuse_map),
+                     _ptr(buffers.best_sim), _ptr(buffers.best_idx), _ptr(buffers.mean_sim), None)
+    with torch.cuda.device(features.device):
+        _check(load_library().ttf_compress_tied(ctypes.byref(p), features.data_ptr(), ws_ptr, ws_bytes,
+                                                ctypes.byref(o), _stream_ptr(stream, features.device)))
+    return buffers
 
 
 def ttf_restore_map(out: TTFOutput, restore_map: Optional[torch.Tensor] = None,

@@ -13,6 +13,8 @@
 namespace ttf {
 namespace {
 
+constexpr int kAnchorGiven = -2;   // "fixed_anchor" value: the anchor of every clip is already in anchor_index
+
 // One block = one frame x one slice of 64*V channels.  Wave w adds rows w, w+4, ...; the four
 // partial sums are combined through LDS in wave order, so the result is order-stable.
 template <typename T, int V>
@@ -175,6 +177,46 @@ __device__ __forceinline__ int pick_anchor(const double* __restrict__ score_part
     return arg == 0x7fffffff ? 0 : arg;
 }
 
+// Batch-tied anchor (tied-batch mode): the frame whose anchor score, averaged over the B clips
+// (summed in ascending b, fp64), is largest; lowest k on ties.  A fixed frame is simply
+// broadcast.  One wave; writes the shared index to every entry of anchor_index.
+__global__ __launch_bounds__(64) void k_tied_anchor(const double* __restrict__ score_part,
+                                                    const double* __restrict__ clip_part,
+                                                    int32_t* __restrict__ anchor_index, int B, int F, int S,
+                                                    int fixed_anchor)
+{
+    const int lane = threadIdx.x;
+    int arg = fixed_anchor;
+    if (fixed_anchor < 0) {
+        double best = -1.0e300;
+        arg = 0x7fffffff;
+        for (int k = lane; k < F; k += 64) {
+            double acc = 0.0;
+            for (int b = 0; b < B; ++b) {
+                double vv = 0.0, uv = 0.0, uu = 0.0;
+                for (int s = 0; s < S; ++s) {
+                    vv += clip_part[(size_t)b * S + s];
+                    const double2 o = *reinterpret_cast<const double2*>(score_part + (((size_t)b * S + s) * F + k) * 2);
+                    uv += o.x;
+                    uu += o.y;
+                }
+                const double den = sqrt(uu) * sqrt(vv);
+                acc += den > 0.0 ? uv / den : 0.0;
+            }
+            const double score = acc / (double)B;
+            if (score > best) { best = score; arg = k; }
+        }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            const double ob = __shfl_xor(best, m, 64);
+            const int oa = __shfl_xor(arg, m, 64);
+            if (ob > best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+        }
+        if (arg == 0x7fffffff) arg = 0;
+    }
+    for (int b = lane; b < B; b += 64) anchor_index[b] = arg;
+}
+
 // Picks the anchor of clip b (arg max of frame_score, lowest k on ties, or the fixed frame),
 // publishes it, and writes 1/||x_{a,j}|| for the anchor tokens.  One wave per anchor token.
 template <typename T, int V>
@@ -188,10 +230,13 @@ __global__ __launch_bounds__(256) void k_anchor_norms(const T* __restrict__ x, c
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int b = blockIdx.x / groups;
     const int j = (blockIdx.x % groups) * 4 + wave;
-    // the anchor is a frame of x (fixed or picked), or frame b of ext_anchor (published as -1)
+    // the anchor is a frame of x (fixed, picked here, or already chosen: kAnchorGiven), or frame b
+    // of ext_anchor (published as -1)
     const int a = ext_anchor ? -1
-                : fixed_anchor >= 0 ? fixed_anchor : pick_anchor(score_part, clip_part, b, F, S, lane);
-    if (blockIdx.x % groups == 0 && threadIdx.x == 0) anchor_index[b] = a;
+                : fixed_anchor >= 0 ? fixed_anchor
+                : fixed_anchor == kAnchorGiven ? anchor_index[b]
+                                               : pick_anchor(score_part, clip_part, b, F, S, lane);
+    if (fixed_anchor != kAnchorGiven && blockIdx.x % groups == 0 && threadIdx.x == 0) anchor_index[b] = a;
     if (j >= N) return;
     const T* row = (ext_anchor ? ext_anchor + (size_t)b * N * C : x + ((size_t)b * F + a) * N * C) + (size_t)j * C;
     float ss = 0.f;
@@ -226,11 +271,14 @@ __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restri
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int tiles = N / 16;
     const int b = blockIdx.x / tiles, tile = blockIdx.x % tiles;
-    // the anchor is a frame of x (fixed or picked), or frame b of ext_anchor (published as -1)
+    // the anchor is a frame of x (fixed, picked here, or already chosen: kAnchorGiven), or frame b
+    // of ext_anchor (published as -1)
     const int a = ext_anchor ? -1
-                : fixed_anchor >= 0 ? fixed_anchor : pick_anchor(score_part, clip_part, b, F, S, lane);
-    if (tile == 0 && threadIdx.x == 0) anchor_index[b] = a;
-    if (a >= 0 && threadIdx.x < 16) {                        // anchor tokens are always retained
+                : fixed_anchor >= 0 ? fixed_anchor
+                : fixed_anchor == kAnchorGiven ? anchor_index[b]
+                                               : pick_anchor(score_part, clip_part, b, F, S, lane);
+    if (fixed_anchor != kAnchorGiven && tile == 0 && threadIdx.x == 0) anchor_index[b] = a;
+    if (a >= 0 && fuse_map && threadIdx.x < 16) {            // anchor tokens are always retained
         const size_t o = ((size_t)b * F + a) * N + 16 * tile + threadIdx.x;
         fuse_map[o] = -1;
         if (best_sim) best_sim[o] = 1.0f;
@@ -313,13 +361,25 @@ hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, hipStre
     return hipGetLastError();
 }
 
+static int fixed_frame(const ttf_params& p)
+{
+    if (p.anchor_mode != TTF_ANCHOR_FIXED) return -1;
+    return p.anchor_index < 0 ? p.anchor_index + p.F : p.anchor_index;
+}
+
+hipError_t launch_tied_anchor(const ttf_params& p, const Workspace& w, int32_t* anchor_index, hipStream_t s)
+{
+    k_tied_anchor<<<1, 64, 0, s>>>(w.score_part, w.clip_part, anchor_index, p.B, p.F, (p.C + 255) / 256,
+                                   fixed_frame(p));
+    return hipGetLastError();
+}
+
 hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
-                               int32_t* anchor_index, hipStream_t s)
+                               int32_t* anchor_index, bool anchor_given, hipStream_t s)
 {
     const int N = p.H * p.W;
     const int groups = (N + 3) / 4;
-    int fixed = -1;
-    if (p.anchor_mode == TTF_ANCHOR_FIXED) fixed = p.anchor_index < 0 ? p.anchor_index + p.F : p.anchor_index;
+    const int fixed = anchor_given ? kAnchorGiven : fixed_frame(p);
     return by_layout(p, [&](auto tag, auto vtag) {
         using T = decltype(tag);
         constexpr int V = decltype(vtag)::value;
@@ -333,11 +393,10 @@ hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const void* e
 
 hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                       int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
-                                      int32_t* best_idx, hipStream_t s)
+                                      int32_t* best_idx, bool anchor_given, hipStream_t s)
 {
     const int N = p.H * p.W;
-    int fixed = -1;
-    if (p.anchor_mode == TTF_ANCHOR_FIXED) fixed = p.anchor_index < 0 ? p.anchor_index + p.F : p.anchor_index;
+    const int fixed = anchor_given ? kAnchorGiven : fixed_frame(p);
     k_anchor_prepare<<<(unsigned)(p.B * (N / 16)), 512, 0, s>>>(static_cast<const uint16_t*>(x),
                                                                 static_cast<const uint16_t*>(ext_anchor), w.score_part,
                                                                 w.clip_part, anchor_index, w.anchor_inv,

@@ -11,11 +11,11 @@ namespace ttf {
 
 hipError_t launch_window_search_generic(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                         const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
-                                        int32_t* best_idx, hipStream_t s);
+                                        int32_t* best_idx, float* win_sim, hipStream_t s);
 
 hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,
                                      const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
-                                     int32_t* best_idx, hipStream_t s);
+                                     int32_t* best_idx, float* win_sim, hipStream_t s);
 
 // bf16 tokens on 16- or 32-wide grids take the matrix-core kernels; everything else (fp32 input,
 // other grids, large radii, odd channel counts) takes the general wave-per-token kernel.  Setting
@@ -29,11 +29,12 @@ bool use_mfma_path(const ttf_params& p)
 
 hipError_t launch_window_search(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                 const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
-                                int32_t* best_idx, hipStream_t s)
+                                int32_t* best_idx, float* win_sim, hipStream_t s)
 {
     if (use_mfma_path(p))
-        return launch_window_search_mfma(p, x, ext_anchor != nullptr, w, anchor_index, fuse_map, best_sim, best_idx, s);
-    return launch_window_search_generic(p, x, ext_anchor, w, anchor_index, fuse_map, best_sim, best_idx, s);
+        return launch_window_search_mfma(p, x, ext_anchor != nullptr, w, anchor_index, fuse_map, best_sim, best_idx,
+                                         win_sim, s);
+    return launch_window_search_generic(p, x, ext_anchor, w, anchor_index, fuse_map, best_sim, best_idx, win_sim, s);
 }
 
 namespace {
@@ -127,16 +128,16 @@ static ttf_status run_pass(const ttf_params* params, const void* features, const
     mark();
     if (use_mfma_path(p))
         TTF_STEP(launch_anchor_prepare_mfma(p, features, ext_anchor, w, out->anchor_index, out->fuse_map,
-                                            out->best_sim, out->best_idx, s));
-    else TTF_STEP(launch_anchor_norms(p, features, ext_anchor, w, out->anchor_index, s));
+                                            out->best_sim, out->best_idx, false, s));
+    else TTF_STEP(launch_anchor_norms(p, features, ext_anchor, w, out->anchor_index, false, s));
     mark();
     TTF_STEP(launch_window_search(p, features, ext_anchor, w, out->anchor_index, out->fuse_map, out->best_sim,
-                                  out->best_idx, s));
+                                  out->best_idx, nullptr, s));
     mark();
-    TTF_STEP(launch_offsets_scan(p, w, out->anchor_index, out->kept_count, out->row_offsets, s));
+    TTF_STEP(launch_offsets_scan(p, w, out->anchor_index, out->kept_count, out->row_offsets, false, s));
     mark();
     TTF_STEP(launch_emit_rows(p, features, w, out->anchor_index, out->tokens_out, out->pos_ids,
-                              out->src_index, frame_offset, s));
+                              out->src_index, frame_offset, false, s));
     mark();                                                    // end of stage 5
     if (out->host_counts) {
         TTF_STEP(hipMemcpyAsync(out->host_counts, out->kept_count, sizeof(int32_t) * p.B,
@@ -166,6 +167,67 @@ ttf_status ttf_compress_segment(const ttf_params* params, const void* features, 
     if (!anchor_frame) return TTF_ERR_INVALID_ARG;
     if (params && (long long)frame_offset + params->F > 0x7fffffffll) return TTF_ERR_INVALID_ARG;
     return run_pass(params, features, anchor_frame, frame_offset, workspace, workspace_bytes, out, hip_stream);
+}
+
+// Largest radius of the tied-batch mode: its workspace keeps all (2r+1)^2 similarities per token.
+static constexpr int kTiedMaxRadius = 3;
+
+ttf_status ttf_tied_workspace_size(const ttf_params* params, size_t* bytes)
+{
+    if (!bytes) return TTF_ERR_INVALID_ARG;
+    const ttf_status st = check_params(params);
+    if (st != TTF_OK) return st;
+    if (params->r > kTiedMaxRadius) return TTF_ERR_UNSUPPORTED;
+    *bytes = carve_tied(*params, nullptr).bytes;
+    return TTF_OK;
+}
+
+ttf_status ttf_compress_tied(const ttf_params* params, const void* features, void* workspace,
+                             size_t workspace_bytes, const ttf_tied_outputs* out, void* hip_stream)
+{
+    const ttf_status st = check_params(params);
+    if (st != TTF_OK) return st;
+    if (!features || !workspace || !out) return TTF_ERR_INVALID_ARG;
+    if (!out->tokens_out || !out->pos_ids || !out->src_index || !out->kept_count || !out->anchor_index ||
+        !out->fuse_map)
+        return TTF_ERR_INVALID_ARG;
+    if (params->r > kTiedMaxRadius) return TTF_ERR_UNSUPPORTED;
+    if (!aligned(features, 16) || !aligned(out->tokens_out, 16) || !aligned(workspace, 256))
+        return TTF_ERR_UNSUPPORTED;
+    const ttf_params& p = *params;
+    const TiedWorkspace tw = carve_tied(p, workspace);
+    if (workspace_bytes < tw.bytes) return TTF_ERR_WORKSPACE_TOO_SMALL;
+    const Workspace& w = tw.base;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = hipSuccess;
+#define TTF_STEP(call)                 \
+    do {                               \
+        if (e == hipSuccess) e = (call); \
+    } while (0)
+    if (p.anchor_mode == TTF_ANCHOR_AUTO) {
+        TTF_STEP(launch_frame_sums(p, features, w, s));
+        TTF_STEP(launch_anchor_scores(p, w, s));
+    }
+    TTF_STEP(launch_tied_anchor(p, w, out->anchor_index, s));
+    if (use_mfma_path(p))
+        TTF_STEP(launch_anchor_prepare_mfma(p, features, nullptr, w, out->anchor_index, nullptr, nullptr, nullptr,
+                                            true, s));
+    else TTF_STEP(launch_anchor_norms(p, features, nullptr, w, out->anchor_index, true, s));
+    TTF_STEP(launch_window_search(p, features, nullptr, w, out->anchor_index, nullptr, nullptr, nullptr,
+                                  tw.win_sim, s));
+    TTF_STEP(launch_tie(p, w, tw.win_sim, out->anchor_index, out->fuse_map, out->best_sim, out->best_idx,
+                        out->mean_sim, s));
+    TTF_STEP(launch_offsets_scan(p, w, out->anchor_index, out->kept_count, tw.row_offsets, true, s));
+    TTF_STEP(launch_emit_rows(p, features, w, out->anchor_index, out->tokens_out, out->pos_ids, out->src_index, 0,
+                              true, s));
+    if (out->host_counts)
+        TTF_STEP(hipMemcpyAsync(out->host_counts, out->kept_count, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+#undef TTF_STEP
+    if (e != hipSuccess) {
+        g_last_hip_error = static_cast<int>(e);
+        return TTF_ERR_HIP;
+    }
+    return TTF_OK;
 }
 
 ttf_status ttf_restore_map(const ttf_params* params, const int32_t* fuse_map, const int32_t* row_offsets,
@@ -247,9 +309,11 @@ ttf_status ttf_regate(const ttf_params* params, const void* features, const floa
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     hipError_t e = launch_regate(p, w, out->best_sim, out->best_idx, out->anchor_index, thresholds,
                                  out->fuse_map, s);
-    if (e == hipSuccess) e = launch_offsets_scan(p, w, out->anchor_index, out->kept_count, out->row_offsets, s);
     if (e == hipSuccess)
-        e = launch_emit_rows(p, features, w, out->anchor_index, out->tokens_out, out->pos_ids, out->src_index, 0, s);
+        e = launch_offsets_scan(p, w, out->anchor_index, out->kept_count, out->row_offsets, false, s);
+    if (e == hipSuccess)
+        e = launch_emit_rows(p, features, w, out->anchor_index, out->tokens_out, out->pos_ids, out->src_index, 0,
+                             false, s);
     if (e == hipSuccess && out->host_counts) {
         e = hipMemcpyAsync(out->host_counts, out->kept_count, sizeof(int32_t) * p.B, hipMemcpyDeviceToHost, s);
         if (e == hipSuccess)

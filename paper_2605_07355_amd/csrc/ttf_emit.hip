@@ -70,7 +70,9 @@ __global__ __launch_bounds__(1024) void k_offsets_scan(const uint64_t* __restric
 }
 
 // One block = 16 tokens (a quarter of a 64-token keep word) of one frame; its kept tokens are dealt
-// to the four waves by rank.  Small blocks matter: a wave copies its rows one after the other, so
+// to the four waves by rank.  tied_rows > 0 (tied-batch mode): keep bits and frame bases are shared
+// by all clips ([F,NW] and [F]), clip b writes its rows at row b*tied_rows + shared row, and only
+// clip 0 writes the shared position ids and source indices.  Small blocks matter: a wave copies its rows one after the other, so
 // the fewer rows per wave, the more copies are in flight across the chip.
 template <int U>
 __global__ __launch_bounds__(256) void k_emit_rows(const char* __restrict__ x,
@@ -80,18 +82,21 @@ __global__ __launch_bounds__(256) void k_emit_rows(const char* __restrict__ x,
                                                    int32_t* __restrict__ pos_ids,
                                                    int32_t* __restrict__ src_index,
                                                    int F, int N, int W, int NW, size_t row_bytes, size_t cap,
-                                                   int frame_offset)
+                                                   int frame_offset, size_t tied_rows)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int quarter = blockIdx.x & 3;
     const int word = (blockIdx.x >> 2) % NW;
     const size_t frame = (blockIdx.x >> 2) / NW;
     const int k = (int)(frame % F);
-    const uint64_t* kb = keep_bits + frame * (size_t)NW;
+    const size_t meta = tied_rows ? (size_t)k : frame;        // which frame's bits and base to use
+    const size_t row0 = tied_rows ? (frame / F) * tied_rows : 0;
+    const bool ids = !tied_rows || frame < (size_t)F;
+    const uint64_t* kb = keep_bits + meta * (size_t)NW;
     const uint64_t wbits = kb[word];
     const uint64_t bits = wbits & (0xffffull << (16 * quarter));
     if (bits == 0) return;
-    int before = frame_base[frame];
+    int before = frame_base[meta];
     for (int q = 0; q < word; ++q) before += __popcll(kb[q]);
     before += __popcll(wbits & ((1ull << (16 * quarter)) - 1ull));
     uint64_t rem = bits;
@@ -101,8 +106,8 @@ __global__ __launch_bounds__(256) void k_emit_rows(const char* __restrict__ x,
         if ((rank & 3) != wave) continue;
         const int i = word * 64 + bit;
         const size_t row = (size_t)before + rank;
-        copy_row<U>(x + (frame * (size_t)N + i) * row_bytes, tokens_out + row * row_bytes, row_bytes, lane);
-        if (lane == 0) {
+        copy_row<U>(x + (frame * (size_t)N + i) * row_bytes, tokens_out + (row0 + row) * row_bytes, row_bytes, lane);
+        if (ids && lane == 0) {
             pos_ids[row] = k + frame_offset;
             pos_ids[cap + row] = i / W;
             pos_ids[2 * cap + row] = i % W;
@@ -114,34 +119,36 @@ __global__ __launch_bounds__(256) void k_emit_rows(const char* __restrict__ x,
 }  // namespace
 
 hipError_t launch_offsets_scan(const ttf_params& p, const Workspace& w, const int32_t* anchor_index,
-                               int32_t* kept_count, int32_t* row_offsets, hipStream_t s)
+                               int32_t* kept_count, int32_t* row_offsets, bool tied, hipStream_t s)
 {
     const int N = p.H * p.W, NW = (N + 63) / 64;
+    // tied-batch mode: one shared mask, i.e. the scan of a single clip
     k_offsets_scan<<<1, 1024, 0, s>>>(w.keep_bits, anchor_index, w.frame_base, kept_count, row_offsets,
-                                      p.B, p.F, N, NW);
+                                      tied ? 1 : p.B, p.F, N, NW);
     return hipGetLastError();
 }
 
 hipError_t launch_emit_rows(const ttf_params& p, const void* x, const Workspace& w,
                             const int32_t* anchor_index, void* tokens_out, int32_t* pos_ids,
-                            int32_t* src_index, int frame_offset, hipStream_t s)
+                            int32_t* src_index, int frame_offset, bool tied, hipStream_t s)
 {
     (void)anchor_index;
     const int N = p.H * p.W, NW = (N + 63) / 64;
     const size_t row_bytes = (size_t)p.C * (p.dtype == TTF_BF16 ? 2 : 4);
-    const size_t cap = (size_t)p.B * p.F * N;
+    const size_t tied_rows = tied ? (size_t)p.F * N : 0;
+    const size_t cap = tied ? tied_rows : (size_t)p.B * p.F * N;  // length of one pos_ids plane
     const unsigned grid = (unsigned)((size_t)p.B * p.F * NW * 4);
     const char* xs = static_cast<const char*>(x);
     char* out = static_cast<char*>(tokens_out);
     if (row_bytes % 16 == 0)
         k_emit_rows<16><<<grid, 256, 0, s>>>(xs, w.keep_bits, w.frame_base, out, pos_ids, src_index,
-                                             p.F, N, p.W, NW, row_bytes, cap, frame_offset);
+                                             p.F, N, p.W, NW, row_bytes, cap, frame_offset, tied_rows);
     else if (row_bytes % 4 == 0)
         k_emit_rows<4><<<grid, 256, 0, s>>>(xs, w.keep_bits, w.frame_base, out, pos_ids, src_index,
-                                            p.F, N, p.W, NW, row_bytes, cap, frame_offset);
+                                            p.F, N, p.W, NW, row_bytes, cap, frame_offset, tied_rows);
     else
         k_emit_rows<2><<<grid, 256, 0, s>>>(xs, w.keep_bits, w.frame_base, out, pos_ids, src_index,
-                                            p.F, N, p.W, NW, row_bytes, cap, frame_offset);
+                                            p.F, N, p.W, NW, row_bytes, cap, frame_offset, tied_rows);
     return hipGetLastError();
 }
 

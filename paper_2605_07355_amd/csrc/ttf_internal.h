@@ -58,22 +58,51 @@ hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, hipStre
 // `ext_anchor` (here and below): nullptr when the anchor is a frame of x; otherwise the anchor
 // frames [B,N,C] of a segment, in which case anchor_index is written as -1 and every frame of x
 // is a source frame.
+// `anchor_given`: the anchor of every clip is already in anchor_index (tied-batch mode); it is
+// read, not chosen.
 hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
-                               int32_t* anchor_index, hipStream_t s);
+                               int32_t* anchor_index, bool anchor_given, hipStream_t s);
 // Matrix-core path: anchor choice, inverse norms, the anchor frame re-laid in fragment order, and
 // the anchor-frame rows of fuse_map / best_sim / best_idx / keep bits.
 hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                       int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
-                                      int32_t* best_idx, hipStream_t s);
+                                      int32_t* best_idx, bool anchor_given, hipStream_t s);
 bool mfma_search_supported(const ttf_params& p);
 hipError_t launch_window_search(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                 const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
-                                int32_t* best_idx, hipStream_t s);
+                                int32_t* best_idx, float* win_sim, hipStream_t s);
 hipError_t launch_offsets_scan(const ttf_params& p, const Workspace& w, const int32_t* anchor_index,
-                               int32_t* kept_count, int32_t* row_offsets, hipStream_t s);
+                               int32_t* kept_count, int32_t* row_offsets, bool tied, hipStream_t s);
 hipError_t launch_emit_rows(const ttf_params& p, const void* x, const Workspace& w,
                             const int32_t* anchor_index, void* tokens_out, int32_t* pos_ids,
-                            int32_t* src_index, int frame_offset, hipStream_t s);
+                            int32_t* src_index, int frame_offset, bool tied, hipStream_t s);
+
+// Tied-batch mode.  Workspace behind the common sections: every window similarity of every
+// element, and the two row offsets of the shared mask.
+struct TiedWorkspace {
+    Workspace base;
+    float*    win_sim;       // [B,F,N,(2r+1)^2]
+    int32_t*  row_offsets;   // [2]
+    size_t    bytes;
+};
+inline TiedWorkspace carve_tied(const ttf_params& p, void* base)
+{
+    TiedWorkspace t;
+    t.base = carve(p, base);
+    const size_t K = (size_t)(2 * p.r + 1) * (2 * p.r + 1);
+    const size_t o_ws = t.base.bytes;
+    const size_t o_ro = align_up(o_ws + (size_t)p.B * p.F * p.H * p.W * K * sizeof(float), 256);
+    char* c = static_cast<char*>(base);
+    t.win_sim = reinterpret_cast<float*>(c + o_ws);
+    t.row_offsets = reinterpret_cast<int32_t*>(c + o_ro);
+    t.bytes = o_ro + 256;
+    return t;
+}
+// The shared anchor (batch-mean score, or the fixed frame) written to every entry of anchor_index.
+hipError_t launch_tied_anchor(const ttf_params& p, const Workspace& w, int32_t* anchor_index, hipStream_t s);
+// Shared offset, per-element s^, united keep mask (keep bits [F,NW] at the start of w.keep_bits).
+hipError_t launch_tie(const ttf_params& p, const Workspace& w, const float* win_sim, const int32_t* anchor_index,
+                      int32_t* fuse_map, float* best_sim, int32_t* best_idx, float* mean_sim, hipStream_t s);
 
 // Restoration: map from every original token to the compressed row that stands for it, and the
 // gather that rebuilds the full layout.

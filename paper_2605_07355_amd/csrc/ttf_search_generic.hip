@@ -19,12 +19,15 @@ namespace {
 constexpr int G = 9;                 // candidates per pass over the channels (a 3x3 window in one pass)
 constexpr float kNegInf = -__builtin_inff();
 
-template <typename T, int V>
+// ALL = false: arg max and gate per token.  ALL = true (tied-batch mode): every window similarity
+// is written to win_sim[token][(dy+r)*(2r+1) + (dx+r)] instead and nothing else is produced.
+template <typename T, int V, bool ALL>
 __global__ __launch_bounds__(1024) void k_search_generic(
     const T* __restrict__ x, const T* __restrict__ ext_anchor, const int32_t* __restrict__ anchor_index,
     const float* __restrict__ anchor_inv,
     int32_t* __restrict__ fuse_map, float* __restrict__ best_sim, int32_t* __restrict__ best_idx,
-    uint64_t* __restrict__ keep_bits, int F, int H, int W, int C, int r, float t, int NW)
+    uint64_t* __restrict__ keep_bits, float* __restrict__ win_sim, int F, int H, int W, int C, int r, float t,
+    int NW)
 {
     const int N = H * W;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -44,7 +47,7 @@ __global__ __launch_bounds__(1024) void k_search_generic(
         if (i >= N) break;
         const size_t o = frame * (size_t)N + i;
         if (k == a) {                                 // anchor tokens are always retained
-            if (lane == 0) {
+            if (!ALL && lane == 0) {
                 fuse_map[o] = -1;
                 if (best_sim) best_sim[o] = 1.0f;
                 if (best_idx) best_idx[o] = i;
@@ -95,11 +98,17 @@ __global__ __launch_bounds__(1024) void k_search_generic(
                 const float d = wave_sum(dot[g]);
                 if (c0 + g < ncand) {
                     const float sim = d * src_inv * ainv[cand[g]];
-                    if (sim > best) { best = sim; arg = cand[g]; }   // ascending index, strict: first maximum
+                    if constexpr (ALL) {
+                        const int slot = (cand[g] / W - y + r) * (2 * r + 1) + (cand[g] % W - xx + r);
+                        if (lane == 0) win_sim[o * (size_t)((2 * r + 1) * (2 * r + 1)) + slot] = sim;
+                    } else if (sim > best) {                         // ascending index, strict: first maximum
+                        best = sim;
+                        arg = cand[g];
+                    }
                 }
             }
         }
-        if (lane == 0) {
+        if (!ALL && lane == 0) {
             const bool fused = best > t;                  // keep = 1[s^ <= t]
             fuse_map[o] = fused ? arg : -1;
             if (best_sim) best_sim[o] = best;
@@ -108,24 +117,28 @@ __global__ __launch_bounds__(1024) void k_search_generic(
         }
     }
     __syncthreads();
-    if (threadIdx.x == 0) keep_bits[frame * (size_t)NW + word] = keep_word;
+    if (!ALL && threadIdx.x == 0) keep_bits[frame * (size_t)NW + word] = keep_word;
 }
 
 }  // namespace
 
 hipError_t launch_window_search_generic(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                         const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
-                                        int32_t* best_idx, hipStream_t s)
+                                        int32_t* best_idx, float* win_sim, hipStream_t s)
 {
     const int N = p.H * p.W, NW = (N + 63) / 64;
     const unsigned grid = (unsigned)((size_t)p.B * p.F * NW);
     auto go = [&](auto tag, auto vtag) {
         using T = decltype(tag);
         constexpr int V = decltype(vtag)::value;
-        k_search_generic<T, V><<<grid, 1024, 0, s>>>(static_cast<const T*>(x), static_cast<const T*>(ext_anchor),
-                                                    anchor_index, w.anchor_inv,
-                                                    fuse_map, best_sim, best_idx, w.keep_bits,
-                                                    p.F, p.H, p.W, p.C, p.r, p.t, NW);
+        if (win_sim)
+            k_search_generic<T, V, true><<<grid, 1024, 0, s>>>(
+                static_cast<const T*>(x), static_cast<const T*>(ext_anchor), anchor_index, w.anchor_inv, fuse_map,
+                best_sim, best_idx, w.keep_bits, win_sim, p.F, p.H, p.W, p.C, p.r, p.t, NW);
+        else
+            k_search_generic<T, V, false><<<grid, 1024, 0, s>>>(
+                static_cast<const T*>(x), static_cast<const T*>(ext_anchor), anchor_index, w.anchor_inv, fuse_map,
+                best_sim, best_idx, w.keep_bits, win_sim, p.F, p.H, p.W, p.C, p.r, p.t, NW);
         return hipGetLastError();
     };
     if (p.dtype == TTF_BF16)

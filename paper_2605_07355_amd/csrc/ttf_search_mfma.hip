@@ -93,11 +93,14 @@ __device__ __forceinline__ bf16x8 load_frag(const uint16_t* p)
 // masks the band |dx| <= RAD and the rows outside the grid, takes the arg max (lowest anchor
 // index on ties), applies the threshold and writes s^, dst, the fuse map and the tile's 16 keep
 // bits.  Straight-line code: no divergent branches.
-template <int CT, int RAD>
+// ALL (tied-batch mode): instead of the arg max, every in-window cosine is stored to
+// win_sim[token][(dy+RAD)*(2*RAD+1) + (dx+RAD)] and nothing else is written.
+template <int CT, int RAD, bool ALL>
 __device__ __forceinline__ void finish_tile(const f32x4* v, const float* nn, int s, bool live, int si, int a, int b,
                                             int F, int H, int i0, float t, const float* ai_tile,
                                             int32_t* __restrict__ fuse_map, float* __restrict__ best_sim,
-                                            int32_t* __restrict__ best_idx, uint16_t* __restrict__ keep16, int lane)
+                                            int32_t* __restrict__ best_idx, uint16_t* __restrict__ keep16,
+                                            float* __restrict__ win_sim, int lane)
 {
     using S = Shape<CT, RAD>;
     constexpr int W = S::W, NPS = S::NPS;
@@ -112,6 +115,25 @@ __device__ __forceinline__ void finish_tile(const f32x4* v, const float* nn, int
     int arg[4] = {kNoArg, kNoArg, kNoArg, kNoArg};
     const int ysrc = y0 + (CT == 1 ? u : 0);
     const int xsrc0 = CT == 1 ? 0 : 16 * u;
+    if constexpr (ALL) {
+        constexpr int K1 = 2 * RAD + 1;
+        const int kk = si + (si >= a ? 1 : 0);
+        const size_t tok0 = ((size_t)b * F + kk) * N + i0 + 16 * u + 4 * g;
+#pragma unroll
+        for (int q = 0; q < NPS; ++q) {
+            const int yy = CT == 1 ? ysrc - RAD + q : ylo + q / 2;
+            const int xa_col = (CT == 1 ? 0 : 16 * (q % 2)) + m;
+            const bool row_ok = (yy >= 0) & (yy < H) & (yy - ysrc >= -RAD) & (yy - ysrc <= RAD);
+            const float ai = ai_tile[S::pair_tile(u, q)];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int dx = xa_col - (xsrc0 + 4 * g + j);
+                if (live & row_ok & (dx >= -RAD) & (dx <= RAD))
+                    win_sim[(tok0 + j) * (K1 * K1) + (yy - ysrc + RAD) * K1 + dx + RAD] = v[q][j] * sinv[j] * ai;
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int q = 0; q < NPS; ++q) {
         // anchor tile of pair q: CT==1: row ysrc-RAD+q; CT==2: row ylo + q/2, column q%2
@@ -160,12 +182,12 @@ __device__ __forceinline__ void finish_tile(const f32x4* v, const float* nn, int
     if (lane == 0 && live) keep16[o0 / 16] = (uint16_t)keep;
 }
 
-template <int CT, int RAD, int KSW, int NW>
+template <int CT, int RAD, int KSW, int NW, bool ALL>
 __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ anchor_frag,
     const int32_t* __restrict__ anchor_index, const float* __restrict__ anchor_inv,
     int32_t* __restrict__ fuse_map, float* __restrict__ best_sim, int32_t* __restrict__ best_idx,
-    uint16_t* __restrict__ keep16, int F, int H, int C, float t, int passes, int groups)
+    uint16_t* __restrict__ keep16, float* __restrict__ win_sim, int F, int H, int C, float t, int passes, int groups)
 {
     using S = Shape<CT, RAD>;
     constexpr int W = S::W, NA = S::NA, NPS = S::NPS, FR = S::FR, PF = S::PF, RT = S::RT;
@@ -278,8 +300,8 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
             float nn[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) nn[j] = __shfl(nv[s], 4 * (4 * g + j), 64);
-            finish_tile<CT, RAD>(acc[s], nn, s, grp * S::FR + s / 2 < nsrc, min(grp * S::FR + s / 2, nsrc - 1), a, b,
-                                 F, H, i0, t, ai_tile, fuse_map, best_sim, best_idx, keep16, lane);
+            finish_tile<CT, RAD, ALL>(acc[s], nn, s, grp * S::FR + s / 2 < nsrc, min(grp * S::FR + s / 2, nsrc - 1),
+                                      a, b, F, H, i0, t, ai_tile, fuse_map, best_sim, best_idx, keep16, win_sim, lane);
         }
     } else {
         // ---- add the channel slices through LDS (wave order), RT source tiles per round ----
@@ -317,8 +339,9 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
                         v[q][0] += p[0]; v[q][1] += p[1]; v[q][2] += p[2]; v[q][3] += p[3];
                     }
                 }
-                finish_tile<CT, RAD>(v, nn, s, grp * S::FR + s / 2 < nsrc, min(grp * S::FR + s / 2, nsrc - 1), a, b,
-                                     F, H, i0, t, ai_tile, fuse_map, best_sim, best_idx, keep16, lane);
+                finish_tile<CT, RAD, ALL>(v, nn, s, grp * S::FR + s / 2 < nsrc, min(grp * S::FR + s / 2, nsrc - 1),
+                                          a, b, F, H, i0, t, ai_tile, fuse_map, best_sim, best_idx, keep16, win_sim,
+                                          lane);
             }
             __syncthreads();
         }
@@ -328,7 +351,7 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
 template <int CT, int RAD>
 hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,
                         const int32_t* anchor_index, int32_t* fuse_map, float* best_sim, int32_t* best_idx,
-                        hipStream_t s)
+                        float* win_sim, hipStream_t s)
 {
     using S = Shape<CT, RAD>;
     const int nsrc = external_anchor ? p.F : p.F - 1;        // source frames per clip
@@ -340,10 +363,15 @@ hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor
     const unsigned grid = (unsigned)blocks;
     const int ks_total = p.C / 32;                           // K-steps per token
     uint16_t* keep16 = reinterpret_cast<uint16_t*>(w.keep_bits);
-#define TTF_LAUNCH(KSW, NW)                                                                                  \
-    k_search_mfma<CT, RAD, KSW, NW><<<grid, NW * 64, 0, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv,  \
-                                                             fuse_map, best_sim, best_idx, keep16, p.F, p.H, \
-                                                             p.C, p.t, ks_total / (NW * KSW), groups)
+#define TTF_LAUNCH_AS(KSW, NW, ALL)                                                                           \
+    k_search_mfma<CT, RAD, KSW, NW, ALL><<<grid, NW * 64, 0, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv,  \
+                                                                  fuse_map, best_sim, best_idx, keep16, win_sim,  \
+                                                                  p.F, p.H, p.C, p.t, ks_total / (NW * KSW), groups)
+#define TTF_LAUNCH(KSW, NW)                   \
+    do {                                      \
+        if (win_sim) TTF_LAUNCH_AS(KSW, NW, true); \
+        else TTF_LAUNCH_AS(KSW, NW, false);   \
+    } while (0)
     // With several rounds of workgroups per wave slot, one wave per workgroup walks the whole
     // channel axis (no cross-wave sum, no LDS).  With fewer, such long-running single waves
     // leave SIMDs unevenly loaded (measured: 0.24 ms against 0.20 ms on 1024 workgroups), so the
@@ -352,6 +380,7 @@ hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor
     else if (ks_total % 8 == 0) TTF_LAUNCH(2, 4);
     else TTF_LAUNCH(1, 4);
 #undef TTF_LAUNCH
+#undef TTF_LAUNCH_AS
     return hipGetLastError();
 }
 
@@ -370,11 +399,11 @@ bool mfma_search_supported(const ttf_params& p)
 
 hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,
                                      const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
-                                     int32_t* best_idx, hipStream_t s)
+                                     int32_t* best_idx, float* win_sim, hipStream_t s)
 {
 #define TTF_CASE(CT, RAD)             \
     if (p.W == 16 * CT && p.r == RAD) \
-    return launch_shape<CT, RAD>(p, x, external_anchor, w, anchor_index, fuse_map, best_sim, best_idx, s)
+    return launch_shape<CT, RAD>(p, x, external_anchor, w, anchor_index, fuse_map, best_sim, best_idx, win_sim, s)
     TTF_CASE(1, 0);
     TTF_CASE(1, 1);
     TTF_CASE(1, 2);

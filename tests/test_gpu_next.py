@@ -354,3 +354,108 @@ def test_segment_rejects_bad_arguments():
     assert lib.ttf_compress_segment(ctypes.byref(p), q, q, 2 ** 31 - 2, q, 1 << 20, ctypes.byref(o), None) == bd.TTF_ERR_INVALID_ARG
     torch.cuda.synchronize()
     assert int(buf.abs().sum()) == 0
+
+
+# ------------------------------------------------------------------------------ tied batch
+def _tied_case(cfg, t, anchor="auto"):
+    from oracle import margins
+    mode, idx = (ANCHOR_AUTO, 0) if anchor == "auto" else (ANCHOR_FIXED, int(anchor))
+    for attempt in range(4):
+        batch = make_clip_batch(cfg, seed=cfg.seed + 1000 * attempt)
+        try:
+            return batch, margins.enforce_tied_margins(batch, cfg.r, (t,), mode, idx, want_tokens=True)
+        except margins.MarginError:
+            continue
+    raise RuntimeError("no seed met the margins")
+
+
+def _run_tied(x_np, r, t, anchor="auto"):
+    import paper_2605_07355_amd as ttf
+    x = to_device(x_np)
+    B, F, H, W, C = x.shape
+    buf = ttf.TTFTiedBuffers.allocate(B, F, H, W, C, x.dtype, x.device, r=r)
+    buf.tokens_out.view(torch.uint8).fill_(0x7A)
+    for tns in (buf.pos_ids, buf.src_index, buf.kept_count, buf.anchor_index, buf.fuse_map, buf.best_idx):
+        tns.fill_(SENTINEL)
+    buf.best_sim.fill_(float("nan"))
+    buf.mean_sim.fill_(float("nan"))
+    buf.workspace.fill_(0xCD)
+    ttf.ttf_compress_tied(x, r=r, t=t, anchor=anchor, buffers=buf)
+    torch.cuda.synchronize()
+    return buf
+
+
+def _compare_tied(x_np, buf, res):
+    B, F, H, W, C = x_np.shape
+    N = H * W
+    n = res.kept_count
+    np.testing.assert_array_equal(buf.anchor_index.cpu().numpy(), np.full(B, res.anchor_index))
+    np.testing.assert_array_equal(buf.best_idx.cpu().numpy(), res.best_idx)
+    np.testing.assert_array_equal(buf.fuse_map.cpu().numpy(), res.fuse_map)
+    assert int(buf.kept_count[0]) == n
+    src = buf.src_index.cpu().numpy()
+    np.testing.assert_array_equal(src[:n], res.src_index[:n])
+    assert (src[n:] == SENTINEL).all()
+    pos = buf.pos_ids.cpu().numpy()
+    np.testing.assert_array_equal(pos[:, :n], res.pos_ids[:, :n])
+    assert (pos[:, n:] == SENTINEL).all()
+    assert np.abs(buf.best_sim.cpu().numpy().astype(np.float64) - res.best_sim).max() <= 1e-5
+    assert np.abs(buf.mean_sim.cpu().numpy().astype(np.float64) - res.mean_sim).max() <= 1e-5
+    bits = np.uint16 if x_np.dtype == np.uint16 else np.uint32
+    got = rows_as_bits(buf.tokens_out.view(B * F * N, C)).reshape(B, F * N, C)
+    xin = x_np.reshape(B, F * N, C).view(bits)
+    fill = 0x7A7A if bits == np.uint16 else 0x7A7A7A7A
+    for b in range(B):
+        np.testing.assert_array_equal(got[b, :n], xin[b][res.src_index[:n]])
+        assert (got[b, n:] == fill).all()
+
+
+TIED = [
+    ("qwen3vl_2b", dict(B=3, F=6), 1, "auto"),                              # matrix-core path
+    ("qwen3vl_2b", dict(B=2, F=4, C=256), 2, "auto"),
+    ("qwen3vl_2b", dict(B=4, F=5, C=128), 0, 2),
+    ("highres_wide", dict(B=2, F=4, H=8, C=128), 2, "auto"),                # 32-wide grid
+    ("highres_wide", dict(B=2, F=3, H=4, C=128), 1, -1),
+    ("tiny", dict(B=3, F=5, H=7, W=9, C=40, dtype="f32"), 1, "auto"),       # general kernels
+    ("tiny", dict(B=2, F=4, H=5, W=13, C=129, dtype="bf16"), 3, "auto"),
+    ("tiny", dict(B=1, F=4, H=6, W=6, C=64, dtype="bf16"), 1, "auto"),      # B = 1: the plain pass
+    ("qwen3vl_2b", dict(B=2, F=1, C=128), 1, "auto"),                       # no source frame
+]
+
+
+@pytest.mark.parametrize("name,scale,r,anchor", TIED)
+def test_tied_batch(name, scale, r, anchor):
+    cfg = CONFIGS[name].scaled(**{**scale, "r": r, "shared_motion": True})
+    t = cfg.t[0]
+    batch, res = _tied_case(cfg, t, anchor)
+    buf = _run_tied(batch.x, r, t, anchor)
+    _compare_tied(batch.x, buf, res)
+    if cfg.F > 1 and cfg.B > 1:
+        assert 0 < (res.fuse_map >= 0).mean() < 1
+
+
+def test_tied_batch_at_headline_size():
+    cfg = CONFIGS["qwen3vl_8b_batched"].scaled(shared_motion=True)
+    t = cfg.t[0]
+    batch, res = _tied_case(cfg, t)
+    buf = _run_tied(batch.x, cfg.r, t)
+    _compare_tied(batch.x, buf, res)
+    assert (res.fuse_map >= 0).mean() > 0.2
+
+
+def test_tied_rejects_bad_arguments():
+    import paper_2605_07355_amd as ttf
+    from paper_2605_07355_amd import binding as bd
+    lib = ttf.load_library()
+    p = bd._make_params(2, 2, 2, 2, 8, bd.TTF_F32, 4, 0.7, "auto")            # r = 4 is beyond the mode's limit
+    n = ctypes.c_size_t(0)
+    assert lib.ttf_tied_workspace_size(ctypes.byref(p), ctypes.byref(n)) == bd.TTF_ERR_UNSUPPORTED
+    p = bd._make_params(2, 2, 2, 2, 8, bd.TTF_F32, 1, 0.7, "auto")
+    buf = torch.zeros(1 << 16, dtype=torch.int32, device="cuda")
+    q = buf.data_ptr()
+    o = bd._TiedOutputs(q, q, q, q, q, None, None, None, None, None)         # fuse_map missing
+    assert lib.ttf_compress_tied(ctypes.byref(p), q, q, 1 << 18, ctypes.byref(o), None) == bd.TTF_ERR_INVALID_ARG
+    o = bd._TiedOutputs(q, q, q, q, q, q, None, None, None, None)
+    assert lib.ttf_compress_tied(ctypes.byref(p), q, q, 16, ctypes.byref(o), None) == bd.TTF_ERR_WORKSPACE_TOO_SMALL
+    torch.cuda.synchronize()
+    assert int(buf.abs().sum()) == 0
