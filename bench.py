@@ -218,6 +218,26 @@ def main() -> int:
             extensions["compress_segment"] = entry(ms, nbytes, source_tokens=seg_tokens, rows=seg_rows,
                                                    GTok_per_s=round(seg_tokens / (ms * 1e-3) / 1e9, 4))
             del seg, anc, sbuf
+        # tied-batch mode on a batch whose clips share their motion (views of one scene dynamics)
+        if cfg.r <= 3:
+            tb = make_clip_batch(cfg.scaled(shared_motion=True))
+            if cfg.dtype == "bf16":
+                xt = torch.from_numpy(tb.x.view(np.int16)).to(dev).view(torch.bfloat16)
+            else:
+                xt = torch.from_numpy(tb.x).to(dev)
+            del tb
+            tbuf = ttf.TTFTiedBuffers.allocate(cfg.B, cfg.F, cfg.H, cfg.W, cfg.C, xt.dtype, dev, r=r)
+            ms = timed(lambda: ttf.ttf_compress_tied(xt, r=r, t=t, buffers=tbuf))
+            lp = int(tbuf.kept_count.item())
+            kwin = (2 * r + 1) ** 2
+            # both passes over the input, the window similarities written and read once, shared
+            # outputs, and the kept rows of every element written
+            nbytes = ((2.0 + 1.0 / cfg.F) * row_bytes + 8 * kwin + 4) * tokens + cfg.B * lp * row_bytes
+            extensions["compress_tied"] = entry(ms, nbytes, rows_per_element=lp,
+                                                fused_fraction=round(float((tbuf.fuse_map >= 0).sum().item())
+                                                                     / max(1, (cfg.F - 1) * cfg.N), 4),
+                                                GTok_per_s=round(tokens / (ms * 1e-3) / 1e9, 4))
+            del xt, tbuf
         ttf.ttf_compress(x, r=r, t=t, anchor="auto", buffers=buf, stream=stream)   # leave buf as the pass wrote it
         torch.cuda.synchronize()
 

@@ -7,7 +7,7 @@
 // M = (F-1) N source tokens, t = the rank-th smallest s^ with rank = clamp(ceil((1-phi) M), 1, M);
 // only tokens strictly above it are fused, so at most floor(phi M) are.  It is found exactly by a
 // most-significant-digit-first radix selection over an order-preserving integer image of the
-// floats: four passes of 256-bin counting, one workgroup per clip, integer LDS atomics only
+// floats: four passes of 256-bin counting, one workgroup per clip, integer LDS counters only
 // (counts do not depend on the order of the additions).
 #include "ttf_device.h"
 #include "ttf_internal.h"
@@ -33,17 +33,19 @@ __global__ __launch_bounds__(1024) void k_select_threshold(const float* __restri
                                                            int F, int N, long long rank)
 {
     const int b = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int a = anchor_index[b];
     const float* sim = best_sim + (size_t)b * F * N;
     const long long FN = (long long)F * N;
     const long long skip_lo = (long long)a * N, skip_hi = skip_lo + N;   // the anchor frame is not a source
-    __shared__ unsigned hist[256];
+    __shared__ unsigned hist[16][256];               // one histogram per wave: no cross-wave contention
+    __shared__ unsigned total[256];
     __shared__ uint32_t s_prefix;
     __shared__ long long s_k;
     if (threadIdx.x == 0) { s_prefix = 0u; s_k = rank - 1; }
     uint32_t mask = 0u;
     for (int shift = 24; shift >= 0; shift -= 8) {
-        if (threadIdx.x < 256) hist[threadIdx.x] = 0u;
+        for (int q = lane; q < 256; q += 64) hist[wave][q] = 0u;
         __syncthreads();
         const uint32_t prefix = s_prefix;
         // eight independent loads in flight per thread before their counts are added
@@ -58,17 +60,55 @@ __global__ __launch_bounds__(1024) void k_select_threshold(const float* __restri
             for (int u = 0; u < 8; ++u) {
                 const long long j = j0 + 1024 * u;
                 const uint32_t key = order_key(v[u]);
-                if (j < FN && (j < skip_lo || j >= skip_hi) && (key & mask) == prefix)
-                    atomicAdd(&hist[(key >> shift) & 255u], 1u);
+                const bool act = j < FN && (j < skip_lo || j >= skip_hi) && (key & mask) == prefix;
+                const uint32_t bin = (key >> shift) & 255u;
+                if (shift == 24) {
+                    // leading digit (sign and high exponent bits): similarities crowd into a few bins,
+                    // so lanes with equal bins are counted together and one lane adds the count
+                    uint64_t todo = __ballot(act);
+                    while (todo) {
+                        const int leader = __ffsll((unsigned long long)todo) - 1;
+                        const uint32_t lb = (uint32_t)__shfl((int)bin, leader, 64);
+                        const uint64_t same = __ballot(act && bin == lb);
+                        if (lane == leader) hist[wave][lb] += (unsigned)__popcll(same);
+                        todo &= ~same;
+                    }
+                } else if (act) {
+                    atomicAdd(&hist[wave][bin], 1u);
+                }
             }
         }
         __syncthreads();
-        if (threadIdx.x == 0) {                     // 256 bins: a serial walk is short next to the counting pass
-            long long k = s_k;
-            int d = 0;
-            while (d < 255 && k >= (long long)hist[d]) { k -= hist[d]; ++d; }
-            s_k = k;
-            s_prefix = prefix | ((uint32_t)d << shift);
+        if (threadIdx.x < 256) {
+            unsigned c = 0;
+#pragma unroll
+            for (int w = 0; w < 16; ++w) c += hist[w][threadIdx.x];
+            total[threadIdx.x] = c;
+        }
+        __syncthreads();
+        if (wave == 0) {
+            // find the bin that holds the k-th remaining key: lane l owns bins 4l..4l+3, a wave scan
+            // of the lane sums locates the lane, which then walks its four bins
+            const long long k = s_k;
+            unsigned c[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) c[e] = total[4 * lane + e];
+            const long long mine = (long long)c[0] + c[1] + c[2] + c[3];
+            long long incl = mine;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const long long o = __shfl_up(incl, d, 64);
+                if (lane >= d) incl += o;
+            }
+            const uint64_t hit = __ballot(k < incl);          // never empty: k < number of remaining keys
+            const int owner = hit ? __ffsll((unsigned long long)hit) - 1 : 63;
+            if (lane == owner) {
+                long long rest = k - (incl - mine);
+                int e = 0;
+                while (e < 3 && rest >= (long long)c[e]) { rest -= c[e]; ++e; }
+                s_k = rest;
+                s_prefix = prefix | ((uint32_t)(4 * lane + e) << shift);
+            }
         }
         mask |= 255u << shift;
         __syncthreads();

@@ -194,6 +194,7 @@ __global__ __launch_bounds__(64) void k_tied_anchor(const double* __restrict__ s
             double acc = 0.0;
             for (int b = 0; b < B; ++b) {
                 double vv = 0.0, uv = 0.0, uu = 0.0;
+#pragma unroll 8
                 for (int s = 0; s < S; ++s) {
                     vv += clip_part[(size_t)b * S + s];
                     const double2 o = *reinterpret_cast<const double2*>(score_part + (((size_t)b * S + s) * F + k) * 2);
