@@ -459,3 +459,20 @@ def test_tied_rejects_bad_arguments():
     assert lib.ttf_compress_tied(ctypes.byref(p), q, q, 16, ctypes.byref(o), None) == bd.TTF_ERR_WORKSPACE_TOO_SMALL
     torch.cuda.synchronize()
     assert int(buf.abs().sum()) == 0
+
+
+@pytest.mark.parametrize("H,W,C,dtype", [(4, 16, 128, "bf16"), (3, 5, 24, "f32")])
+def test_tied_ties_go_to_the_lowest_index(H, W, C, dtype):
+    """The anchor frame repeats a token in neighbouring cells and all frames are identical: equal
+    batch-mean similarities and equal anchor scores must resolve to the first maximum."""
+    from oracle import ttf_oracle as T
+    from workloads import f32_to_bf16_bits
+    rng = np.random.default_rng(51)
+    frame = rng.standard_normal((3, H, W, C)).astype(np.float32)
+    frame[:, :, 2] = frame[:, :, 1]
+    x = np.repeat(frame[:, None], 3, axis=1)
+    x = f32_to_bf16_bits(x) if dtype == "bf16" else x
+    res = T.compress_tied(x, 1, 0.5)
+    assert res.anchor_index == 0 and (res.best_idx[1].reshape(H, W)[:, 2] == np.arange(H) * W + 1).all()
+    buf = _run_tied(x, 1, 0.5)
+    _compare_tied(x, buf, res)

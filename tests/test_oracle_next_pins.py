@@ -364,3 +364,43 @@ def test_tied_union_rule_and_fixed_anchor(oracle):
     some = (res.best_sim > float(np.float32(t)))[:, src]
     assert (some.any(axis=0) & ~some.all(axis=0)).any()
     np.testing.assert_allclose(res.mean_sim[src] >= res.second_mean[src], True)
+
+
+def test_tied_gate_is_strict_per_element(oracle):
+    """cos((1,1,1,1),(1,0,0,0)) = 1/2 exactly.  At t = 1/2 that element is not above t, so the
+    position is kept although the other element matches perfectly; just below 1/2 it fuses."""
+    anchor = [[1, 0, 0, 0]]
+    x = np.array([[anchor, [[1, 1, 1, 1]]], [anchor, [[1, 0, 0, 0]]]], np.float32).reshape(2, 2, 1, 1, 4)
+    res = oracle.compress_tied(x, 0, 0.5, 1, 0)
+    np.testing.assert_array_equal(res.best_sim[:, 1, 0], [0.5, 1.0])
+    assert res.mean_sim[1, 0] == 0.75
+    assert res.fuse_map[1, 0] == -1 and res.kept_count == 2
+    res = oracle.compress_tied(x, 0, float(np.nextafter(np.float32(0.5), np.float32(0))), 1, 0)
+    assert res.fuse_map[1, 0] == 0 and res.kept_count == 1
+
+
+def test_tied_anchor_is_the_batch_mean_of_the_scores(oracle):
+    """Two elements that disagree about the best frame: the shared anchor follows the mean score,
+    checked against the single-clip scores of the already pinned plain pass."""
+    cfg = _tied_cfg(seed=46, B=4, shared_motion=False)
+    x = make_clip_batch(cfg).x
+    per = oracle.compress(x, 1, 0.6, want_tokens=False)
+    tied = oracle.compress_tied(x, 1, 0.6, want_tokens=False)
+    mean = per.anchor_score.mean(axis=0)
+    np.testing.assert_allclose(tied.anchor_score, mean, rtol=0, atol=1e-15)
+    assert tied.anchor_index == int(np.argmax(mean))
+    assert len(set(per.anchor_index.tolist())) > 1        # the elements alone would not agree
+
+
+def test_tied_ties_go_to_the_lowest_index(oracle):
+    """Equal batch-mean similarities at two anchor cells (the anchor frame repeats a token) and
+    equal anchor scores (identical frames): the first maximum wins in both rules."""
+    rng = np.random.default_rng(50)
+    frame = rng.standard_normal((2, 1, 4, 8)).astype(np.float32)        # B=2, grid 1x4
+    frame[:, 0, 2] = frame[:, 0, 1]                                     # cells 1 and 2 hold the same token
+    x = np.repeat(frame[:, None], 3, axis=1)                            # three identical frames
+    res = oracle.compress_tied(x, 1, 0.5)
+    assert res.anchor_index == 0                                        # all frames score the same
+    np.testing.assert_array_equal(res.best_idx[1], [0, 1, 1, 3])        # token 2 ties between cells 1 and 2
+    np.testing.assert_array_equal(res.best_idx[2], [0, 1, 1, 3])
+    assert res.second_mean[1, 2] == res.mean_sim[1, 2]                  # the twin is the runner-up
