@@ -23,7 +23,9 @@
 //  * Large problems: one wavefront per workgroup walks the whole channel axis, so its 16x16
 //    products are final and the epilogue is wave-local.  Small problems: the channel axis is split
 //    across 4 wavefronts and the partial products are added through LDS in wave order (fixed
-//    order: reproducible).  Either way one wave per source tile forms the cosines, masks the band,
+//    order: reproducible).  The 5x5 window on 32-wide grids (10 anchor tiles per K-step) has its
+//    own layout, k_search_mfma_shared: 4 waves with one frame each share the anchor fragments
+//    through LDS.  In every layout one wave per source tile forms the cosines, masks the band,
 //    takes the arg max (lowest anchor index on ties), applies the threshold and writes s^, dst,
 //    the fuse map and 16 keep bits.
 //  * Source squared norms: v_dot2 on the loaded fragments (one VGPR per tile), reduced with the
@@ -197,9 +199,22 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, g = lane >> 4;
     const int tpf = N / 32;                                  // workgroups per frame group
-    const int tp = blockIdx.x % tpf;
-    const int grp = (blockIdx.x / tpf) % groups;
-    const int b = blockIdx.x / tpf / groups;
+    // Workgroup -> (clip, frame group, 32-cell strip).  Workgroups are dealt to the 8 XCDs round
+    // robin and every XCD has its own L2, so when the strips divide evenly each XCD owns tpf/8
+    // ADJACENT strips (for every clip and frame group): the anchor rows its workgroups re-read
+    // overlap and stay resident in that L2 instead of being fetched again by every frame group.
+    int tp, grp, b;
+    if ((tpf & 7) == 0) {
+        const int chunk = tpf >> 3;
+        const int idx = blockIdx.x >> 3;
+        tp = (blockIdx.x & 7) * chunk + idx % chunk;
+        grp = (idx / chunk) % groups;
+        b = idx / chunk / groups;
+    } else {
+        tp = blockIdx.x % tpf;
+        grp = (blockIdx.x / tpf) % groups;
+        b = blockIdx.x / tpf / groups;
+    }
     const int a_in = anchor_index[b];                        // < 0: the anchor frame lies outside x (segment mode)
     const int a = a_in < 0 ? F : a_in;                       // then no frame of x is skipped
     const int i0 = tp * 32;                                  // first grid cell of this workgroup
@@ -348,6 +363,202 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
     }
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load of the wave (its fence covers global memory), which would drain the
+// source fragments requested a pass ahead; the data exchanged here lives in LDS alone.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Variant for shapes with many anchor tiles per source tile (5x5 window on a 32-wide grid: 10 anchor
+// tiles per K-step).  With two frames per wave the accumulators leave room for one wave per SIMD
+// only and nothing hides memory latency; with one frame per one-wave workgroup every workgroup
+// would fetch five times its source bytes in anchor fragments.  Here the 4 waves of a workgroup
+// work on the same 32-cell strip in 4*FW consecutive source frames (FW frames each, whole channel
+// axis, wave-local epilogue) and share the anchor fragments through LDS, which keeps the register
+// count at two waves per SIMD.  Loads complete in issue order, so the pipeline is arranged such
+// that the loads a wave has to wait for are always its oldest: per pass of KSW K-steps a wave
+// stores the anchor fragments it requested one pass ago to the idle LDS buffer, requests its share
+// of the anchor fragments of the pass after next and then the source fragments two passes ahead,
+// and computes the current pass from LDS and registers.
+template <int CT, int RAD, int KSW, int FW, bool ALL>
+__global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ anchor_frag,
+    const int32_t* __restrict__ anchor_index, const float* __restrict__ anchor_inv,
+    int32_t* __restrict__ fuse_map, float* __restrict__ best_sim, int32_t* __restrict__ best_idx,
+    uint16_t* __restrict__ keep16, float* __restrict__ win_sim, int F, int H, int C, float t, int groups)
+{
+    using S = Shape<CT, RAD>;
+    constexpr int W = S::W, NA = S::NA, NPS = S::NPS;
+    constexpr int NS = 2 * FW;                               // source tiles per wave (FW frames)
+    constexpr int FRG = 4 * FW;                              // frames per workgroup
+    constexpr int GL = KSW * NA / 4;                         // anchor fragments each wave stages per pass
+    static_assert((KSW * NA) % 4 == 0, "anchor fragments divide over the four waves");
+    extern __shared__ u32x4 frag_lds[];                      // [2][KSW][NA][64]
+    const int N = H * W;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps per-wave offsets scalar
+    const int m = lane & 15, g = lane >> 4;
+    const int tpf = N / 32;
+    int tp, grp, b;                                          // same XCD-aware mapping as k_search_mfma
+    if ((tpf & 7) == 0) {
+        const int chunk = tpf >> 3;
+        const int idx = blockIdx.x >> 3;
+        tp = (blockIdx.x & 7) * chunk + idx % chunk;
+        grp = (idx / chunk) % groups;
+        b = idx / chunk / groups;
+    } else {
+        tp = blockIdx.x % tpf;
+        grp = (blockIdx.x / tpf) % groups;
+        b = blockIdx.x / tpf / groups;
+    }
+    const int a_in = anchor_index[b];
+    const int a = a_in < 0 ? F : a_in;
+    const int nsrc = a_in < 0 ? F : F - 1;
+    const int i0 = tp * 32;
+    const int ylo = i0 / W - RAD;
+    const int KS = C / 32;
+    const int passes = KS / KSW;
+
+    const uint16_t* sp[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        const int si = min(grp * FRG + wave * FW + s / 2, nsrc - 1);
+        const int k = si + (si >= a ? 1 : 0);
+        sp[s] = x + (((size_t)b * F + k) * N + i0 + 16 * (s % 2) + (lane >> 2)) * (size_t)C + (lane & 3) * 8;
+    }
+    const int bperm = (4 * m + g) * 4;
+    // this wave's share of a pass's anchor fragments: fragment e = wave + 4*i is (K-step e / NA, tile
+    // e % NA); offsets are wave-uniform (scalar registers), the lane part is added at the access
+    const uint16_t* gbase = anchor_frag + (size_t)b * (N / 16) * KS * 512 + lane * 8;
+    int goff[GL], gslot[GL];
+#pragma unroll
+    for (int i = 0; i < GL; ++i) {
+        const int e = wave + 4 * i, ks = e / NA, q = e % NA;
+        const int yy = min(max(ylo + S::tile_row(q), 0), H - 1);
+        const int tile = yy * CT + S::tile_col(q);
+        goff[i] = (tile * KS + ks) * 512;
+        gslot[i] = (ks * NA + q) * 64;
+    }
+
+    f32x4 acc[NS][NPS];
+    float nv[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        nv[s] = 0.f;
+#pragma unroll
+        for (int q = 0; q < NPS; ++q) acc[s][q] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    u32x4 A[3][NS][KSW];                                     // native vectors: plain SSA values, never memory
+    u32x4 G[GL];
+    // (macros, not lambdas: captured by a lambda the staged fragments were kept in scratch memory)
+#define TTF_REQUEST_ANCHOR(pass_)                                                                             \
+    do {                                                                                                      \
+        const int pq = min((pass_), passes - 1);                                                              \
+        _Pragma("unroll") for (int i = 0; i < GL; ++i)                                                        \
+            G[i] = *reinterpret_cast<const u32x4*>(gbase + goff[i] + pq * (KSW * 512));                       \
+    } while (0)
+#define TTF_REQUEST_SOURCE(pass_, Abuf)                                                                       \
+    do {                                                                                                      \
+        const int pq = min((pass_), passes - 1);                                                              \
+        _Pragma("unroll") for (int ks = 0; ks < KSW; ++ks) {                                                  \
+            _Pragma("unroll") for (int s = 0; s < NS; ++s)                                                    \
+                Abuf[s][ks] = *reinterpret_cast<const u32x4*>(sp[s] + (pq * KSW + ks) * 32);                  \
+        }                                                                                                     \
+    } while (0)
+#define TTF_STAGE(buf_)                                                                                       \
+    do {                                                                                                      \
+        _Pragma("unroll") for (int i = 0; i < GL; ++i)                                                        \
+            frag_lds[(buf_) * (KSW * NA * 64) + gslot[i] + lane] = G[i];                                      \
+    } while (0)
+    auto compute = [&](int buf, const u32x4 (&Abuf)[NS][KSW]) {
+#pragma unroll
+        for (int ks = 0; ks < KSW; ++ks) {
+            bf16x8 av[NS];                                   // source tiles in operand order
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                uint32_t r[4] = {Abuf[s][ks][0], Abuf[s][ks][1], Abuf[s][ks][2], Abuf[s][ks][3]};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bf16x2 p = __builtin_bit_cast(bf16x2, r[e]);
+                    nv[s] = __builtin_amdgcn_fdot2_f32_bf16(p, p, nv[s], false);
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) r[e] = (uint32_t)__builtin_amdgcn_ds_bpermute(bperm, (int)r[e]);
+                av[s] = __builtin_bit_cast(bf16x8, uint4{r[0], r[1], r[2], r[3]});
+            }
+            // one anchor tile at a time from LDS, used by every source tile paired with it
+#pragma unroll
+            for (int qa = 0; qa < NA; ++qa) {
+                const bf16x8 bt = __builtin_bit_cast(bf16x8, frag_lds[buf * (KSW * NA * 64) + (ks * NA + qa) * 64 + lane]);
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    const int q = CT == 1 ? qa - s % 2 : qa;     // pair index of anchor tile qa for this source tile
+                    if (q >= 0 && q < NPS)
+                        acc[s][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[s], bt, acc[s][q], 0, 0, 0);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);               // keep the K-steps apart: bounded live ranges
+        }
+    };
+
+    // State at the top of pass p: LDS buffer p%2 holds the anchor fragments of pass p; the source
+    // fragments of passes p and p+1 (A[p%3], A[(p+1)%3]) and the anchor fragments of pass p+1 (G) are
+    // already requested.  Every value is used in a later iteration than the one that requested it,
+    // so no load can be moved next to its use; the anchor loads waited for are always older than
+    // the source loads that may still be in flight, which therefore stay in flight (two passes of
+    // source data per wave) across the wait.
+    TTF_REQUEST_ANCHOR(0);
+    TTF_REQUEST_SOURCE(0, A[0]);
+    TTF_STAGE(0);
+    lds_barrier();
+    TTF_REQUEST_ANCHOR(1);
+    TTF_REQUEST_SOURCE(1, A[1]);
+#define TTF_PASS(j)                                                   \
+    do {                                                              \
+        const int pp = pass + (j);                                    \
+        TTF_STAGE((pp + 1) & 1);                                      \
+        TTF_REQUEST_ANCHOR(pp + 2);                                   \
+        TTF_REQUEST_SOURCE(pp + 2, A[((j) + 2) % 3]);                 \
+        __builtin_amdgcn_sched_barrier(0);                            \
+        compute(pp & 1, A[(j)]);                                      \
+        __builtin_amdgcn_sched_barrier(0);                            \
+        lds_barrier();                                                \
+    } while (0)
+    for (int pass = 0; pass < passes; pass += 3) {
+        TTF_PASS(0);
+        if (pass + 1 < passes) TTF_PASS(1);                  // wave-uniform
+        if (pass + 2 < passes) TTF_PASS(2);
+    }
+#undef TTF_PASS
+#undef TTF_REQUEST_ANCHOR
+#undef TTF_REQUEST_SOURCE
+#undef TTF_STAGE
+
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        nv[s] += __shfl_xor(nv[s], 1, 64);
+        nv[s] += __shfl_xor(nv[s], 2, 64);
+    }
+    float ai_tile[NA];                                       // this lane's anchor inverse norms (epilogue only)
+#pragma unroll
+    for (int q = 0; q < NA; ++q) {
+        const int yy = min(max(ylo + S::tile_row(q), 0), H - 1);
+        ai_tile[q] = anchor_inv[(size_t)b * N + 16 * (yy * CT + S::tile_col(q)) + m];
+    }
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        float nn[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) nn[j] = __shfl(nv[s], 4 * (4 * g + j), 64);
+        const int si = grp * FRG + wave * FW + s / 2;
+        finish_tile<CT, RAD, ALL>(acc[s], nn, s, si < nsrc, min(si, nsrc - 1), a, b, F, H, i0, t, ai_tile, fuse_map,
+                                  best_sim, best_idx, keep16, win_sim, lane);
+    }
+}
+
 template <int CT, int RAD>
 hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,
                         const int32_t* anchor_index, int32_t* fuse_map, float* best_sim, int32_t* best_idx,
@@ -363,6 +574,29 @@ hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor
     const unsigned grid = (unsigned)blocks;
     const int ks_total = p.C / 32;                           // K-steps per token
     uint16_t* keep16 = reinterpret_cast<uint16_t*>(w.keep_bits);
+    if constexpr (S::NPS > 6) {
+        // many anchor tiles per source tile (32-wide grid, 5x5 window): workgroups of 4 waves x 1 frame
+        // sharing the anchor fragments in LDS, as soon as there are enough of them to cover the chip
+        // twice (measured on B4 F64 32x32 C4096 r2: 0.48-0.52 ms against 0.58-0.60 ms for one-wave
+        // workgroups; for the smaller windows the split-channel kernel below is as fast or faster)
+        constexpr int FWS = 1;                               // frames per wave
+        const int groups8 = (nsrc + 4 * FWS - 1) / (4 * FWS);
+        const size_t wgs = (size_t)p.B * groups8 * (N / 32);
+        constexpr int KSWS = 2;                              // K-steps per pass of the shared-anchor kernel
+        if (wgs >= 2 * 256 && ks_total % KSWS == 0) {
+            const size_t lds = 2 * KSWS * (size_t)S::NA * 1024;
+            auto go = [&](auto kernel) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                if (e != hipSuccess) return e;
+                kernel<<<(unsigned)wgs, 256, lds, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv, fuse_map,
+                                                       best_sim, best_idx, keep16, win_sim, p.F, p.H, p.C, p.t, groups8);
+                return hipGetLastError();
+            };
+            return win_sim ? go(k_search_mfma_shared<CT, RAD, KSWS, FWS, true>)
+                           : go(k_search_mfma_shared<CT, RAD, KSWS, FWS, false>);
+        }
+    }
 #define TTF_LAUNCH_AS(KSW, NW, ALL)                                                                           \
     k_search_mfma<CT, RAD, KSW, NW, ALL><<<grid, NW * 64, 0, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv,  \
                                                                   fuse_map, best_sim, best_idx, keep16, win_sim,  \
@@ -376,7 +610,8 @@ hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor
     // channel axis (no cross-wave sum, no LDS).  With fewer, such long-running single waves
     // leave SIMDs unevenly loaded (measured: 0.24 ms against 0.20 ms on 1024 workgroups), so the
     // channels are split over four waves instead.
-    if (blocks >= 3 * kSimds * S::OCC && ks_total % 2 == 0) TTF_LAUNCH(2, 1);
+    if (blocks >= 3 * kSimds * S::OCC && S::OCC == 1 && ks_total % 4 == 0) TTF_LAUNCH(4, 1);
+    else if (blocks >= 3 * kSimds * S::OCC && ks_total % 2 == 0) TTF_LAUNCH(2, 1);
     else if (ks_total % 8 == 0) TTF_LAUNCH(2, 4);
     else TTF_LAUNCH(1, 4);
 #undef TTF_LAUNCH

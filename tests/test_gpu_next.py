@@ -275,6 +275,7 @@ SEGMENTS = [
     ("qwen3vl_2b", dict(B=1, F=2), 1),                                 # one-frame segment
     ("qwen3vl_2b", dict(B=2, F=10, C=256), 2),                         # more frames than one workgroup group
     ("highres_wide", dict(B=1, F=4, H=8, C=128), 2),                   # 32-wide grid
+    ("highres_wide", dict(B=2, F=18, H=64, C=128), 2),                 # LDS-shared anchor kernel, 17 source frames
     ("tiny", dict(B=3, F=5, H=7, W=9, C=40, dtype="f32"), 1),          # general kernels, ragged keep words
     ("tiny", dict(B=2, F=3, H=5, W=13, C=129, dtype="bf16"), 3),
 ]
@@ -420,6 +421,7 @@ TIED = [
     ("tiny", dict(B=2, F=4, H=5, W=13, C=129, dtype="bf16"), 3, "auto"),
     ("tiny", dict(B=1, F=4, H=6, W=6, C=64, dtype="bf16"), 1, "auto"),      # B = 1: the plain pass
     ("qwen3vl_2b", dict(B=2, F=1, C=128), 1, "auto"),                       # no source frame
+    ("highres_wide", dict(B=2, F=18, H=64, C=128), 2, "auto"),              # LDS-shared anchor kernel, all-window form
 ]
 
 

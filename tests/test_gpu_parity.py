@@ -101,6 +101,9 @@ SHAPES = [
     (2, 3, 12, 20, 64, "f32", 30),       # radius beyond the grid: global matching
     (1, 2, 1, 1, 8, "f32", 1),           # single-token frames
     (1, 9, 3, 200, 32, "bf16", 1),       # wide, flat grid
+    (2, 18, 64, 32, 128, "bf16", 2),     # 32-wide 5x5 with >= 512 workgroups: LDS-shared anchor kernel,
+                                         # 17 source frames = 4 full groups of 4 and one group with one frame
+    (1, 6, 512, 32, 128, "bf16", 2),     # same kernel on a tall grid, 5 source frames (second group: one frame)
 ]
 
 
