@@ -258,6 +258,10 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 // the tile once with coalesced loads (lane l: chunk l%4 of token l/4), accumulates squared
 // norms, permutes every 16x64-byte block into MFMA operand order (lane = token + 16*chunk) and
 // stores it as one contiguous KiB: anchor_frag[b][tile][K-step][lane][8 bf16].
+// PAD: the grid is Wg <= 16*CT tokens wide; a tile is 16 columns of one grid row, columns at and
+// beyond Wg are padding (zero fragments, inverse norm 0), and tiles are numbered row * CT + column
+// tile.  Without PAD a tile is 16 consecutive flat tokens (the same thing when Wg == 16*CT).
+template <bool PAD>
 __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restrict__ x,
                                                         const uint16_t* __restrict__ ext_anchor,
                                                         const double* __restrict__ score_part,
@@ -267,10 +271,10 @@ __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restri
                                                         uint16_t* __restrict__ anchor_frag,
                                                         int32_t* __restrict__ fuse_map, float* __restrict__ best_sim,
                                                         int32_t* __restrict__ best_idx, uint16_t* __restrict__ keep16,
-                                                        int F, int N, int C, int S, int fixed_anchor)
+                                                        int F, int N, int C, int S, int fixed_anchor, int tiles,
+                                                        int Wg, int CT)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int tiles = N / 16;
     const int b = blockIdx.x / tiles, tile = blockIdx.x % tiles;
     // the anchor is a frame of x (fixed, picked here, or already chosen: kAnchorGiven), or frame b
     // of ext_anchor (published as -1)
@@ -279,16 +283,20 @@ __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restri
                 : fixed_anchor == kAnchorGiven ? anchor_index[b]
                                                : pick_anchor(score_part, clip_part, b, F, S, lane);
     if (fixed_anchor != kAnchorGiven && tile == 0 && threadIdx.x == 0) anchor_index[b] = a;
-    if (a >= 0 && fuse_map && threadIdx.x < 16) {            // anchor tokens are always retained
-        const size_t o = ((size_t)b * F + a) * N + 16 * tile + threadIdx.x;
+    // flat index of the tile's first token, and how many of its 16 columns exist
+    const int first = PAD ? (tile / CT) * Wg + 16 * (tile % CT) : 16 * tile;
+    const int ncol = PAD ? min(16, Wg - 16 * (tile % CT)) : 16;
+    if (a >= 0 && fuse_map && (int)threadIdx.x < ncol) {     // anchor tokens are always retained
+        const size_t o = ((size_t)b * F + a) * N + first + threadIdx.x;
         fuse_map[o] = -1;
         if (best_sim) best_sim[o] = 1.0f;
-        if (best_idx) best_idx[o] = 16 * tile + (int)threadIdx.x;
-        if (threadIdx.x == 0) keep16[o / 16] = 0xffffu;
+        if (best_idx) best_idx[o] = first + (int)threadIdx.x;
+        if (!PAD && threadIdx.x == 0) keep16[o / 16] = 0xffffu;
     }
     const int KS = C / 32;
     const uint16_t* frame = ext_anchor ? ext_anchor + (size_t)b * N * C : x + ((size_t)b * F + a) * N * C;
-    const uint16_t* src = frame + (size_t)(16 * tile + (lane >> 2)) * C + (lane & 3) * 8;
+    const bool real = (lane >> 2) < ncol;                    // this lane's token exists (padding reads the tile's first)
+    const uint16_t* src = frame + (size_t)(first + (real ? lane >> 2 : 0)) * C + (lane & 3) * 8;
     uint16_t* dst = anchor_frag + ((size_t)b * tiles + tile) * (size_t)KS * 512 + lane * 8;
     const int bperm = (4 * (lane & 15) + (lane >> 4)) * 4;
     float nn = 0.f;
@@ -298,7 +306,10 @@ __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restri
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
             const int ks = k0 + 8 * u;
-            if (ks < KS) v[u] = *reinterpret_cast<const uint4*>(src + (size_t)ks * 32);
+            if (ks < KS) {
+                v[u] = *reinterpret_cast<const uint4*>(src + (size_t)ks * 32);
+                if (PAD && !real) v[u] = uint4{0u, 0u, 0u, 0u};
+            }
         }
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
@@ -324,7 +335,7 @@ __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restri
         float ss = part[0][threadIdx.x];
 #pragma unroll
         for (int w = 1; w < 8; ++w) ss += part[w][threadIdx.x];
-        anchor_inv[(size_t)b * N + 16 * tile + threadIdx.x] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+        anchor_inv[((size_t)b * tiles + tile) * 16 + threadIdx.x] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
     }
 }
 
@@ -398,13 +409,18 @@ hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const 
 {
     const int N = p.H * p.W;
     const int fixed = anchor_given ? kAnchorGiven : fixed_frame(p);
-    k_anchor_prepare<<<(unsigned)(p.B * (N / 16)), 512, 0, s>>>(static_cast<const uint16_t*>(x),
-                                                                static_cast<const uint16_t*>(ext_anchor), w.score_part,
-                                                                w.clip_part, anchor_index, w.anchor_inv,
-                                                                w.anchor_frag, fuse_map, best_sim, best_idx,
-                                                                reinterpret_cast<uint16_t*>(w.keep_bits),
-                                                                p.F, N, p.C, (p.C + 255) / 256, fixed);
-    return hipGetLastError();
+    const bool pad = mfma_search_padded(p);
+    const int CT = p.W <= 16 ? 1 : 2;
+    const int tiles = pad ? p.H * CT : N / 16;
+    auto go = [&](auto kernel) {
+        kernel<<<(unsigned)(p.B * tiles), 512, 0, s>>>(static_cast<const uint16_t*>(x),
+                                                       static_cast<const uint16_t*>(ext_anchor), w.score_part,
+                                                       w.clip_part, anchor_index, w.anchor_inv, w.anchor_frag, fuse_map,
+                                                       best_sim, best_idx, reinterpret_cast<uint16_t*>(w.keep_bits),
+                                                       p.F, N, p.C, (p.C + 255) / 256, fixed, tiles, p.W, CT);
+        return hipGetLastError();
+    };
+    return pad ? go(k_anchor_prepare<true>) : go(k_anchor_prepare<false>);
 }
 
 }  // namespace ttf

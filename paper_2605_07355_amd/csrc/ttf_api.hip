@@ -20,18 +20,18 @@ hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool ex
 // bf16 tokens on 16- or 32-wide grids take the matrix-core kernels; everything else (fp32 input,
 // other grids, large radii, odd channel counts) takes the general wave-per-token kernel.  Setting
 // the environment variable TTF_SEARCH=general forces the general kernels (for comparisons).
-bool use_mfma_path(const ttf_params& p)
+bool use_mfma_path(const ttf_params& p, bool tied = false)
 {
     const char* force = std::getenv("TTF_SEARCH");
     const bool general = force && std::strcmp(force, "general") == 0;
-    return !general && mfma_search_supported(p);
+    return !general && (mfma_search_supported(p) || (!tied && mfma_search_padded(p)));
 }
 
 hipError_t launch_window_search(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                 const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                 int32_t* best_idx, float* win_sim, hipStream_t s)
 {
-    if (use_mfma_path(p))
+    if (use_mfma_path(p, win_sim != nullptr))
         return launch_window_search_mfma(p, x, ext_anchor != nullptr, w, anchor_index, fuse_map, best_sim, best_idx,
                                          win_sim, s);
     return launch_window_search_generic(p, x, ext_anchor, w, anchor_index, fuse_map, best_sim, best_idx, win_sim, s);
@@ -209,7 +209,7 @@ ttf_status ttf_compress_tied(const ttf_params* params, const void* features, voi
         TTF_STEP(launch_anchor_scores(p, w, s));
     }
     TTF_STEP(launch_tied_anchor(p, w, out->anchor_index, s));
-    if (use_mfma_path(p))
+    if (use_mfma_path(p, true))
         TTF_STEP(launch_anchor_prepare_mfma(p, features, nullptr, w, out->anchor_index, nullptr, nullptr, nullptr,
                                             true, s));
     else TTF_STEP(launch_anchor_norms(p, features, nullptr, w, out->anchor_index, true, s));

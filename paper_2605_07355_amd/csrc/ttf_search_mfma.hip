@@ -97,16 +97,19 @@ __device__ __forceinline__ bf16x8 load_frag(const uint16_t* p)
 // bits.  Straight-line code: no divergent branches.
 // ALL (tied-batch mode): instead of the arg max, every in-window cosine is stored to
 // win_sim[token][(dy+RAD)*(2*RAD+1) + (dx+RAD)] and nothing else is written.
-template <int CT, int RAD, bool ALL>
+// PAD: the grid is Wg <= W tokens wide (columns Wg..W-1 of every tile row are padding): flat
+// indices use Wg, padding columns never win nor get written, H may be odd, and the keep bits are
+// packed afterwards by k_pack_keep (tiles are no longer aligned to 16-bit pieces of keep words).
+template <int CT, int RAD, bool ALL, bool PAD = false>
 __device__ __forceinline__ void finish_tile(const f32x4* v, const float* nn, int s, bool live, int si, int a, int b,
                                             int F, int H, int i0, float t, const float* ai_tile,
                                             int32_t* __restrict__ fuse_map, float* __restrict__ best_sim,
                                             int32_t* __restrict__ best_idx, uint16_t* __restrict__ keep16,
-                                            float* __restrict__ win_sim, int lane)
+                                            float* __restrict__ win_sim, int lane, int Wg = Shape<CT, RAD>::W)
 {
     using S = Shape<CT, RAD>;
     constexpr int W = S::W, NPS = S::NPS;
-    const int N = H * W;
+    const int N = PAD ? H * Wg : H * W;
     const int m = lane & 15, g = lane >> 4;
     const int u = s % 2;                                     // tile within the frame
     const int y0 = i0 / W, ylo = y0 - RAD;
@@ -141,8 +144,8 @@ __device__ __forceinline__ void finish_tile(const f32x4* v, const float* nn, int
         // anchor tile of pair q: CT==1: row ysrc-RAD+q; CT==2: row ylo + q/2, column q%2
         const int yy = CT == 1 ? ysrc - RAD + q : ylo + q / 2;
         const int xa_col = (CT == 1 ? 0 : 16 * (q % 2)) + m;      // this lane's anchor column
-        const bool row_ok = (yy >= 0) & (yy < H);
-        const int ja = min(max(yy, 0), H - 1) * W + xa_col;
+        const bool row_ok = PAD ? (yy >= 0) & (yy < H) & (xa_col < Wg) : (yy >= 0) & (yy < H);
+        const int ja = min(max(yy, 0), H - 1) * (PAD ? Wg : W) + xa_col;
         const float ai = ai_tile[S::pair_tile(u, q)];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -164,6 +167,22 @@ __device__ __forceinline__ void finish_tile(const f32x4* v, const float* nn, int
         arg[j] = arg[j] == kNoArg ? -1 : arg[j];
     }
     const int k = si + (si >= a ? 1 : 0);
+    if constexpr (PAD) {
+        const size_t row0 = ((size_t)b * F + k) * N + (size_t)ysrc * Wg;
+        if (m == 0 && live && ysrc < H) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int xs = xsrc0 + 4 * g + j;
+                if (xs < Wg) {
+                    const bool fused = best[j] > t;               // keep = 1[s^ <= t]
+                    fuse_map[row0 + xs] = fused ? arg[j] : -1;
+                    if (best_sim) best_sim[row0 + xs] = best[j];
+                    if (best_idx) best_idx[row0 + xs] = arg[j];
+                }
+            }
+        }
+        return;
+    }
     const size_t o0 = ((size_t)b * F + k) * N + i0 + 16 * u;
     unsigned keep = 0;
     if (m == 0) {
@@ -382,12 +401,13 @@ __device__ __forceinline__ void lds_barrier()
 // stores the anchor fragments it requested one pass ago to the idle LDS buffer, requests its share
 // of the anchor fragments of the pass after next and then the source fragments two passes ahead,
 // and computes the current pass from LDS and registers.
-template <int CT, int RAD, int KSW, int FW, bool ALL>
+// PAD: grids narrower than the tile row (Wg <= 16*CT) and of any height; see finish_tile.
+template <int CT, int RAD, int KSW, int FW, bool ALL, bool PAD = false>
 __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ anchor_frag,
     const int32_t* __restrict__ anchor_index, const float* __restrict__ anchor_inv,
     int32_t* __restrict__ fuse_map, float* __restrict__ best_sim, int32_t* __restrict__ best_idx,
-    uint16_t* __restrict__ keep16, float* __restrict__ win_sim, int F, int H, int C, float t, int groups)
+    uint16_t* __restrict__ keep16, float* __restrict__ win_sim, int F, int H, int C, float t, int groups, int Wg)
 {
     using S = Shape<CT, RAD>;
     constexpr int W = S::W, NA = S::NA, NPS = S::NPS;
@@ -396,11 +416,12 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
     constexpr int GL = KSW * NA / 4;                         // anchor fragments each wave stages per pass
     static_assert((KSW * NA) % 4 == 0, "anchor fragments divide over the four waves");
     extern __shared__ u32x4 frag_lds[];                      // [2][KSW][NA][64]
-    const int N = H * W;
+    const int N = PAD ? H * Wg : H * W;                      // tokens per frame
+    const int NT = H * CT;                                   // anchor tiles per frame (tile rows x column tiles)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps per-wave offsets scalar
     const int m = lane & 15, g = lane >> 4;
-    const int tpf = N / 32;
+    const int tpf = PAD ? (CT == 1 ? (H + 1) / 2 : H) : N / 32;          // 32-cell strips per frame
     int tp, grp, b;                                          // same XCD-aware mapping as k_search_mfma
     if ((tpf & 7) == 0) {
         const int chunk = tpf >> 3;
@@ -416,7 +437,7 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
     const int a_in = anchor_index[b];
     const int a = a_in < 0 ? F : a_in;
     const int nsrc = a_in < 0 ? F : F - 1;
-    const int i0 = tp * 32;
+    const int i0 = tp * 32;                                  // first cell of the strip in tile-row coordinates
     const int ylo = i0 / W - RAD;
     const int KS = C / 32;
     const int passes = KS / KSW;
@@ -426,12 +447,18 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
     for (int s = 0; s < NS; ++s) {
         const int si = min(grp * FRG + wave * FW + s / 2, nsrc - 1);
         const int k = si + (si >= a ? 1 : 0);
-        sp[s] = x + (((size_t)b * F + k) * N + i0 + 16 * (s % 2) + (lane >> 2)) * (size_t)C + (lane & 3) * 8;
+        size_t cell = i0 + 16 * (s % 2) + (lane >> 2);       // flat token index inside the frame
+        if constexpr (PAD) {                                 // padding cells read a valid token; results are dropped
+            const int ys = min(i0 / W + (CT == 1 ? s % 2 : 0), H - 1);
+            const int xs = min((CT == 1 ? 0 : 16 * (s % 2)) + (lane >> 2), Wg - 1);
+            cell = (size_t)ys * Wg + xs;
+        }
+        sp[s] = x + (((size_t)b * F + k) * N + cell) * (size_t)C + (lane & 3) * 8;
     }
     const int bperm = (4 * m + g) * 4;
     // this wave's share of a pass's anchor fragments: fragment e = wave + 4*i is (K-step e / NA, tile
     // e % NA); offsets are wave-uniform (scalar registers), the lane part is added at the access
-    const uint16_t* gbase = anchor_frag + (size_t)b * (N / 16) * KS * 512 + lane * 8;
+    const uint16_t* gbase = anchor_frag + (size_t)b * NT * KS * 512 + lane * 8;
     int goff[GL], gslot[GL];
 #pragma unroll
     for (int i = 0; i < GL; ++i) {
@@ -546,7 +573,7 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
 #pragma unroll
     for (int q = 0; q < NA; ++q) {
         const int yy = min(max(ylo + S::tile_row(q), 0), H - 1);
-        ai_tile[q] = anchor_inv[(size_t)b * N + 16 * (yy * CT + S::tile_col(q)) + m];
+        ai_tile[q] = anchor_inv[(size_t)b * NT * 16 + 16 * (yy * CT + S::tile_col(q)) + m];
     }
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
@@ -554,8 +581,8 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
 #pragma unroll
         for (int j = 0; j < 4; ++j) nn[j] = __shfl(nv[s], 4 * (4 * g + j), 64);
         const int si = grp * FRG + wave * FW + s / 2;
-        finish_tile<CT, RAD, ALL>(acc[s], nn, s, si < nsrc, min(si, nsrc - 1), a, b, F, H, i0, t, ai_tile, fuse_map,
-                                  best_sim, best_idx, keep16, win_sim, lane);
+        finish_tile<CT, RAD, ALL, PAD>(acc[s], nn, s, si < nsrc, min(si, nsrc - 1), a, b, F, H, i0, t, ai_tile,
+                                       fuse_map, best_sim, best_idx, keep16, win_sim, lane, Wg);
     }
 }
 
@@ -590,7 +617,8 @@ hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
                 if (e != hipSuccess) return e;
                 kernel<<<(unsigned)wgs, 256, lds, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv, fuse_map,
-                                                       best_sim, best_idx, keep16, win_sim, p.F, p.H, p.C, p.t, groups8);
+                                                       best_sim, best_idx, keep16, win_sim, p.F, p.H, p.C, p.t, groups8,
+                                                       p.W);
                 return hipGetLastError();
             };
             return win_sim ? go(k_search_mfma_shared<CT, RAD, KSWS, FWS, true>)
@@ -619,6 +647,54 @@ hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor
     return hipGetLastError();
 }
 
+// Keep words from the fuse map (padded grids): bit i of frame (b,k) is set iff the token is an
+// anchor token or was not fused.  One wave per 64-token word.
+__global__ __launch_bounds__(256) void k_pack_keep(const int32_t* __restrict__ fuse_map,
+                                                   const int32_t* __restrict__ anchor_index,
+                                                   uint64_t* __restrict__ keep_bits, int F, int N, int NW, size_t words)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t wd = (size_t)blockIdx.x * 4 + wave;
+    if (wd >= words) return;
+    const size_t frame = wd / NW;
+    const int i = (int)(wd % NW) * 64 + lane;
+    const int b = (int)(frame / F), k = (int)(frame % F);
+    const bool keep = i < N && (k == anchor_index[b] || fuse_map[frame * (size_t)N + i] < 0);
+    const uint64_t bits = __ballot(keep);
+    if (lane == 0) keep_bits[wd] = bits;
+}
+
+// Grids up to 32 tokens wide that are not exactly 16 or 32 wide (or whose height does not make
+// whole keep words): the LDS-shared kernel on tile rows padded to 16 or 32 columns.
+template <int CT, int RAD>
+hipError_t launch_padded(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,
+                         const int32_t* anchor_index, int32_t* fuse_map, float* best_sim, int32_t* best_idx,
+                         hipStream_t s)
+{
+    using S = Shape<CT, RAD>;
+    const int nsrc = external_anchor ? p.F : p.F - 1;
+    const int N = p.H * p.W, NW = (N + 63) / 64;
+    const size_t words = (size_t)p.B * p.F * NW;
+    if (nsrc >= 1) {
+        constexpr int FWS = S::NPS <= 3 ? 2 : 1, KSWS = 2;
+        const int groups = (nsrc + 4 * FWS - 1) / (4 * FWS);
+        const int strips = CT == 1 ? (p.H + 1) / 2 : p.H;
+        const size_t wgs = (size_t)p.B * groups * strips;
+        const size_t lds = 2 * KSWS * (size_t)S::NA * 1024;
+        auto kernel = k_search_mfma_shared<CT, RAD, KSWS, FWS, false, true>;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        kernel<<<(unsigned)wgs, 256, lds, s>>>(static_cast<const uint16_t*>(x), w.anchor_frag, anchor_index,
+                                               w.anchor_inv, fuse_map, best_sim, best_idx, nullptr, nullptr, p.F, p.H,
+                                               p.C, p.t, groups, p.W);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    k_pack_keep<<<(unsigned)((words + 3) / 4), 256, 0, s>>>(fuse_map, anchor_index, w.keep_bits, p.F, N, NW, words);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 // True when the matrix-core kernels cover this problem: bf16, grid width 16 or 32, radius <= 2,
@@ -632,10 +708,31 @@ bool mfma_search_supported(const ttf_params& p)
     return false;
 }
 
+// Same element type, radius and channel conditions, but any grid up to 32 tokens wide and any
+// height: served by the padded-tile kernels (not in tied-batch mode).
+bool mfma_search_padded(const ttf_params& p)
+{
+    if (p.dtype != TTF_BF16 || p.r > 2 || p.C % 128 != 0 || p.W > 32) return false;
+    return !mfma_search_supported(p);
+}
+
 hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,
                                      const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                      int32_t* best_idx, float* win_sim, hipStream_t s)
 {
+    if (mfma_search_padded(p)) {
+#define TTF_PCASE(CT, RAD)                              \
+    if ((p.W <= 16) == (CT == 1) && p.r == RAD)         \
+    return launch_padded<CT, RAD>(p, x, external_anchor, w, anchor_index, fuse_map, best_sim, best_idx, s)
+        TTF_PCASE(1, 0);
+        TTF_PCASE(1, 1);
+        TTF_PCASE(1, 2);
+        TTF_PCASE(2, 0);
+        TTF_PCASE(2, 1);
+        TTF_PCASE(2, 2);
+#undef TTF_PCASE
+        return hipErrorInvalidValue;
+    }
 #define TTF_CASE(CT, RAD)             \
     if (p.W == 16 * CT && p.r == RAD) \
     return launch_shape<CT, RAD>(p, x, external_anchor, w, anchor_index, fuse_map, best_sim, best_idx, win_sim, s)

@@ -31,6 +31,7 @@ def _prepared(cfg, ts, r=None):
 
 SMALL = [
     ("tiny", {}),
+    ("qwen3vl_2b", dict(B=2, F=5, H=14, W=14, C=128)),                 # matrix-core path on padded tile rows
     ("qwen3vl_2b", dict(B=2, F=6)),                                    # matrix-core search path, 16x16 grid
     ("tiny", dict(B=3, F=5, H=7, W=9, C=40, dtype="f32")),             # ragged keep words, scalar rows
     ("tiny", dict(B=2, F=4, H=5, W=13, C=129, dtype="bf16")),          # odd row length (2-byte copies)
@@ -278,6 +279,8 @@ SEGMENTS = [
     ("highres_wide", dict(B=2, F=18, H=64, C=128), 2),                 # LDS-shared anchor kernel, 17 source frames
     ("tiny", dict(B=3, F=5, H=7, W=9, C=40, dtype="f32"), 1),          # general kernels, ragged keep words
     ("tiny", dict(B=2, F=3, H=5, W=13, C=129, dtype="bf16"), 3),
+    ("qwen3vl_2b", dict(B=2, F=7, H=14, W=14, C=128), 1),              # padded tile rows, external anchor
+    ("qwen3vl_2b", dict(B=1, F=4, H=9, W=24, C=256), 2),
 ]
 
 
@@ -421,6 +424,7 @@ TIED = [
     ("tiny", dict(B=2, F=4, H=5, W=13, C=129, dtype="bf16"), 3, "auto"),
     ("tiny", dict(B=1, F=4, H=6, W=6, C=64, dtype="bf16"), 1, "auto"),      # B = 1: the plain pass
     ("qwen3vl_2b", dict(B=2, F=1, C=128), 1, "auto"),                       # no source frame
+    ("qwen3vl_2b", dict(B=3, F=4, H=14, W=14, C=128), 1, "auto"),           # 14x14: tied mode takes the general kernels
     ("highres_wide", dict(B=2, F=18, H=64, C=128), 2, "auto"),              # LDS-shared anchor kernel, all-window form
 ]
 

@@ -104,6 +104,16 @@ SHAPES = [
     (2, 18, 64, 32, 128, "bf16", 2),     # 32-wide 5x5 with >= 512 workgroups: LDS-shared anchor kernel,
                                          # 17 source frames = 4 full groups of 4 and one group with one frame
     (1, 6, 512, 32, 128, "bf16", 2),     # same kernel on a tall grid, 5 source frames (second group: one frame)
+    # grids up to 32 wide that are not 16 or 32 wide, or whose height leaves partial keep words: padded tile rows
+    (2, 6, 14, 14, 128, "bf16", 1),      # 14x14: one padded column tile, N = 196
+    (1, 11, 18, 24, 256, "bf16", 1),     # 24 wide: second column tile half empty; 10 source frames (two groups)
+    (2, 4, 15, 20, 128, "bf16", 2),      # odd height, 5x5 window
+    (1, 3, 27, 27, 128, "bf16", 0),      # 1x1 window
+    (1, 5, 6, 16, 384, "bf16", 1),       # 16 wide but H % 4 != 0
+    (2, 3, 5, 32, 128, "bf16", 2),       # 32 wide, odd height
+    (1, 4, 3, 9, 128, "bf16", 1),        # fewer rows than a strip pair
+    (1, 2, 1, 17, 128, "bf16", 2),       # a single grid row
+    (3, 10, 7, 31, 128, "bf16", 1),
 ]
 
 
