@@ -410,7 +410,7 @@ hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const 
     const int N = p.H * p.W;
     const int fixed = anchor_given ? kAnchorGiven : fixed_frame(p);
     const bool pad = mfma_search_padded(p);
-    const int CT = p.W <= 16 ? 1 : 2;
+    const int CT = (p.W + 15) / 16;                          // column tiles per grid row
     const int tiles = pad ? p.H * CT : N / 16;
     auto go = [&](auto kernel) {
         kernel<<<(unsigned)(p.B * tiles), 512, 0, s>>>(static_cast<const uint16_t*>(x),

@@ -19,8 +19,8 @@ struct Workspace {
     float*    frame_sum;     // [B,F,C]  sum over the N tokens of every frame (anchor rule, inner sum)
     double*   score_part;    // [B,S,F,2] per 256-channel slice: <frame sum, clip sum> and |frame sum|^2
     double*   clip_part;     // [B,S]    per slice: |clip sum|^2          (S = ceil(C/256))
-    float*    anchor_inv;    // [B,NP]   1/||x_{a,j}|| of every anchor token (0 for a zero token); NP = N, or the
-                             //          token count of the grid with rows padded to 16 / 32 columns (W <= 32)
+    float*    anchor_inv;    // [B,NP]   1/||x_{a,j}|| of every anchor token (0 for a zero token); NP = token count
+                             //          of the grid with rows padded to whole 16-column tiles (N when W % 16 == 0)
     uint16_t* anchor_frag;   // [B,NP/16,C/32,64,8] bf16 anchor frame in MFMA fragment order (matrix-core path)
     uint64_t* keep_bits;     // [B,F,NW] bit i%64 of word i/64 set iff token i is kept (NW=ceil(N/64))
     int32_t*  frame_base;    // [B,F]    output row of the first kept token of every frame
@@ -30,7 +30,7 @@ struct Workspace {
 inline Workspace carve(const ttf_params& p, void* base)
 {
     const size_t B = p.B, F = p.F, N = (size_t)p.H * p.W, C = p.C, NW = (N + 63) / 64;
-    const size_t NP = p.W <= 32 ? (size_t)p.H * (p.W <= 16 ? 16 : 32) : N;   // tile rows padded to 16 / 32 columns
+    const size_t NP = (size_t)p.H * ((p.W + 15) / 16) * 16;   // grid rows padded to whole 16-column tiles
     size_t off = 0;
     auto take = [&](size_t n) { size_t o = off; off = align_up(off + n, 256); return o; };
     const size_t o_fs = take(B * F * C * sizeof(float));
@@ -70,7 +70,7 @@ hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const 
                                       int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                       int32_t* best_idx, bool anchor_given, hipStream_t s);
 bool mfma_search_supported(const ttf_params& p);   // grids exactly 16 or 32 wide with whole keep words
-bool mfma_search_padded(const ttf_params& p);      // other grids up to 32 wide (padded tile rows)
+bool mfma_search_padded(const ttf_params& p);      // every other grid (tile rows padded to 16 columns)
 hipError_t launch_window_search(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                 const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                 int32_t* best_idx, float* win_sim, hipStream_t s);

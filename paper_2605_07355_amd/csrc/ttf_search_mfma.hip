@@ -43,16 +43,20 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr float kNegInf = -__builtin_inff();
 constexpr size_t kSimds = 256 * 4;             // SIMDs of the chip: wave slots per unit of occupancy
 
-// Geometry of one workgroup's problem.  CT = W/16 column tiles per grid row.
+// Geometry of one workgroup's problem: a strip of 32 grid cells (two source tiles of 16).
+// CT = 1: grid (tile row) 16 wide, the strip is two rows.  CT = 2: 32 wide, the strip is one row.
+// CT = 3: any wider grid; the strip is 32 consecutive columns of one row starting at column tile
+// c0 (even), and the anchor tiles fetched are column tiles c0-1 .. c0+2 of the rows around it.
 template <int CT, int RAD>
 struct Shape {
-    static_assert(CT == 1 || CT == 2, "grids of width 16 or 32");
-    static constexpr int W = 16 * CT;
+    static_assert(CT >= 1 && CT <= 3, "1: 16 wide, 2: 32 wide, 3: wider");
+    static constexpr int W = CT == 1 ? 16 : 32;              // cells per strip row
     static constexpr int ROWS = 2 * RAD + 1;
-    // anchor tiles fetched per K-step: CT==1: rows y0-RAD .. y0+1+RAD; CT==2: rows y-RAD .. y+RAD, 2 columns
-    static constexpr int NA = CT == 1 ? 2 * RAD + 2 : 2 * ROWS;
-    // anchor tiles paired with each source tile
-    static constexpr int NPS = CT == 1 ? ROWS : 2 * ROWS;
+    // anchor tiles fetched per K-step: CT==1: rows y0-RAD .. y0+1+RAD; CT==2: rows y-RAD .. y+RAD, 2 columns;
+    // CT==3: the same rows, 4 columns
+    static constexpr int NA = CT == 1 ? 2 * RAD + 2 : (CT == 2 ? 2 : 4) * ROWS;
+    // anchor tiles paired with each source tile (CT==3: the column tile itself and both neighbours)
+    static constexpr int NPS = CT == 1 ? ROWS : (CT == 2 ? 2 : 3) * ROWS;
     // source frames per workgroup and anchor fragment prefetch distance: sized so accumulators
     // (4*NPS VGPRs per source tile), source fragments (4 per tile and K-step) and the anchor
     // ring (4*NA per K-step) fit the 256 VGPRs of a wave at two waves per SIMD
@@ -62,9 +66,18 @@ struct Shape {
     static constexpr int PF = 1;
     // source tiles whose partial products go through LDS together (<= 48 KiB)
     static constexpr int RT = NPS <= 3 ? 4 : (NPS <= 6 ? 2 : 1);
-    __device__ static constexpr int pair_tile(int u, int q) { return CT == 1 ? u + q : q; }   // u = tile within frame
-    __device__ static constexpr int tile_row(int a) { return CT == 1 ? a : a / 2; }           // offset from ylo
-    __device__ static constexpr int tile_col(int a) { return CT == 1 ? 0 : a % 2; }
+    // fetched anchor tile that pair q of source tile u (tile within the strip) uses
+    __device__ static constexpr int pair_tile(int u, int q)
+    {
+        return CT == 1 ? u + q : (CT == 2 ? q : (q / 3) * 4 + u + q % 3);
+    }
+    // fetched anchor tile a: row offset from ylo, column tile relative to the strip's first
+    __device__ static constexpr int tile_row(int a) { return CT == 1 ? a : (CT == 2 ? a / 2 : a / 4); }
+    __device__ static constexpr int tile_col(int a) { return CT == 1 ? 0 : (CT == 2 ? a % 2 : a % 4 - 1); }
+    // pair q of source tile u: anchor row offset from the source row - RAD, and anchor column tile
+    // relative to the strip's first column tile
+    __device__ static constexpr int pair_row(int u, int q) { return CT == 1 ? q : (CT == 2 ? q / 2 : q / 3); }
+    __device__ static constexpr int pair_col(int u, int q) { return CT == 1 ? 0 : (CT == 2 ? q % 2 : u - 1 + q % 3); }
 };
 
 constexpr int kNoArg = 0x7fffffff;       // "no candidate yet" while reducing (so that min() breaks ties)
@@ -105,8 +118,10 @@ __device__ __forceinline__ void finish_tile(const f32x4* v, const float* nn, int
                                             int F, int H, int i0, float t, const float* ai_tile,
                                             int32_t* __restrict__ fuse_map, float* __restrict__ best_sim,
                                             int32_t* __restrict__ best_idx, uint16_t* __restrict__ keep16,
-                                            float* __restrict__ win_sim, int lane, int Wg = Shape<CT, RAD>::W)
+                                            float* __restrict__ win_sim, int lane, int Wg = Shape<CT, RAD>::W,
+                                            int c0 = 0)
 {
+    static_assert(PAD || CT <= 2, "wider grids only through the padded path");
     using S = Shape<CT, RAD>;
     constexpr int W = S::W, NPS = S::NPS;
     const int N = PAD ? H * Wg : H * W;
@@ -119,7 +134,7 @@ __device__ __forceinline__ void finish_tile(const f32x4* v, const float* nn, int
     float best[4] = {kNegInf, kNegInf, kNegInf, kNegInf};
     int arg[4] = {kNoArg, kNoArg, kNoArg, kNoArg};
     const int ysrc = y0 + (CT == 1 ? u : 0);
-    const int xsrc0 = CT == 1 ? 0 : 16 * u;
+    const int xsrc0 = CT == 1 ? 0 : 16 * (c0 + u);           // c0 = 0 unless CT == 3
     if constexpr (ALL) {
         constexpr int K1 = 2 * RAD + 1;
         const int kk = si + (si >= a ? 1 : 0);
@@ -141,10 +156,11 @@ __device__ __forceinline__ void finish_tile(const f32x4* v, const float* nn, int
     }
 #pragma unroll
     for (int q = 0; q < NPS; ++q) {
-        // anchor tile of pair q: CT==1: row ysrc-RAD+q; CT==2: row ylo + q/2, column q%2
-        const int yy = CT == 1 ? ysrc - RAD + q : ylo + q / 2;
-        const int xa_col = (CT == 1 ? 0 : 16 * (q % 2)) + m;      // this lane's anchor column
-        const bool row_ok = PAD ? (yy >= 0) & (yy < H) & (xa_col < Wg) : (yy >= 0) & (yy < H);
+        // anchor tile of pair q: CT==1: row ysrc-RAD+q; CT==2: row ylo + q/2, column tile q%2;
+        // CT==3: row ylo + q/3, column tile c0 + u - 1 + q%3
+        const int yy = ysrc - RAD + S::pair_row(u, q);
+        const int xa_col = 16 * (c0 + S::pair_col(u, q)) + m;     // this lane's anchor column
+        const bool row_ok = PAD ? (yy >= 0) & (yy < H) & (xa_col >= 0) & (xa_col < Wg) : (yy >= 0) & (yy < H);
         const int ja = min(max(yy, 0), H - 1) * (PAD ? Wg : W) + xa_col;
         const float ai = ai_tile[S::pair_tile(u, q)];
 #pragma unroll
@@ -416,12 +432,15 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
     constexpr int GL = KSW * NA / 4;                         // anchor fragments each wave stages per pass
     static_assert((KSW * NA) % 4 == 0, "anchor fragments divide over the four waves");
     extern __shared__ u32x4 frag_lds[];                      // [2][KSW][NA][64]
+    static_assert(PAD || CT <= 2, "wider grids only through the padded path");
     const int N = PAD ? H * Wg : H * W;                      // tokens per frame
-    const int NT = H * CT;                                   // anchor tiles per frame (tile rows x column tiles)
+    const int CTt = CT <= 2 ? CT : (Wg + 15) / 16;           // column tiles per grid row
+    const int NT = H * CTt;                                  // anchor tiles per frame (tile rows x column tiles)
+    const int spr = (CTt + 1) / 2;                           // strips per grid row (CT == 3)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps per-wave offsets scalar
     const int m = lane & 15, g = lane >> 4;
-    const int tpf = PAD ? (CT == 1 ? (H + 1) / 2 : H) : N / 32;          // 32-cell strips per frame
+    const int tpf = PAD ? (CT == 1 ? (H + 1) / 2 : (CT == 2 ? H : H * spr)) : N / 32;   // 32-cell strips per frame
     int tp, grp, b;                                          // same XCD-aware mapping as k_search_mfma
     if ((tpf & 7) == 0) {
         const int chunk = tpf >> 3;
@@ -437,8 +456,11 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
     const int a_in = anchor_index[b];
     const int a = a_in < 0 ? F : a_in;
     const int nsrc = a_in < 0 ? F : F - 1;
-    const int i0 = tp * 32;                                  // first cell of the strip in tile-row coordinates
-    const int ylo = i0 / W - RAD;
+    // first source row y0 and first column tile c0 of the strip; i0 = y0 * W is what finish_tile decodes
+    const int y0 = CT == 3 ? tp / spr : tp * 32 / W;
+    const int c0 = CT == 3 ? 2 * (tp % spr) : 0;
+    const int i0 = CT == 3 ? y0 * W : tp * 32;
+    const int ylo = y0 - RAD;
     const int KS = C / 32;
     const int passes = KS / KSW;
 
@@ -449,8 +471,8 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
         const int k = si + (si >= a ? 1 : 0);
         size_t cell = i0 + 16 * (s % 2) + (lane >> 2);       // flat token index inside the frame
         if constexpr (PAD) {                                 // padding cells read a valid token; results are dropped
-            const int ys = min(i0 / W + (CT == 1 ? s % 2 : 0), H - 1);
-            const int xs = min((CT == 1 ? 0 : 16 * (s % 2)) + (lane >> 2), Wg - 1);
+            const int ys = min(y0 + (CT == 1 ? s % 2 : 0), H - 1);
+            const int xs = min((CT == 1 ? 0 : 16 * (c0 + s % 2)) + (lane >> 2), Wg - 1);
             cell = (size_t)ys * Wg + xs;
         }
         sp[s] = x + (((size_t)b * F + k) * N + cell) * (size_t)C + (lane & 3) * 8;
@@ -464,7 +486,7 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
     for (int i = 0; i < GL; ++i) {
         const int e = wave + 4 * i, ks = e / NA, q = e % NA;
         const int yy = min(max(ylo + S::tile_row(q), 0), H - 1);
-        const int tile = yy * CT + S::tile_col(q);
+        const int tile = yy * CTt + min(max(c0 + S::tile_col(q), 0), CTt - 1);   // outside the grid: clamped, masked later
         goff[i] = (tile * KS + ks) * 512;
         gslot[i] = (ks * NA + q) * 64;
     }
@@ -522,9 +544,11 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
                 const bf16x8 bt = __builtin_bit_cast(bf16x8, frag_lds[buf * (KSW * NA * 64) + (ks * NA + qa) * 64 + lane]);
 #pragma unroll
                 for (int s = 0; s < NS; ++s) {
-                    const int q = CT == 1 ? qa - s % 2 : qa;     // pair index of anchor tile qa for this source tile
-                    if (q >= 0 && q < NPS)
-                        acc[s][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[s], bt, acc[s][q], 0, 0, 0);
+#pragma unroll
+                    for (int q = 0; q < NPS; ++q) {              // the pair (if any) of this source tile that uses tile qa
+                        if (S::pair_tile(s % 2, q) == qa)
+                            acc[s][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[s], bt, acc[s][q], 0, 0, 0);
+                    }
                 }
             }
             __builtin_amdgcn_sched_barrier(0);               // keep the K-steps apart: bounded live ranges
@@ -573,7 +597,7 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
 #pragma unroll
     for (int q = 0; q < NA; ++q) {
         const int yy = min(max(ylo + S::tile_row(q), 0), H - 1);
-        ai_tile[q] = anchor_inv[(size_t)b * NT * 16 + 16 * (yy * CT + S::tile_col(q)) + m];
+        ai_tile[q] = anchor_inv[(size_t)b * NT * 16 + 16 * (yy * CTt + min(max(c0 + S::tile_col(q), 0), CTt - 1)) + m];
     }
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
@@ -582,7 +606,7 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
         for (int j = 0; j < 4; ++j) nn[j] = __shfl(nv[s], 4 * (4 * g + j), 64);
         const int si = grp * FRG + wave * FW + s / 2;
         finish_tile<CT, RAD, ALL, PAD>(acc[s], nn, s, si < nsrc, min(si, nsrc - 1), a, b, F, H, i0, t, ai_tile,
-                                       fuse_map, best_sim, best_idx, keep16, win_sim, lane, Wg);
+                                       fuse_map, best_sim, best_idx, keep16, win_sim, lane, Wg, c0);
     }
 }
 
@@ -664,8 +688,8 @@ __global__ __launch_bounds__(256) void k_pack_keep(const int32_t* __restrict__ f
     if (lane == 0) keep_bits[wd] = bits;
 }
 
-// Grids up to 32 tokens wide that are not exactly 16 or 32 wide (or whose height does not make
-// whole keep words): the LDS-shared kernel on tile rows padded to 16 or 32 columns.
+// Grids that are not exactly 16 or 32 wide (or whose height does not make whole keep words): the
+// LDS-shared kernel on tile rows padded to whole 16-column tiles.
 template <int CT, int RAD>
 hipError_t launch_padded(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,
                          const int32_t* anchor_index, int32_t* fuse_map, float* best_sim, int32_t* best_idx,
@@ -678,7 +702,7 @@ hipError_t launch_padded(const ttf_params& p, const void* x, bool external_ancho
     if (nsrc >= 1) {
         constexpr int FWS = S::NPS <= 3 ? 2 : 1, KSWS = 2;
         const int groups = (nsrc + 4 * FWS - 1) / (4 * FWS);
-        const int strips = CT == 1 ? (p.H + 1) / 2 : p.H;
+        const int strips = CT == 1 ? (p.H + 1) / 2 : (CT == 2 ? p.H : p.H * (((p.W + 15) / 16 + 1) / 2));
         const size_t wgs = (size_t)p.B * groups * strips;
         const size_t lds = 2 * KSWS * (size_t)S::NA * 1024;
         auto kernel = k_search_mfma_shared<CT, RAD, KSWS, FWS, false, true>;
@@ -708,11 +732,11 @@ bool mfma_search_supported(const ttf_params& p)
     return false;
 }
 
-// Same element type, radius and channel conditions, but any grid up to 32 tokens wide and any
-// height: served by the padded-tile kernels (not in tied-batch mode).
+// Same element type, radius and channel conditions, but any grid: served by the padded-tile
+// kernels (not in tied-batch mode).
 bool mfma_search_padded(const ttf_params& p)
 {
-    if (p.dtype != TTF_BF16 || p.r > 2 || p.C % 128 != 0 || p.W > 32) return false;
+    if (p.dtype != TTF_BF16 || p.r > 2 || p.C % 128 != 0) return false;
     return !mfma_search_supported(p);
 }
 
@@ -721,8 +745,9 @@ hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool ex
                                      int32_t* best_idx, float* win_sim, hipStream_t s)
 {
     if (mfma_search_padded(p)) {
+        const int ct = p.W <= 16 ? 1 : (p.W <= 32 ? 2 : 3);
 #define TTF_PCASE(CT, RAD)                              \
-    if ((p.W <= 16) == (CT == 1) && p.r == RAD)         \
+    if (ct == CT && p.r == RAD)                         \
     return launch_padded<CT, RAD>(p, x, external_anchor, w, anchor_index, fuse_map, best_sim, best_idx, s)
         TTF_PCASE(1, 0);
         TTF_PCASE(1, 1);
@@ -730,6 +755,9 @@ hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool ex
         TTF_PCASE(2, 0);
         TTF_PCASE(2, 1);
         TTF_PCASE(2, 2);
+        TTF_PCASE(3, 0);
+        TTF_PCASE(3, 1);
+        TTF_PCASE(3, 2);
 #undef TTF_PCASE
         return hipErrorInvalidValue;
     }

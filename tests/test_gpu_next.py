@@ -281,6 +281,7 @@ SEGMENTS = [
     ("tiny", dict(B=2, F=3, H=5, W=13, C=129, dtype="bf16"), 3),
     ("qwen3vl_2b", dict(B=2, F=7, H=14, W=14, C=128), 1),              # padded tile rows, external anchor
     ("qwen3vl_2b", dict(B=1, F=4, H=9, W=24, C=256), 2),
+    ("qwen3vl_2b", dict(B=1, F=6, H=7, W=44, C=128), 1),               # wider than 32
 ]
 
 

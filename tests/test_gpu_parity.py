@@ -114,6 +114,13 @@ SHAPES = [
     (1, 4, 3, 9, 128, "bf16", 1),        # fewer rows than a strip pair
     (1, 2, 1, 17, 128, "bf16", 2),       # a single grid row
     (3, 10, 7, 31, 128, "bf16", 1),
+    # wider than 32: strips of 32 columns with the neighbouring column tiles on both sides
+    (1, 5, 9, 40, 128, "bf16", 1),       # 3 column tiles, the last half empty; odd tile count
+    (2, 4, 6, 48, 128, "bf16", 2),       # 5x5 window
+    (1, 3, 4, 100, 256, "bf16", 0),      # 7 column tiles
+    (1, 6, 5, 33, 128, "bf16", 1),       # one token in the third column tile
+    (1, 4, 3, 64, 128, "bf16", 2),       # whole tiles only
+    (2, 9, 20, 36, 128, "bf16", 1),
 ]
 
 
