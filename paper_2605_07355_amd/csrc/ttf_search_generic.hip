@@ -5,9 +5,11 @@
 // cells [max(0,y-r), min(H-1,y+r)] x [max(0,x-r), min(W-1,x+r)], each counted once after the
 // duplicate masking the paper prescribes; walking those cells in ascending flat index and
 // keeping the first maximum is the row-major arg max over offsets.  One wavefront handles one
-// token at a time (16 wavefronts per 64-token keep word): lanes stride over channels, products
-// accumulate in fp32, a butterfly adds the lanes.  Candidates are taken in groups of G so the
-// source row is read once per group.
+// token at a time: lanes stride over channels, products accumulate in fp32, a butterfly adds the
+// lanes.  Candidates are taken in groups of G so the source row is read once per group.  A
+// workgroup is 16 wavefronts with TPW tokens each: 4 (one workgroup per 64-token keep word) on
+// large inputs, 1 (a quarter word per workgroup, four times the workgroups) on small ones, where
+// the serial walk of a wave over its tokens is the whole run time.
 #include <type_traits>
 
 #include "ttf_device.h"
@@ -21,7 +23,7 @@ constexpr float kNegInf = -__builtin_inff();
 
 // ALL = false: arg max and gate per token.  ALL = true (tied-batch mode): every window similarity
 // is written to win_sim[token][(dy+r)*(2r+1) + (dx+r)] instead and nothing else is produced.
-template <typename T, int V, bool ALL>
+template <typename T, int V, bool ALL, int TPW>
 __global__ __launch_bounds__(1024) void k_search_generic(
     const T* __restrict__ x, const T* __restrict__ ext_anchor, const int32_t* __restrict__ anchor_index,
     const float* __restrict__ anchor_inv,
@@ -31,8 +33,10 @@ __global__ __launch_bounds__(1024) void k_search_generic(
 {
     const int N = H * W;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int word = blockIdx.x % NW;                 // 64-token group inside the frame
-    const size_t frame = blockIdx.x / NW;             // b*F + k
+    constexpr int PARTS = 4 / TPW;                    // workgroups per keep word
+    const int part = blockIdx.x % PARTS;
+    const int word = (blockIdx.x / PARTS) % NW;       // 64-token group inside the frame
+    const size_t frame = blockIdx.x / PARTS / NW;     // b*F + k
     const int b = (int)(frame / F), k = (int)(frame % F);
     const int a = anchor_index[b];                    // < 0: the anchor frames are in ext_anchor [B,N,C]
     __shared__ unsigned long long keep_word;
@@ -42,8 +46,8 @@ __global__ __launch_bounds__(1024) void k_search_generic(
     const T* anchor = a < 0 ? ext_anchor + (size_t)b * N * C : x + ((size_t)b * F + a) * (size_t)N * C;
     const float* ainv = anchor_inv + (size_t)b * N;
 
-    for (int q = 0; q < 4; ++q) {
-        const int i = word * 64 + wave * 4 + q;       // wave-uniform
+    for (int q = 0; q < TPW; ++q) {
+        const int i = word * 64 + part * (16 * TPW) + wave * TPW + q;   // wave-uniform
         if (i >= N) break;
         const size_t o = frame * (size_t)N + i;
         if (k == a) {                                 // anchor tokens are always retained
@@ -117,7 +121,14 @@ __global__ __launch_bounds__(1024) void k_search_generic(
         }
     }
     __syncthreads();
-    if (!ALL && threadIdx.x == 0) keep_bits[frame * (size_t)NW + word] = keep_word;
+    if (!ALL && threadIdx.x == 0) {
+        if constexpr (TPW == 4) {
+            keep_bits[frame * (size_t)NW + word] = keep_word;
+        } else {                                      // this workgroup's 16 bits of the word
+            uint16_t* keep16 = reinterpret_cast<uint16_t*>(keep_bits);
+            keep16[(frame * (size_t)NW + word) * 4 + part] = (uint16_t)(keep_word >> (16 * part));
+        }
+    }
 }
 
 }  // namespace
@@ -127,18 +138,19 @@ hipError_t launch_window_search_generic(const ttf_params& p, const void* x, cons
                                         int32_t* best_idx, float* win_sim, hipStream_t s)
 {
     const int N = p.H * p.W, NW = (N + 63) / 64;
-    const unsigned grid = (unsigned)((size_t)p.B * p.F * NW);
+    const size_t words = (size_t)p.B * p.F * NW;
+    const bool small = words < 2048;                  // fewer than two workgroups per CU at 4 tokens per wave
+    const unsigned grid = (unsigned)(small ? 4 * words : words);
     auto go = [&](auto tag, auto vtag) {
         using T = decltype(tag);
         constexpr int V = decltype(vtag)::value;
-        if (win_sim)
-            k_search_generic<T, V, true><<<grid, 1024, 0, s>>>(
-                static_cast<const T*>(x), static_cast<const T*>(ext_anchor), anchor_index, w.anchor_inv, fuse_map,
-                best_sim, best_idx, w.keep_bits, win_sim, p.F, p.H, p.W, p.C, p.r, p.t, NW);
-        else
-            k_search_generic<T, V, false><<<grid, 1024, 0, s>>>(
-                static_cast<const T*>(x), static_cast<const T*>(ext_anchor), anchor_index, w.anchor_inv, fuse_map,
-                best_sim, best_idx, w.keep_bits, win_sim, p.F, p.H, p.W, p.C, p.r, p.t, NW);
+#define TTF_GEN(ALL, TPW)                                                                                       \
+    k_search_generic<T, V, ALL, TPW><<<grid, 1024, 0, s>>>(                                                     \
+        static_cast<const T*>(x), static_cast<const T*>(ext_anchor), anchor_index, w.anchor_inv, fuse_map,      \
+        best_sim, best_idx, w.keep_bits, win_sim, p.F, p.H, p.W, p.C, p.r, p.t, NW)
+        if (win_sim) { if (small) TTF_GEN(true, 1); else TTF_GEN(true, 4); }
+        else { if (small) TTF_GEN(false, 1); else TTF_GEN(false, 4); }
+#undef TTF_GEN
         return hipGetLastError();
     };
     if (p.dtype == TTF_BF16)

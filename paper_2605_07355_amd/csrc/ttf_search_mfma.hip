@@ -219,7 +219,9 @@ __device__ __forceinline__ void finish_tile(const f32x4* v, const float* nn, int
     if (lane == 0 && live) keep16[o0 / 16] = (uint16_t)keep;
 }
 
-template <int CT, int RAD, int KSW, int NW, bool ALL>
+// FRO: source frames per workgroup, 0 = the shape's default.  Small inputs use 1 frame and long
+// passes (more workgroups, fewer dependent rounds of loads per workgroup).
+template <int CT, int RAD, int KSW, int NW, bool ALL, int FRO = 0>
 __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ anchor_frag,
     const int32_t* __restrict__ anchor_index, const float* __restrict__ anchor_inv,
@@ -227,8 +229,10 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
     uint16_t* __restrict__ keep16, float* __restrict__ win_sim, int F, int H, int C, float t, int passes, int groups)
 {
     using S = Shape<CT, RAD>;
-    constexpr int W = S::W, NA = S::NA, NPS = S::NPS, FR = S::FR, PF = S::PF, RT = S::RT;
+    constexpr int W = S::W, NA = S::NA, NPS = S::NPS, PF = S::PF;
+    constexpr int FR = FRO ? FRO : S::FR;
     constexpr int NS = 2 * FR;                               // source tiles of the workgroup
+    constexpr int RT = S::RT < NS ? S::RT : NS;              // source tiles per LDS round
     constexpr int NB = PF + 1;                               // anchor fragment ring
     const int N = H * W;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -350,7 +354,7 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
             float nn[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) nn[j] = __shfl(nv[s], 4 * (4 * g + j), 64);
-            finish_tile<CT, RAD, ALL>(acc[s], nn, s, grp * S::FR + s / 2 < nsrc, min(grp * S::FR + s / 2, nsrc - 1),
+            finish_tile<CT, RAD, ALL>(acc[s], nn, s, grp * FR + s / 2 < nsrc, min(grp * FR + s / 2, nsrc - 1),
                                       a, b, F, H, i0, t, ai_tile, fuse_map, best_sim, best_idx, keep16, win_sim, lane);
         }
     } else {
@@ -389,7 +393,7 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
                         v[q][0] += p[0]; v[q][1] += p[1]; v[q][2] += p[2]; v[q][3] += p[3];
                     }
                 }
-                finish_tile<CT, RAD, ALL>(v, nn, s, grp * S::FR + s / 2 < nsrc, min(grp * S::FR + s / 2, nsrc - 1),
+                finish_tile<CT, RAD, ALL>(v, nn, s, grp * FR + s / 2 < nsrc, min(grp * FR + s / 2, nsrc - 1),
                                           a, b, F, H, i0, t, ai_tile, fuse_map, best_sim, best_idx, keep16, win_sim,
                                           lane);
             }
@@ -662,7 +666,20 @@ hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor
     // channel axis (no cross-wave sum, no LDS).  With fewer, such long-running single waves
     // leave SIMDs unevenly loaded (measured: 0.24 ms against 0.20 ms on 1024 workgroups), so the
     // channels are split over four waves instead.
-    if (blocks >= 3 * kSimds * S::OCC && S::OCC == 1 && ks_total % 4 == 0) TTF_LAUNCH(4, 1);
+    if (blocks < 256 && ks_total % 32 == 0) {
+        // fewer workgroups than CUs: one source frame per workgroup (up to FR times the workgroups)
+        // and 8 K-steps per pass, so that a workgroup waits for memory C/1024 times instead of C/256
+        // times (B1 F32 16x16 C2048: 0.024 -> 0.013 ms; anchor fragments come from L2 either way)
+        const unsigned grid1 = (unsigned)((size_t)p.B * nsrc * (N / 32));
+        if (win_sim)
+            k_search_mfma<CT, RAD, 8, 4, true, 1><<<grid1, 256, 0, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv,
+                                                                        fuse_map, best_sim, best_idx, keep16, win_sim,
+                                                                        p.F, p.H, p.C, p.t, ks_total / 32, nsrc);
+        else
+            k_search_mfma<CT, RAD, 8, 4, false, 1><<<grid1, 256, 0, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv,
+                                                                         fuse_map, best_sim, best_idx, keep16, win_sim,
+                                                                         p.F, p.H, p.C, p.t, ks_total / 32, nsrc);
+    } else if (blocks >= 3 * kSimds * S::OCC && S::OCC == 1 && ks_total % 4 == 0) TTF_LAUNCH(4, 1);
     else if (blocks >= 3 * kSimds * S::OCC && ks_total % 2 == 0) TTF_LAUNCH(2, 1);
     else if (ks_total % 8 == 0) TTF_LAUNCH(2, 4);
     else TTF_LAUNCH(1, 4);
