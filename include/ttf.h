@@ -108,8 +108,10 @@ ttf_status ttf_workspace_size(const ttf_params* params, size_t* bytes);
  * Errors: INVALID_ARG (NULL params/features/workspace/out or required output, a size < 1,
  * B*F*H*W >= 2^31, r < 0, t not finite, anchor_index outside [-F,F) in FIXED mode, unknown
  * anchor_mode), UNSUPPORTED (unknown dtype; features, tokens_out or workspace misaligned),
- * WORKSPACE_TOO_SMALL, HIP.  Any C works; rows whose byte length is a multiple of 16 take the
- * vector paths.
+ * WORKSPACE_TOO_SMALL, HIP.  Any C, grid and radius work.  Fast paths: bf16 input with
+ * C % 128 == 0 and r <= 2 runs the window search on the matrix cores (any grid; grids exactly 16
+ * or 32 tokens wide with H*W % 64 == 0 are the best case); rows whose byte length is a multiple
+ * of 16 are read and copied with 16-byte accesses.
  */
 ttf_status ttf_compress(const ttf_params* params, const void* features,
                         void* workspace, size_t workspace_bytes,

@@ -17,9 +17,11 @@ hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool ex
                                      const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                      int32_t* best_idx, float* win_sim, hipStream_t s);
 
-// bf16 tokens on 16- or 32-wide grids take the matrix-core kernels; everything else (fp32 input,
-// other grids, large radii, odd channel counts) takes the general wave-per-token kernel.  Setting
-// the environment variable TTF_SEARCH=general forces the general kernels (for comparisons).
+// bf16 tokens with r <= 2 and C % 128 == 0 take the matrix-core kernels (grids exactly 16 or 32 wide
+// with whole keep words the aligned ones, every other grid the padded-tile ones; the tied-batch
+// mode only the aligned ones); fp32 input, larger radii and other channel counts take the general
+// wave-per-token kernel.  Setting the environment variable TTF_SEARCH=general forces the general
+// kernels (for comparisons).
 bool use_mfma_path(const ttf_params& p, bool tied = false)
 {
     const char* force = std::getenv("TTF_SEARCH");
