@@ -122,6 +122,8 @@ SHAPES = [
     (1, 4, 3, 64, 128, "bf16", 2),       # whole tiles only
     (2, 9, 20, 36, 128, "bf16", 1),
     (2, 1, 14, 14, 128, "bf16", 1),      # padded tile rows, no source frame
+    (2, 6, 14, 14, 4096, "bf16", 1),     # padded and wide grids at the full channel count (128 K-steps)
+    (1, 5, 10, 40, 4096, "bf16", 2),
     (1, 2, 70, 20, 1024, "bf16", 1),     # one source frame, long rows of channels (8 K-steps per pass variant not used here)
     (1, 3, 16, 16, 1024, "bf16", 1),     # fewer workgroups than CUs and C % 1024 == 0: one-frame long-pass variant
     (1, 5, 8, 32, 2048, "bf16", 2),      # the same variant on a 32-wide grid with a 5x5 window
