@@ -483,3 +483,28 @@ def test_tied_ties_go_to_the_lowest_index(H, W, C, dtype):
     assert res.anchor_index == 0 and (res.best_idx[1].reshape(H, W)[:, 2] == np.arange(H) * W + 1).all()
     buf = _run_tied(x, 1, 0.5)
     _compare_tied(x, buf, res)
+
+
+def _random_segment_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    widths = [3, 15, 16, 17, 24, 32, 33, 47, 48, 50]
+    out = []
+    for _ in range(n):
+        out.append((int(rng.integers(1, 4)), int(rng.integers(2, 11)), int(rng.integers(1, 11)), int(rng.choice(widths)),
+                    int(rng.choice([128, 256, 96])), "bf16" if rng.random() < 0.8 else "f32", int(rng.choice([0, 1, 2, 3]))))
+    return out
+
+
+@pytest.mark.parametrize("B,F,H,W,C,dtype,r", _random_segment_shapes(20, seed=20260102))
+def test_random_segments(B, F, H, W, C, dtype, r):
+    """Seeded small segments across every search path: frame 0 of a generated clip is the external
+    anchor, the rest is the segment."""
+    from oracle import streaming as S
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=B, F=F, H=H, W=W, C=C, dtype=dtype, r=r, max_offset=min(max(r, 1), 2),
+                                       sigma=0.5, region=2, seed=700 + B + 3 * F + 5 * H + 7 * W + C + r)
+    t = cfg.t[0]
+    batch = _segment_case(cfg, t)
+    anchor, seg = batch.x[:, 0], np.ascontiguousarray(batch.x[:, 1:])
+    want = S.compress_segment(seg, anchor, r, t, frame_offset=3)
+    out = _run_segment(seg, anchor, 3, r, t)
+    _compare_segment(seg, out, want)

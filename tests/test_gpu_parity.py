@@ -317,3 +317,29 @@ def test_graph_capture_and_replay():
         assert torch.equal(buf.src_index[:rows], ref.src_index[:rows])
         assert torch.equal(buf.pos_ids[:, :rows], ref.pos_ids[:, :rows])
         assert torch.equal(buf.tokens_out[:rows].view(torch.int16), ref.tokens_out[:rows].view(torch.int16))
+
+
+def _random_shapes(n, seed):
+    """Seeded draw of small problems that spreads over every search path: grid widths around the
+    tile boundaries (15..17, 31..33, 47..49), heights 1..12, radii 0..2 (3 now and then), channel
+    counts that do and do not qualify for the matrix cores, both element types."""
+    rng = np.random.default_rng(seed)
+    widths = [1, 2, 7, 15, 16, 17, 24, 31, 32, 33, 40, 47, 48, 49, 65]
+    out = []
+    for _ in range(n):
+        W = int(rng.choice(widths))
+        H = int(rng.integers(1, 13))
+        r = int(rng.choice([0, 1, 1, 2, 2, 3]))
+        C = int(rng.choice([128, 128, 256, 384, 64, 100]))
+        dtype = "bf16" if rng.random() < 0.8 else "f32"
+        B = int(rng.integers(1, 4))
+        F = int(rng.integers(1, 12))
+        out.append((B, F, H, W, C, dtype, r))
+    return out
+
+
+@pytest.mark.parametrize("B,F,H,W,C,dtype,r", _random_shapes(36, seed=20260101))
+def test_random_shapes(B, F, H, W, C, dtype, r):
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=B, F=F, H=H, W=W, C=C, dtype=dtype, r=r, max_offset=min(max(r, 1), 2),
+                                       sigma=0.5, region=2)
+    _parity(cfg, seed=500 + B + 3 * F + 5 * H + 7 * W + C + r)
