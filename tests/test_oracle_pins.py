@@ -432,3 +432,31 @@ def test_tied_margin_helper_moves_every_decision_off_the_edge(oracle):
     src[res.anchor_index] = False
     assert np.all((res.mean_sim - res.second_mean)[src] >= 1e-4)
     assert np.all(np.abs(res.best_sim[:, src] - float(np.float32(0.7))) >= 1e-3)
+
+
+def _random_small(n, seed):
+    rng = np.random.default_rng(seed)
+    return [(int(rng.integers(1, 4)), int(rng.integers(1, 7)), int(rng.integers(1, 8)), int(rng.integers(1, 10)),
+             int(rng.choice([1, 3, 8, 24])), str(rng.choice(["f32", "bf16"])), int(rng.integers(0, 5)),
+             float(rng.choice([0.2, 0.5, 0.7, 0.95]))) for _ in range(n)]
+
+
+@pytest.mark.parametrize("B,F,H,W,C,dtype,r,t", _random_small(40, seed=11))
+def test_random_small_problems_match_bruteforce(oracle, B, F, H, W, C, dtype, r, t):
+    """Seeded sweep over odd little shapes (single rows and columns, one channel, radius beyond the
+    grid, one frame): the plain pass and the tied-batch pass against their NumPy formulations."""
+    from bruteforce import ttf_tied
+    rng = np.random.default_rng(1000 * B + 100 * F + 10 * H + W + C + r)
+    x = rng.standard_normal((B, F, H, W, C)).astype(np.float32)
+    x[:, 1:] = 0.6 * x[:, 1:] + 0.8 * x[:, :1]                 # frames correlated with frame 0: both gate outcomes
+    if dtype == "bf16":
+        x = f32_to_bf16_bits(x)
+    _check_against_bruteforce(oracle, x, r, t)
+    res = oracle.compress_tied(x, r, t)
+    ref = ttf_tied(_as_f64(x).reshape(B, F, H * W, C), H, W, r, t)
+    assert res.anchor_index == ref["anchor"]
+    np.testing.assert_array_equal(res.best_idx, ref["best_idx"])
+    np.testing.assert_array_equal(res.fuse_map, ref["fuse_map"])
+    np.testing.assert_allclose(res.best_sim, ref["best_sim"], rtol=0, atol=1e-12)
+    assert res.kept_count == len(ref["src_index"])
+    np.testing.assert_array_equal(res.src_index[:res.kept_count], ref["src_index"])
