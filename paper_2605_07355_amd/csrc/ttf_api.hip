@@ -18,15 +18,15 @@ hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool ex
                                      int32_t* best_idx, float* win_sim, hipStream_t s);
 
 // bf16 tokens with r <= 2 and C % 128 == 0 take the matrix-core kernels (grids exactly 16 or 32 wide
-// with whole keep words the aligned ones, every other grid the padded-tile ones; the tied-batch
-// mode only the aligned ones); fp32 input, larger radii and other channel counts take the general
+// with whole keep words the aligned ones, every other grid the padded-tile ones); fp32 input, larger radii and other channel counts take the general
 // wave-per-token kernel.  Setting the environment variable TTF_SEARCH=general forces the general
 // kernels (for comparisons).
 bool use_mfma_path(const ttf_params& p, bool tied = false)
 {
     const char* force = std::getenv("TTF_SEARCH");
     const bool general = force && std::strcmp(force, "general") == 0;
-    return !general && (mfma_search_supported(p) || (!tied && mfma_search_padded(p)));
+    (void)tied;
+    return !general && (mfma_search_supported(p) || mfma_search_padded(p));
 }
 
 hipError_t launch_window_search(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,

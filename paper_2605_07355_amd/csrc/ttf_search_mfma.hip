@@ -127,7 +127,7 @@ __device__ __forceinline__ void finish_tile(const f32x4* v, const float* nn, int
     const int N = PAD ? H * Wg : H * W;
     const int m = lane & 15, g = lane >> 4;
     const int u = s % 2;                                     // tile within the frame
-    const int y0 = i0 / W, ylo = y0 - RAD;
+    const int y0 = i0 / W;
     float sinv[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) sinv[j] = nn[j] > 0.f ? __builtin_amdgcn_rsqf(nn[j]) : 0.f;
@@ -138,17 +138,21 @@ __device__ __forceinline__ void finish_tile(const f32x4* v, const float* nn, int
     if constexpr (ALL) {
         constexpr int K1 = 2 * RAD + 1;
         const int kk = si + (si >= a ? 1 : 0);
-        const size_t tok0 = ((size_t)b * F + kk) * N + i0 + 16 * u + 4 * g;
+        // flat index of source token (4g + 0) of this tile inside the frame
+        const size_t cell0 = PAD ? (size_t)ysrc * Wg + xsrc0 + 4 * g : (size_t)i0 + 16 * u + 4 * g;
+        const size_t tok0 = ((size_t)b * F + kk) * N + cell0;
+        const bool src_row_ok = !PAD || ysrc < H;
 #pragma unroll
         for (int q = 0; q < NPS; ++q) {
-            const int yy = CT == 1 ? ysrc - RAD + q : ylo + q / 2;
-            const int xa_col = (CT == 1 ? 0 : 16 * (q % 2)) + m;
-            const bool row_ok = (yy >= 0) & (yy < H) & (yy - ysrc >= -RAD) & (yy - ysrc <= RAD);
+            const int yy = ysrc - RAD + S::pair_row(u, q);
+            const int xa_col = 16 * (c0 + S::pair_col(u, q)) + m;
+            const bool row_ok = (yy >= 0) & (yy < H) & (!PAD || ((xa_col >= 0) & (xa_col < Wg)));
             const float ai = ai_tile[S::pair_tile(u, q)];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int dx = xa_col - (xsrc0 + 4 * g + j);
-                if (live & row_ok & (dx >= -RAD) & (dx <= RAD))
+                const int xs = xsrc0 + 4 * g + j;
+                const int dx = xa_col - xs;
+                if (live & src_row_ok & row_ok & (dx >= -RAD) & (dx <= RAD) & (!PAD || xs < Wg))
                     win_sim[(tok0 + j) * (K1 * K1) + (yy - ysrc + RAD) * K1 + dx + RAD] = v[q][j] * sinv[j] * ai;
             }
         }
@@ -710,7 +714,7 @@ __global__ __launch_bounds__(256) void k_pack_keep(const int32_t* __restrict__ f
 template <int CT, int RAD>
 hipError_t launch_padded(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,
                          const int32_t* anchor_index, int32_t* fuse_map, float* best_sim, int32_t* best_idx,
-                         hipStream_t s)
+                         float* win_sim, hipStream_t s)
 {
     using S = Shape<CT, RAD>;
     const int nsrc = external_anchor ? p.F : p.F - 1;
@@ -722,16 +726,20 @@ hipError_t launch_padded(const ttf_params& p, const void* x, bool external_ancho
         const int strips = CT == 1 ? (p.H + 1) / 2 : (CT == 2 ? p.H : p.H * (((p.W + 15) / 16 + 1) / 2));
         const size_t wgs = (size_t)p.B * groups * strips;
         const size_t lds = 2 * KSWS * (size_t)S::NA * 1024;
-        auto kernel = k_search_mfma_shared<CT, RAD, KSWS, FWS, false, true>;
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        kernel<<<(unsigned)wgs, 256, lds, s>>>(static_cast<const uint16_t*>(x), w.anchor_frag, anchor_index,
-                                               w.anchor_inv, fuse_map, best_sim, best_idx, nullptr, nullptr, p.F, p.H,
-                                               p.C, p.t, groups, p.W);
-        e = hipGetLastError();
+        auto go = [&](auto kernel) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            kernel<<<(unsigned)wgs, 256, lds, s>>>(static_cast<const uint16_t*>(x), w.anchor_frag, anchor_index,
+                                                   w.anchor_inv, fuse_map, best_sim, best_idx, nullptr, win_sim, p.F,
+                                                   p.H, p.C, p.t, groups, p.W);
+            return hipGetLastError();
+        };
+        const hipError_t e = win_sim ? go(k_search_mfma_shared<CT, RAD, KSWS, FWS, true, true>)
+                                     : go(k_search_mfma_shared<CT, RAD, KSWS, FWS, false, true>);
         if (e != hipSuccess) return e;
     }
+    if (win_sim) return hipSuccess;                          // tied-batch mode: the tie kernel forms the keep words
     k_pack_keep<<<(unsigned)((words + 3) / 4), 256, 0, s>>>(fuse_map, anchor_index, w.keep_bits, p.F, N, NW, words);
     return hipGetLastError();
 }
@@ -750,7 +758,7 @@ bool mfma_search_supported(const ttf_params& p)
 }
 
 // Same element type, radius and channel conditions, but any grid: served by the padded-tile
-// kernels (not in tied-batch mode).
+// kernels.
 bool mfma_search_padded(const ttf_params& p)
 {
     if (p.dtype != TTF_BF16 || p.r > 2 || p.C % 128 != 0) return false;
@@ -765,7 +773,7 @@ hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool ex
         const int ct = p.W <= 16 ? 1 : (p.W <= 32 ? 2 : 3);
 #define TTF_PCASE(CT, RAD)                              \
     if (ct == CT && p.r == RAD)                         \
-    return launch_padded<CT, RAD>(p, x, external_anchor, w, anchor_index, fuse_map, best_sim, best_idx, s)
+    return launch_padded<CT, RAD>(p, x, external_anchor, w, anchor_index, fuse_map, best_sim, best_idx, win_sim, s)
         TTF_PCASE(1, 0);
         TTF_PCASE(1, 1);
         TTF_PCASE(1, 2);

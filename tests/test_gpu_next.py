@@ -425,7 +425,10 @@ TIED = [
     ("tiny", dict(B=2, F=4, H=5, W=13, C=129, dtype="bf16"), 3, "auto"),
     ("tiny", dict(B=1, F=4, H=6, W=6, C=64, dtype="bf16"), 1, "auto"),      # B = 1: the plain pass
     ("qwen3vl_2b", dict(B=2, F=1, C=128), 1, "auto"),                       # no source frame
-    ("qwen3vl_2b", dict(B=3, F=4, H=14, W=14, C=128), 1, "auto"),           # 14x14: tied mode takes the general kernels
+    ("qwen3vl_2b", dict(B=3, F=4, H=14, W=14, C=128), 1, "auto"),           # 14x14: padded tile rows
+    ("qwen3vl_2b", dict(B=2, F=5, H=9, W=24, C=256), 2, "auto"),
+    ("qwen3vl_2b", dict(B=2, F=6, H=5, W=44, C=128), 1, 0),                 # wider than 32
+    ("qwen3vl_2b", dict(B=3, F=3, H=7, W=16, C=128), 0, "auto"),            # 16 wide, partial keep words
     ("highres_wide", dict(B=2, F=18, H=64, C=128), 2, "auto"),              # LDS-shared anchor kernel, all-window form
 ]
 
