@@ -74,6 +74,9 @@ bool mfma_search_padded(const ttf_params& p);      // every other grid (tile row
 hipError_t launch_window_search(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                 const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                 int32_t* best_idx, float* win_sim, hipStream_t s);
+// Keep words rebuilt from the fuse map (for searches whose work units do not line up with keep words).
+hipError_t launch_pack_keep(const ttf_params& p, const int32_t* fuse_map, const int32_t* anchor_index,
+                            const Workspace& w, hipStream_t s);
 hipError_t launch_offsets_scan(const ttf_params& p, const Workspace& w, const int32_t* anchor_index,
                                int32_t* kept_count, int32_t* row_offsets, bool tied, hipStream_t s);
 hipError_t launch_emit_rows(const ttf_params& p, const void* x, const Workspace& w,

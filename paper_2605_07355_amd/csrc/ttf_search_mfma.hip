@@ -746,6 +746,15 @@ hipError_t launch_padded(const ttf_params& p, const void* x, bool external_ancho
 
 }  // namespace
 
+hipError_t launch_pack_keep(const ttf_params& p, const int32_t* fuse_map, const int32_t* anchor_index,
+                            const Workspace& w, hipStream_t s)
+{
+    const int N = p.H * p.W, NW = (N + 63) / 64;
+    const size_t words = (size_t)p.B * p.F * NW;
+    k_pack_keep<<<(unsigned)((words + 3) / 4), 256, 0, s>>>(fuse_map, anchor_index, w.keep_bits, p.F, N, NW, words);
+    return hipGetLastError();
+}
+
 // True when the matrix-core kernels cover this problem: bf16, grid width 16 or 32, radius <= 2,
 // channel count a multiple of 128 (4 wave slices of whole 32-channel K-steps), and a token count
 // per frame that is a multiple of 64 so that 64-bit keep words are whole.

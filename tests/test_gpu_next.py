@@ -429,6 +429,7 @@ TIED = [
     ("qwen3vl_2b", dict(B=2, F=5, H=9, W=24, C=256), 2, "auto"),
     ("qwen3vl_2b", dict(B=2, F=6, H=5, W=44, C=128), 1, 0),                 # wider than 32
     ("qwen3vl_2b", dict(B=3, F=3, H=7, W=16, C=128), 0, "auto"),            # 16 wide, partial keep words
+    ("tiny", dict(B=3, F=24, H=64, W=16, C=40, dtype="f32"), 1, "auto"),    # large general input: LDS-tiled kernel
     ("highres_wide", dict(B=2, F=18, H=64, C=128), 2, "auto"),              # LDS-shared anchor kernel, all-window form
 ]
 

@@ -127,6 +127,12 @@ SHAPES = [
     (1, 2, 70, 20, 1024, "bf16", 1),     # one source frame, long rows of channels (8 K-steps per pass variant not used here)
     (1, 3, 16, 16, 1024, "bf16", 1),     # fewer workgroups than CUs and C % 1024 == 0: one-frame long-pass variant
     (1, 5, 8, 32, 2048, "bf16", 2),      # the same variant on a 32-wide grid with a 5x5 window
+    # general path at >= 2048 keep words: the LDS-tiled kernel (anchor halo staged per workgroup)
+    (4, 33, 64, 16, 40, "f32", 1),       # fp32, one partial channel chunk
+    (4, 33, 64, 16, 72, "bf16", 2),      # bf16 with C % 128 != 0, 5x5 window
+    (4, 31, 63, 17, 264, "f32", 1),      # ragged keep words, two channel chunks
+    (2, 40, 90, 20, 8, "bf16", 0),       # 1x1 window, a single 16-byte piece per row
+    (3, 12, 64, 64, 16, "f32", 1),       # halo too large for LDS at this width: direct kernel on a large input
 ]
 
 
