@@ -264,7 +264,9 @@ def main() -> int:
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "F": cfg.F, "H": cfg.H, "W": cfg.W, "C": cfg.C,
                    "r": r, "t": t, "anchor": "auto", "tokens": tokens, "input_bytes": tokens * row_bytes,
-                   "inputs": "resident in HBM before the timed region"},
+                   "inputs": "resident in HBM before the timed region"
+                             + ("; the same tensor every step and small enough for the 256 MiB Infinity Cache "
+                                "(cache-resident run: no bandwidth claim)" if tokens * row_bytes <= (192 << 20) else "")},
         "roofline": roofline, "path": path, "cpu_baseline": cpu_baseline, "extensions": extensions,
         "context": "paper reports ~67% of tokens removed at t=0.70 and ~0.16 GFLOPs matching cost on an "
                    "A100 40GB; no timing of the pass itself",
