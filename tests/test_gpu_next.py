@@ -512,3 +512,34 @@ def test_random_segments(B, F, H, W, C, dtype, r):
     want = S.compress_segment(seg, anchor, r, t, frame_offset=3)
     out = _run_segment(seg, anchor, 3, r, t)
     _compare_segment(seg, out, want)
+
+
+def test_follow_on_calls_are_reproducible_and_honour_the_stream():
+    """Every follow-on entry point enqueues on the stream it is given (here a side stream that
+    also carries the upload) and gives bit-identical results when repeated."""
+    import paper_2605_07355_amd as ttf
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=3, F=6, H=12, W=20, C=128, shared_motion=True)
+    x_np = make_clip_batch(cfg).x
+    side = torch.cuda.Stream()
+    host = torch.from_numpy(x_np.view(np.int16)).pin_memory()
+    runs = []
+    for _ in range(2):
+        with torch.cuda.stream(side):
+            x = torch.empty(host.shape, dtype=torch.int16, device="cuda")
+            x.copy_(host, non_blocking=True)                         # the calls below must wait for this copy
+            x = x.view(torch.bfloat16)
+            out = ttf.ttf_compress(x, r=1, t=0.7, stream=side)
+            rmap = ttf.ttf_restore_map(out, stream=side)
+            full = ttf.ttf_restore(out.buffers.tokens_out, cfg.tokens, rmap, cfg.H, cfg.W, stream=side)
+            thr = ttf.ttf_select_threshold(out, 0.5, stream=side)
+            snap = [t.clone() for t in (out.buffers.fuse_map, out.buffers.kept_count, rmap, full.view(torch.int16), thr)]
+            ttf.ttf_regate(x, out, thr, stream=side)
+            seg = ttf.ttf_compress_segment(x[:, 1:].contiguous(), x[:, 0].contiguous(), 1, r=1, t=0.7, stream=side)
+            tied = ttf.ttf_compress_tied(x, r=1, t=0.7, stream=side)
+            snap += [t.clone() for t in (out.buffers.fuse_map, out.buffers.row_offsets, seg.buffers.fuse_map,
+                                         seg.buffers.row_offsets, tied.fuse_map, tied.kept_count, tied.best_sim)]
+        side.synchronize()
+        runs.append(snap)
+    for first, second in zip(*runs):
+        assert torch.equal(first, second)
+    assert int(runs[0][1].sum()) > 0
