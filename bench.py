@@ -58,7 +58,7 @@ def main() -> int:
                     help="skip the timings of restoration, adaptive threshold and streaming segments")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; clips shard across GPUs with no communication, "
+        print("bench.py: this benchmark runs on one GPU only; clips shard across GPUs with no communication, "
               "but no multi-GPU path is built or measured. Use --gpus 1.", file=sys.stderr)
         return 2
     if int(os.environ.get("WORLD_SIZE", "1")) != 1:
