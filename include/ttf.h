@@ -38,7 +38,8 @@
  *   - Same inputs give bit-identical outputs on every call (no floating-point atomics, fixed
  *     reduction orders).
  *   - Input values are not scanned.  A NaN similarity compares false against "> t", so the
- *     token is kept.
+ *     token is kept.  Dot products and squared norms are accumulated in fp32: token rows whose
+ *     squared norm overflows fp32 (entries around 1e17 and beyond) give NaN similarities.
  */
 #ifndef TTF_H
 #define TTF_H
