@@ -206,6 +206,12 @@ def main() -> int:
         ms = timed(lambda: ttf.ttf_regate(x, out, thr))
         rows_rg = int(buf.kept_count.sum().item())
         extensions["regate"] = entry(ms, 12 * tokens + rows_rg * (2 * row_bytes + 16), rows=rows_rg)
+        # fixed anchor (the paper's first / last frame ablation): no pass for the anchor rule
+        ms = timed(lambda: ttf.ttf_compress(x, r=r, t=t, anchor=0, buffers=buf, stream=stream))
+        rows_fx = int(buf.kept_count.sum().item())
+        extensions["compress_fixed_anchor"] = entry(
+            ms, (1.0 + 1.0 / cfg.F) * row_bytes * tokens + rows_fx * row_bytes, anchor="first frame", rows=rows_fx,
+            GTok_per_s=round(tokens / (ms * 1e-3) / 1e9, 4))
         # one stream segment: frames 1..F-1 of every clip against frame 0 as the rolling anchor
         if cfg.F > 1:
             seg = x[:, 1:].contiguous()

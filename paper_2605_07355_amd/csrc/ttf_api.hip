@@ -21,11 +21,10 @@ hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool ex
 // with whole keep words the aligned ones, every other grid the padded-tile ones); fp32 input, larger radii and other channel counts take the general
 // wave-per-token kernel.  Setting the environment variable TTF_SEARCH=general forces the general
 // kernels (for comparisons).
-bool use_mfma_path(const ttf_params& p, bool tied = false)
+bool use_mfma_path(const ttf_params& p)
 {
     const char* force = std::getenv("TTF_SEARCH");
     const bool general = force && std::strcmp(force, "general") == 0;
-    (void)tied;
     return !general && (mfma_search_supported(p) || mfma_search_padded(p));
 }
 
@@ -33,7 +32,7 @@ hipError_t launch_window_search(const ttf_params& p, const void* x, const void* 
                                 const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                 int32_t* best_idx, float* win_sim, hipStream_t s)
 {
-    if (use_mfma_path(p, win_sim != nullptr))
+    if (use_mfma_path(p))
         return launch_window_search_mfma(p, x, ext_anchor != nullptr, w, anchor_index, fuse_map, best_sim, best_idx,
                                          win_sim, s);
     return launch_window_search_generic(p, x, ext_anchor, w, anchor_index, fuse_map, best_sim, best_idx, win_sim, s);
@@ -211,7 +210,7 @@ ttf_status ttf_compress_tied(const ttf_params* params, const void* features, voi
         TTF_STEP(launch_anchor_scores(p, w, s));
     }
     TTF_STEP(launch_tied_anchor(p, w, out->anchor_index, s));
-    if (use_mfma_path(p, true))
+    if (use_mfma_path(p))
         TTF_STEP(launch_anchor_prepare_mfma(p, features, nullptr, w, out->anchor_index, nullptr, nullptr, nullptr,
                                             true, s));
     else TTF_STEP(launch_anchor_norms(p, features, nullptr, w, out->anchor_index, true, s));
