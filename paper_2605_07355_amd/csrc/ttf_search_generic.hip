@@ -151,25 +151,35 @@ __device__ __forceinline__ float dot16(u32x4 a, u32x4 b, float acc)
     return acc;
 }
 
-// Tiled form of the same search for large inputs with r <= 1 and 16-byte row pieces.  A workgroup
-// (8 waves) owns an 8x8 patch of source tokens of one frame; the 10x10 anchor cells its windows
-// can touch are staged in LDS one 64*V-channel chunk at a time (16 bytes per lane and cell), so an
-// anchor row is fetched once per patch instead of once per source token that has it in its
-// window, whatever the grid width.  Wave w owns patch row w: it keeps the partial dot products of
-// its 8 tokens with their (up to) 9 candidates in registers across the chunks and reduces them
-// over the lanes once at the end.  The halo pieces of the next chunk are requested into
-// registers before the current chunk is computed and are written to LDS at the top of the next
-// iteration, so those loads overlap the arithmetic.  Patches do not line up with keep words;
-// the words are packed from the fuse map afterwards.
-constexpr int kPatch = 8, kHaloW = kPatch + 2, kHaloCells = kHaloW * kHaloW;
-template <typename T, int V, bool ALL>
+// Tiled form of the same search for large inputs with r <= RMAX (1 or 2) and 16-byte row pieces.
+// A workgroup (8 waves) owns a patch of 8 rows x PT columns of source tokens of one frame (PT = 8
+// for the 3x3 window, 4 for the 5x5 window, where every token needs 25 partial sums); the anchor
+// cells its windows can touch (the patch plus RMAX cells on every side) are staged in LDS one
+// 64*V-channel chunk at a time (16 bytes per lane and cell), so an anchor row is fetched once per
+// patch instead of once per source token that has it in its window, whatever the grid width.
+// Wave w owns patch row w: it keeps the partial dot products of its PT tokens with their
+// candidates in registers across the chunks and reduces them over the lanes once at the end.
+// The halo pieces of the next chunk are requested into registers before the current chunk is
+// computed and are written to LDS at the top of the next iteration, so those loads overlap the
+// arithmetic.  Patches do not line up with keep words; the words are packed from the fuse map
+// afterwards.
+template <int RMAX>
+struct Patch {
+    static constexpr int ROWS = 8;                    // one per wave
+    static constexpr int PT = RMAX == 1 ? 8 : 4;      // tokens per wave
+    static constexpr int HW = PT + 2 * RMAX, HH = ROWS + 2 * RMAX, CELLS = HW * HH;
+    static constexpr int K1 = 2 * RMAX + 1, G = K1 * K1;
+};
+template <typename T, int V, int RMAX, bool ALL>
 __global__ __launch_bounds__(512) void k_search_tiled(
     const T* __restrict__ x, const T* __restrict__ ext_anchor, const int32_t* __restrict__ anchor_index,
     const float* __restrict__ anchor_inv,
     int32_t* __restrict__ fuse_map, float* __restrict__ best_sim, int32_t* __restrict__ best_idx,
     float* __restrict__ win_sim, int F, int H, int W, int C, int r, float t, int tiles_x, int tiles)
 {
-    constexpr int HP = (kHaloCells + 7) / 8;          // halo cells a wave stages per chunk
+    using P = Patch<RMAX>;
+    constexpr int PT = P::PT, HW = P::HW, K1 = P::K1, G = P::G;
+    constexpr int HP = (P::CELLS + 7) / 8;            // halo cells a wave stages per chunk
     extern __shared__ u32x4 halo[];                   // [halo cell][lane]
     const int N = H * W;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -177,10 +187,10 @@ __global__ __launch_bounds__(512) void k_search_tiled(
     const size_t frame = blockIdx.x / tiles;
     const int b = (int)(frame / F), k = (int)(frame % F);
     const int a = anchor_index[b];
-    const int ty0 = (tile / tiles_x) * kPatch, tx0 = (tile % tiles_x) * kPatch;
+    const int ty0 = (tile / tiles_x) * P::ROWS, tx0 = (tile % tiles_x) * PT;
     const int y = ty0 + wave;                         // this wave's grid row
     if (k == a) {                                     // anchor tokens are always retained
-        if (!ALL && lane < kPatch && y < H && tx0 + lane < W) {
+        if (!ALL && lane < PT && y < H && tx0 + lane < W) {
             const int i = y * W + tx0 + lane;
             const size_t o = frame * (size_t)N + i;
             fuse_map[o] = -1;
@@ -192,22 +202,22 @@ __global__ __launch_bounds__(512) void k_search_tiled(
     const T* anchor = a < 0 ? ext_anchor + (size_t)b * N * C : x + ((size_t)b * F + a) * (size_t)N * C;
     const float* ainv = anchor_inv + (size_t)b * N;
     const T* src = x + (frame * (size_t)N + (size_t)min(y, H - 1) * W + tx0) * (size_t)C;
-    const int ntok = y < H ? min(kPatch, W - tx0) : 0; // tokens of this wave
+    const int ntok = y < H ? min(PT, W - tx0) : 0;    // tokens of this wave
 
-    // this wave's halo cells: cell j = wave + 8*h is grid cell (ty0 - 1 + j / 10, tx0 - 1 + j % 10)
+    // this wave's halo cells: cell j = wave + 8*h is grid cell (ty0 - RMAX + j / HW, tx0 - RMAX + j % HW)
     int hoff[HP];                                     // token index in the anchor frame, -1 outside the grid
 #pragma unroll
     for (int h = 0; h < HP; ++h) {
         const int j = wave + 8 * h;
-        const int hy = ty0 - 1 + j / kHaloW, hx = tx0 - 1 + j % kHaloW;
-        hoff[h] = (j < kHaloCells && hy >= 0 && hy < H && hx >= 0 && hx < W) ? hy * W + hx : -1;
+        const int hy = ty0 - RMAX + j / HW, hx = tx0 - RMAX + j % HW;
+        hoff[h] = (j < P::CELLS && hy >= 0 && hy < H && hx >= 0 && hx < W) ? hy * W + hx : -1;
     }
-    float dot[kPatch][9], nn[kPatch];
+    float dot[PT][G], nn[PT];
 #pragma unroll
-    for (int q = 0; q < kPatch; ++q) {
+    for (int q = 0; q < PT; ++q) {
         nn[q] = 0.f;
 #pragma unroll
-        for (int g = 0; g < 9; ++g) dot[q][g] = 0.f;
+        for (int g = 0; g < G; ++g) dot[q][g] = 0.f;
     }
     const int chunks = (C + 64 * V - 1) / (64 * V);
     u32x4 hreg[HP];                                   // halo pieces of the chunk in flight
@@ -220,7 +230,7 @@ __global__ __launch_bounds__(512) void k_search_tiled(
 #pragma unroll
         for (int h = 0; h < HP; ++h) {
             const int j = wave + 8 * h;
-            if (j < kHaloCells) halo[j * 64 + lane] = hreg[h];
+            if (j < P::CELLS) halo[j * 64 + lane] = hreg[h];
         }
         __syncthreads();
         {                                             // next chunk's halo pieces: consumed at the top of the next iteration
@@ -232,27 +242,28 @@ __global__ __launch_bounds__(512) void k_search_tiled(
             }
         }
         const int c = (ch * 64 + lane) * V;
-        u32x4 s[kPatch];
+        u32x4 s[PT];
 #pragma unroll
-        for (int q = 0; q < kPatch; ++q) {
+        for (int q = 0; q < PT; ++q) {
             s[q] = u32x4{0u, 0u, 0u, 0u};
             if (q < ntok && c < C) s[q] = *reinterpret_cast<const u32x4*>(src + (size_t)q * C + c);
         }
 #pragma unroll
-        for (int q = 0; q < kPatch; ++q) nn[q] = dot16<T>(s[q], s[q], nn[q]);
-        // every halo cell of the three rows around this wave's row is read once and multiplied with
-        // the (up to three) tokens that have it in their window; cells outside the grid hold zeros and
-        // pieces of absent tokens are zeros, so nothing needs a branch here -- candidates that do not
-        // exist are left out when the arg max is taken
+        for (int q = 0; q < PT; ++q) nn[q] = dot16<T>(s[q], s[q], nn[q]);
+        // every halo cell of the K1 rows around this wave's row is read once and multiplied with the
+        // (up to K1) tokens that have it in their window; cells outside the grid hold zeros and pieces
+        // of absent tokens are zeros, so nothing needs a branch here -- candidates that do not exist
+        // are left out when the arg max is taken
 #pragma unroll
-        for (int hr = 0; hr < 3; ++hr) {
+        for (int hr = 0; hr < K1; ++hr) {
 #pragma unroll
-            for (int hc = 0; hc < kHaloW; ++hc) {
-                const u32x4 cell = halo[((wave + hr) * kHaloW + hc) * 64 + lane];
+            for (int hc = 0; hc < HW; ++hc) {
+                const u32x4 cell = halo[((wave + hr) * HW + hc) * 64 + lane];
 #pragma unroll
-                for (int q = 0; q < kPatch; ++q) {
-                    const int dx = hc - 1 - q;            // column offset of this cell from token q
-                    if (dx >= -1 && dx <= 1) dot[q][hr * 3 + dx + 1] = dot16<T>(s[q], cell, dot[q][hr * 3 + dx + 1]);
+                for (int q = 0; q < PT; ++q) {
+                    const int dx = hc - RMAX - q;         // column offset of this cell from token q
+                    if (dx >= -RMAX && dx <= RMAX)
+                        dot[q][hr * K1 + dx + RMAX] = dot16<T>(s[q], cell, dot[q][hr * K1 + dx + RMAX]);
                 }
             }
         }
@@ -260,7 +271,7 @@ __global__ __launch_bounds__(512) void k_search_tiled(
     }
 
 #pragma unroll
-    for (int q = 0; q < kPatch; ++q) {
+    for (int q = 0; q < PT; ++q) {
         if (q < ntok) {
             const int xx = tx0 + q;
             const int i = y * W + xx;
@@ -270,13 +281,13 @@ __global__ __launch_bounds__(512) void k_search_tiled(
             float best = kNegInf;
             int arg = -1;
 #pragma unroll
-            for (int dy = -1; dy <= 1; ++dy) {
+            for (int dy = -RMAX; dy <= RMAX; ++dy) {
                 if (dy < -r || dy > r || y + dy < 0 || y + dy >= H) continue;
 #pragma unroll
-                for (int dx = -1; dx <= 1; ++dx) {
+                for (int dx = -RMAX; dx <= RMAX; ++dx) {
                     if (dx < -r || dx > r || xx + dx < 0 || xx + dx >= W) continue;
                     const int cand = (y + dy) * W + xx + dx;
-                    const float sim = wave_sum(dot[q][(dy + 1) * 3 + dx + 1]) * src_inv * ainv[cand];
+                    const float sim = wave_sum(dot[q][(dy + RMAX) * K1 + dx + RMAX]) * src_inv * ainv[cand];
                     if constexpr (ALL) {
                         if (lane == 0) win_sim[o * (size_t)((2 * r + 1) * (2 * r + 1)) + (dy + r) * (2 * r + 1) + dx + r] = sim;
                     } else if (sim > best) {          // ascending index, strict: first maximum
@@ -313,11 +324,12 @@ hipError_t launch_window_search_generic(const ttf_params& p, const void* x, cons
         static_cast<const T*>(x), static_cast<const T*>(ext_anchor), anchor_index, w.anchor_inv, fuse_map,      \
         best_sim, best_idx, w.keep_bits, win_sim, p.F, p.H, p.W, p.C, p.r, p.t, NW)
         if constexpr (V > 1) {
-            // large inputs, windows up to 3x3: 8x8 patches with their anchor halo staged in LDS
-            if (!small && p.r <= 1) {
-                const int tiles_x = (p.W + kPatch - 1) / kPatch, tiles = tiles_x * ((p.H + kPatch - 1) / kPatch);
-                const size_t lds = (size_t)kHaloCells * 1024;
-                auto tiled = [&](auto kernel) {
+            // large inputs, windows up to 5x5: patches of source tokens with their anchor halo staged in LDS
+            if (!small && p.r <= 2) {
+                auto tiled = [&](auto kernel, auto patch) {
+                    using P = decltype(patch);
+                    const int tiles_x = (p.W + P::PT - 1) / P::PT, tiles = tiles_x * ((p.H + P::ROWS - 1) / P::ROWS);
+                    const size_t lds = (size_t)P::CELLS * 1024;
                     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
                     if (e != hipSuccess) return e;
@@ -326,9 +338,11 @@ hipError_t launch_window_search_generic(const ttf_params& p, const void* x, cons
                         fuse_map, best_sim, best_idx, win_sim, p.F, p.H, p.W, p.C, p.r, p.t, tiles_x, tiles);
                     return hipGetLastError();
                 };
-                if (win_sim) return tiled(k_search_tiled<T, V, true>);   // the tie kernel forms the keep words
-                const hipError_t e = tiled(k_search_tiled<T, V, false>);
-                return e != hipSuccess ? e : launch_pack_keep(p, fuse_map, anchor_index, w, s);
+                hipError_t e;
+                if (p.r <= 1) e = win_sim ? tiled(k_search_tiled<T, V, 1, true>, Patch<1>{}) : tiled(k_search_tiled<T, V, 1, false>, Patch<1>{});
+                else e = win_sim ? tiled(k_search_tiled<T, V, 2, true>, Patch<2>{}) : tiled(k_search_tiled<T, V, 2, false>, Patch<2>{});
+                if (e != hipSuccess || win_sim) return e;               // tied-batch mode: the tie kernel forms the keep words
+                return launch_pack_keep(p, fuse_map, anchor_index, w, s);
             }
         }
         if (win_sim) { if (small) TTF_GEN(true, 1); else TTF_GEN(true, 4); }
