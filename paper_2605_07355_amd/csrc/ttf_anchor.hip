@@ -178,21 +178,26 @@ __device__ __forceinline__ int pick_anchor(const double* __restrict__ score_part
 }
 
 // Batch-tied anchor (tied-batch mode): the frame whose anchor score, averaged over the B clips
-// (summed in ascending b, fp64), is largest; lowest k on ties.  A fixed frame is simply
-// broadcast.  One wave; writes the shared index to every entry of anchor_index.
-__global__ __launch_bounds__(64) void k_tied_anchor(const double* __restrict__ score_part,
-                                                    const double* __restrict__ clip_part,
-                                                    int32_t* __restrict__ anchor_index, int B, int F, int S,
-                                                    int fixed_anchor)
+// (fp64), is largest; lowest k on ties.  A fixed frame is simply broadcast.  One workgroup of 16
+// waves: wave w adds the scores of clips w, w+16, ... (ascending) for 64 frames at a time, wave 0
+// adds the 16 partial sums in wave order and keeps the running arg max; the shared index is
+// written to every entry of anchor_index.
+__global__ __launch_bounds__(1024) void k_tied_anchor(const double* __restrict__ score_part,
+                                                      const double* __restrict__ clip_part,
+                                                      int32_t* __restrict__ anchor_index, int B, int F, int S,
+                                                      int fixed_anchor)
 {
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __shared__ double part[16][64];
+    __shared__ int s_arg;
     int arg = fixed_anchor;
     if (fixed_anchor < 0) {
         double best = -1.0e300;
         arg = 0x7fffffff;
-        for (int k = lane; k < F; k += 64) {
+        for (int k0 = 0; k0 < F; k0 += 64) {
+            const int k = k0 + lane;
             double acc = 0.0;
-            for (int b = 0; b < B; ++b) {
+            for (int b = wave; b < B && k < F; b += 16) {
                 double vv = 0.0, uv = 0.0, uu = 0.0;
 #pragma unroll 8
                 for (int s = 0; s < S; ++s) {
@@ -204,18 +209,31 @@ __global__ __launch_bounds__(64) void k_tied_anchor(const double* __restrict__ s
                 const double den = sqrt(uu) * sqrt(vv);
                 acc += den > 0.0 ? uv / den : 0.0;
             }
-            const double score = acc / (double)B;
-            if (score > best) { best = score; arg = k; }
-        }
+            part[wave][lane] = acc;
+            __syncthreads();
+            if (wave == 0 && k < F) {
+                double sum = part[0][lane];
 #pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) {
-            const double ob = __shfl_xor(best, m, 64);
-            const int oa = __shfl_xor(arg, m, 64);
-            if (ob > best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+                for (int w = 1; w < 16; ++w) sum += part[w][lane];
+                const double score = sum / (double)B;
+                if (score > best) { best = score; arg = k; }   // ascending k per lane: strict > keeps the lowest
+            }
+            __syncthreads();
         }
-        if (arg == 0x7fffffff) arg = 0;
+        if (wave == 0) {
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) {
+                const double ob = __shfl_xor(best, m, 64);
+                const int oa = __shfl_xor(arg, m, 64);
+                if (ob > best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+            }
+            if (arg == 0x7fffffff) arg = 0;
+            if (lane == 0) s_arg = arg;
+        }
+        __syncthreads();
+        arg = s_arg;
     }
-    for (int b = lane; b < B; b += 64) anchor_index[b] = arg;
+    for (int b = threadIdx.x; b < B; b += 1024) anchor_index[b] = arg;
 }
 
 // Picks the anchor of clip b (arg max of frame_score, lowest k on ties, or the fixed frame),
@@ -381,8 +399,8 @@ static int fixed_frame(const ttf_params& p)
 
 hipError_t launch_tied_anchor(const ttf_params& p, const Workspace& w, int32_t* anchor_index, hipStream_t s)
 {
-    k_tied_anchor<<<1, 64, 0, s>>>(w.score_part, w.clip_part, anchor_index, p.B, p.F, (p.C + 255) / 256,
-                                   fixed_frame(p));
+    k_tied_anchor<<<1, 1024, 0, s>>>(w.score_part, w.clip_part, anchor_index, p.B, p.F, (p.C + 255) / 256,
+                                     fixed_frame(p));
     return hipGetLastError();
 }
 
