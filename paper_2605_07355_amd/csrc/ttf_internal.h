@@ -87,7 +87,7 @@ hipError_t launch_emit_rows(const ttf_params& p, const void* x, const Workspace&
 // element, and the two row offsets of the shared mask.
 struct TiedWorkspace {
     Workspace base;
-    float*    win_sim;       // [B,F,N,(2r+1)^2]
+    float*    win_sim;       // [B,F,(2r+1)^2,N]
     int32_t*  row_offsets;   // [2]
     size_t    bytes;
 };

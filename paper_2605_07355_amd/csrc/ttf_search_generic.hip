@@ -22,7 +22,7 @@ constexpr int G = 9;                 // candidates per pass over the channels (a
 constexpr float kNegInf = -__builtin_inff();
 
 // ALL = false: arg max and gate per token.  ALL = true (tied-batch mode): every window similarity
-// is written to win_sim[token][(dy+r)*(2r+1) + (dx+r)] instead and nothing else is produced.
+// is written to win_sim[b][k][(dy+r)*(2r+1) + (dx+r)][i] instead and nothing else is produced.
 template <typename T, int V, bool ALL, int TPW>
 __global__ __launch_bounds__(1024) void k_search_generic(
     const T* __restrict__ x, const T* __restrict__ ext_anchor, const int32_t* __restrict__ anchor_index,
@@ -104,7 +104,7 @@ __global__ __launch_bounds__(1024) void k_search_generic(
                     const float sim = d * src_inv * ainv[cand[g]];
                     if constexpr (ALL) {
                         const int slot = (cand[g] / W - y + r) * (2 * r + 1) + (cand[g] % W - xx + r);
-                        if (lane == 0) win_sim[o * (size_t)((2 * r + 1) * (2 * r + 1)) + slot] = sim;
+                        if (lane == 0) win_sim[(frame * (size_t)((2 * r + 1) * (2 * r + 1)) + slot) * N + i] = sim;
                     } else if (sim > best) {                         // ascending index, strict: first maximum
                         best = sim;
                         arg = cand[g];
@@ -289,7 +289,8 @@ __global__ __launch_bounds__(512) void k_search_tiled(
                     const int cand = (y + dy) * W + xx + dx;
                     const float sim = wave_sum(dot[q][(dy + RMAX) * K1 + dx + RMAX]) * src_inv * ainv[cand];
                     if constexpr (ALL) {
-                        if (lane == 0) win_sim[o * (size_t)((2 * r + 1) * (2 * r + 1)) + (dy + r) * (2 * r + 1) + dx + r] = sim;
+                        if (lane == 0)
+                            win_sim[(frame * (size_t)((2 * r + 1) * (2 * r + 1)) + (dy + r) * (2 * r + 1) + dx + r) * N + i] = sim;
                     } else if (sim > best) {          // ascending index, strict: first maximum
                         best = sim;
                         arg = cand;

@@ -109,7 +109,7 @@ __device__ __forceinline__ bf16x8 load_frag(const uint16_t* p)
 // index on ties), applies the threshold and writes s^, dst, the fuse map and the tile's 16 keep
 // bits.  Straight-line code: no divergent branches.
 // ALL (tied-batch mode): instead of the arg max, every in-window cosine is stored to
-// win_sim[token][(dy+RAD)*(2*RAD+1) + (dx+RAD)] and nothing else is written.
+// win_sim[b][k][(dy+RAD)*(2*RAD+1) + (dx+RAD)][i] and nothing else is written.
 // PAD: the grid is Wg <= W tokens wide (columns Wg..W-1 of every tile row are padding): flat
 // indices use Wg, padding columns never win nor get written, H may be odd, and the keep bits are
 // packed afterwards by k_pack_keep (tiles are no longer aligned to 16-bit pieces of keep words).
@@ -140,7 +140,7 @@ __device__ __forceinline__ void finish_tile(const f32x4* v, const float* nn, int
         const int kk = si + (si >= a ? 1 : 0);
         // flat index of source token (4g + 0) of this tile inside the frame
         const size_t cell0 = PAD ? (size_t)ysrc * Wg + xsrc0 + 4 * g : (size_t)i0 + 16 * u + 4 * g;
-        const size_t tok0 = ((size_t)b * F + kk) * N + cell0;
+        const size_t tok0 = ((size_t)b * F + kk) * (K1 * K1) * N + cell0;   // slot 0 of token 4g+0
         const bool src_row_ok = !PAD || ysrc < H;
 #pragma unroll
         for (int q = 0; q < NPS; ++q) {
@@ -153,7 +153,7 @@ __device__ __forceinline__ void finish_tile(const f32x4* v, const float* nn, int
                 const int xs = xsrc0 + 4 * g + j;
                 const int dx = xa_col - xs;
                 if (live & src_row_ok & row_ok & (dx >= -RAD) & (dx <= RAD) & (!PAD || xs < Wg))
-                    win_sim[(tok0 + j) * (K1 * K1) + (yy - ysrc + RAD) * K1 + dx + RAD] = v[q][j] * sinv[j] * ai;
+                    win_sim[tok0 + (size_t)((yy - ysrc + RAD) * K1 + dx + RAD) * N + j] = v[q][j] * sinv[j] * ai;
             }
         }
         return;
