@@ -349,3 +349,44 @@ def test_random_shapes(B, F, H, W, C, dtype, r):
     cfg = CONFIGS["qwen3vl_2b"].scaled(B=B, F=F, H=H, W=W, C=C, dtype=dtype, r=r, max_offset=min(max(r, 1), 2),
                                        sigma=0.5, region=2)
     _parity(cfg, seed=500 + B + 3 * F + 5 * H + 7 * W + C + r)
+
+
+# ----------------------------------------------------------------- inputs beyond 4 GiB
+@pytest.mark.parametrize("name,kw,reps", [
+    ("qwen3vl_8b_batched", dict(B=4), 20),                        # bf16, matrix-core path: 5 GiB in, B = 80
+    ("qwen3vl_8b_batched", dict(B=4, C=1000, dtype="f32"), 36),   # fp32, general path: 4.4 GiB in, B = 144
+])
+def test_inputs_beyond_4gib(name, kw, reps):
+    """Byte offsets past 2^32 in the input, the output and the workspace.  Clips are independent,
+    so a batch made of `reps` copies of a small batch that agrees with the oracle must reproduce
+    that small batch's outputs, clip for clip and bit for bit, at the shifted row offsets."""
+    import paper_2605_07355_amd as ttf
+    cfg = CONFIGS[name].scaled(**kw)
+    batch, res, small = _parity(cfg)
+    sb = small.buffers
+    total = int(res.total_rows)
+    x = to_device(batch.x)
+    big_x = x.repeat(reps, 1, 1, 1, 1).contiguous()
+    assert big_x.numel() * big_x.element_size() > (1 << 32)
+    del x
+    out = ttf.ttf_compress(big_x, r=cfg.r, t=cfg.t[0])
+    torch.cuda.synchronize()
+    bb = out.buffers
+    B = cfg.B
+    for got, want in ((bb.anchor_index, sb.anchor_index), (bb.kept_count, sb.kept_count),
+                      (bb.fuse_map, sb.fuse_map), (bb.best_idx, sb.best_idx)):
+        assert torch.equal(got.view(reps, *want.shape), want.unsqueeze(0).expand(reps, *want.shape))
+    assert torch.equal(bb.best_sim.view(reps, *sb.best_sim.shape).view(torch.int32),
+                       sb.best_sim.view(torch.int32).unsqueeze(0).expand(reps, *sb.best_sim.shape))
+    offs = bb.row_offsets.cpu().numpy().astype(np.int64)
+    want_offs = (np.arange(reps)[:, None] * total + res.row_offsets[None, :B]).reshape(-1)
+    np.testing.assert_array_equal(offs[:-1], want_offs)
+    assert offs[-1] == reps * total
+    assert torch.equal(bb.src_index[:reps * total].view(reps, total), sb.src_index[:total].expand(reps, total))
+    assert torch.equal(bb.pos_ids[:, :reps * total].view(3, reps, total),
+                       sb.pos_ids[:, :total].unsqueeze(1).expand(3, reps, total))
+    rows_small = sb.tokens_out.view(-1, cfg.C)[:total]
+    rows_big = bb.tokens_out.view(-1, cfg.C)[:reps * total].view(reps, total, cfg.C)
+    bits = torch.int16 if rows_small.dtype == torch.bfloat16 else torch.int32
+    for rep in range(reps):
+        assert torch.equal(rows_big[rep].view(bits), rows_small.view(bits)), f"copy {rep}"
