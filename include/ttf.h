@@ -63,7 +63,8 @@ typedef enum { TTF_BF16 = 0, TTF_F32 = 1 } ttf_dtype;
 
 typedef enum { TTF_ANCHOR_AUTO = 0, TTF_ANCHOR_FIXED = 1 } ttf_anchor_mode;
 
-/* Problem description.  B*F*H*W must be < 2^31. */
+/* Problem description.  B*F*H*W must be < 2^31, and so must B*F*ceil(H*W/64)*64 (the token count with
+ * every frame rounded up to whole 64-token groups). */
 typedef struct {
     int32_t B, F, H, W, C;    /* clips, frames, token-grid height and width, channels; all >= 1 */
     int32_t dtype;            /* ttf_dtype of `features` and `tokens_out`                        */

@@ -59,6 +59,8 @@ ttf_status check_params(const ttf_params* p)
     const long long tokens = (long long)p->B * p->F * p->H * p->W;
     if ((long long)p->H * p->W >= (1ll << 31) || tokens >= (1ll << 31)) return TTF_ERR_INVALID_ARG;
     if (p->C > (1 << 21)) return TTF_ERR_INVALID_ARG;       // keeps every launch grid inside HIP limits
+    // one block per bit of the 64-token keep words (row emission)
+    if ((long long)p->B * p->F * (((long long)p->H * p->W + 63) / 64) * 64 >= (1ll << 31)) return TTF_ERR_INVALID_ARG;
     if (p->r < 0) return TTF_ERR_INVALID_ARG;
     if (!std::isfinite(p->t)) return TTF_ERR_INVALID_ARG;
     if (p->anchor_mode != TTF_ANCHOR_AUTO && p->anchor_mode != TTF_ANCHOR_FIXED) return TTF_ERR_INVALID_ARG;

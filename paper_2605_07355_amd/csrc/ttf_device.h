@@ -58,11 +58,13 @@ struct RowVec {
 
 // Bit-exact copy of one token row by one wavefront.  U = bytes moved per lane per step: 16 (row
 // bytes % 16 == 0, both addresses 16-byte aligned), 4 or 2.
-template <int U>
+template <int U, bool STREAM = true>
 __device__ __forceinline__ void copy_row(const char* __restrict__ src, char* __restrict__ dst,
                                          size_t row_bytes, int lane)
 {
     if constexpr (U == 16) {
+        // STREAM: the source row is read once (no reason to keep it in cache); otherwise plain loads
+        auto ld = [](const uint4* p) { return STREAM ? load16_stream(p) : *p; };
         const uint4* s = reinterpret_cast<const uint4*>(src);
         uint4* d = reinterpret_cast<uint4*>(dst);
         const int n = (int)(row_bytes / 16);
@@ -70,17 +72,17 @@ __device__ __forceinline__ void copy_row(const char* __restrict__ src, char* __r
         for (; q + 448 < n; q += 512) {                // eight 16-byte pieces in flight per lane
             uint4 v[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = load16_stream(s + q + 64 * u);
+            for (int u = 0; u < 8; ++u) v[u] = ld(s + q + 64 * u);
 #pragma unroll
             for (int u = 0; u < 8; ++u) store16_stream(d + q + 64 * u, v[u]);
         }
         for (; q + 192 < n; q += 256) {
-            const uint4 v0 = load16_stream(s + q), v1 = load16_stream(s + q + 64),
-                        v2 = load16_stream(s + q + 128), v3 = load16_stream(s + q + 192);
+            const uint4 v0 = ld(s + q), v1 = ld(s + q + 64),
+                        v2 = ld(s + q + 128), v3 = ld(s + q + 192);
             store16_stream(d + q, v0); store16_stream(d + q + 64, v1);
             store16_stream(d + q + 128, v2); store16_stream(d + q + 192, v3);
         }
-        for (; q < n; q += 64) store16_stream(d + q, load16_stream(s + q));
+        for (; q < n; q += 64) store16_stream(d + q, ld(s + q));
     } else if constexpr (U == 4) {
         const uint32_t* s = reinterpret_cast<const uint32_t*>(src);
         uint32_t* d = reinterpret_cast<uint32_t*>(dst);

@@ -116,6 +116,55 @@ __global__ __launch_bounds__(256) void k_emit_rows(const char* __restrict__ x,
     }
 }
 
+// Long rows (at least 4 KiB): one block per token; the block of a kept token copies the row
+// together, two 16-byte pieces per thread in flight, and the blocks of fused tokens leave at once.
+// Many small blocks with little work per thread is the shape in which a plain device copy runs
+// fastest on this chip (measured on 1 GiB: one or two pieces per thread 6.4-6.5 TB/s, eight pieces
+// per lane in a loop 5.8; against the wave-per-row kernel above on 8 KiB rows: 0.138 -> 0.123 ms at
+// 35 % kept rows, 0.345 -> 0.303 ms at 90 %; 2, 4, 8 or 16 tokens per block, 128 or 512 threads and
+// rows split over two blocks were all slower).  Meaning of tied_rows as in k_emit_rows.
+__global__ __launch_bounds__(256) void k_emit_row_blocks(const char* __restrict__ x,
+                                                         const uint64_t* __restrict__ keep_bits,
+                                                         const int32_t* __restrict__ frame_base,
+                                                         char* __restrict__ tokens_out,
+                                                         int32_t* __restrict__ pos_ids,
+                                                         int32_t* __restrict__ src_index,
+                                                         int F, int N, int W, int NW, size_t row_bytes, size_t cap,
+                                                         int frame_offset, size_t tied_rows)
+{
+    const int bit = blockIdx.x & 63;
+    const int word = (blockIdx.x >> 6) % NW;
+    const size_t frame = (blockIdx.x >> 6) / NW;
+    const int k = (int)(frame % F);
+    const size_t meta = tied_rows ? (size_t)k : frame;
+    const uint64_t* kb = keep_bits + meta * (size_t)NW;
+    const uint64_t wbits = kb[word];
+    if (((wbits >> bit) & 1ull) == 0) return;
+    int before = frame_base[meta];
+    for (int q = 0; q < word; ++q) before += __popcll(kb[q]);
+    before += __popcll(wbits & ((1ull << bit) - 1ull));
+    const int i = word * 64 + bit;
+    const size_t row = (size_t)before;
+    const size_t row0 = tied_rows ? (frame / F) * tied_rows : 0;
+    const uint4* s = reinterpret_cast<const uint4*>(x + (frame * (size_t)N + i) * row_bytes);
+    uint4* d = reinterpret_cast<uint4*>(tokens_out + (row0 + row) * row_bytes);
+    const int n = (int)(row_bytes / 16);
+    const int step = (int)blockDim.x;                         // 64..256 threads
+    int q = threadIdx.x;
+    for (; q + step < n; q += 2 * step) {
+        const uint4 v0 = load16_stream(s + q), v1 = load16_stream(s + q + step);
+        store16_stream(d + q, v0);
+        store16_stream(d + q + step, v1);
+    }
+    if (q < n) store16_stream(d + q, load16_stream(s + q));
+    if (threadIdx.x == 0 && (!tied_rows || frame < (size_t)F)) {
+        pos_ids[row] = k + frame_offset;
+        pos_ids[cap + row] = i / W;
+        pos_ids[2 * cap + row] = i % W;
+        src_index[row] = k * N + i;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_offsets_scan(const ttf_params& p, const Workspace& w, const int32_t* anchor_index,
@@ -140,7 +189,15 @@ hipError_t launch_emit_rows(const ttf_params& p, const void* x, const Workspace&
     const unsigned grid = (unsigned)((size_t)p.B * p.F * NW * 4);
     const char* xs = static_cast<const char*>(x);
     char* out = static_cast<char*>(tokens_out);
-    if (row_bytes % 16 == 0)
+    // rows of 6 KiB and more: one block per token (below that the launch of the blocks of fused tokens
+    // costs more than the denser copy gains; measured cross-over between 5 and 6 KiB at 35 % kept rows)
+    constexpr size_t kRowBlockMin = 6144;
+    const unsigned threads = (unsigned)(row_bytes / 16 >= 256 ? 256 : (row_bytes / 16 + 63) / 64 * 64);
+    if (row_bytes % 16 == 0 && row_bytes >= kRowBlockMin)
+        k_emit_row_blocks<<<(unsigned)((size_t)p.B * p.F * NW * 64), threads, 0, s>>>(
+            xs, w.keep_bits, w.frame_base, out, pos_ids, src_index, p.F, N, p.W, NW, row_bytes, cap, frame_offset,
+            tied_rows);
+    else if (row_bytes % 16 == 0)
         k_emit_rows<16><<<grid, 256, 0, s>>>(xs, w.keep_bits, w.frame_base, out, pos_ids, src_index,
                                              p.F, N, p.W, NW, row_bytes, cap, frame_offset, tied_rows);
     else if (row_bytes % 4 == 0)

@@ -46,10 +46,36 @@ __global__ __launch_bounds__(256) void k_restore_rows(const char* __restrict__ t
     const long long row = restore_map[tok];
     char* dst = restored + tok * row_bytes;
     if (row >= 0 && row < rows) {
-        copy_row<U>(tokens + (size_t)row * row_bytes, dst, row_bytes, lane);
+        copy_row<U, false>(tokens + (size_t)row * row_bytes, dst, row_bytes, lane);   // rows are read many times
     } else {
         for (size_t q = lane * (size_t)U; q < row_bytes; q += 64 * (size_t)U)
             for (int e = 0; e < U; ++e) dst[q + e] = 0;
+    }
+}
+
+// Long rows: one block per original token, the whole block copies the row (the copy shape that runs
+// fastest on this chip; see k_emit_row_blocks).
+__global__ __launch_bounds__(256) void k_restore_row_blocks(const char* __restrict__ tokens,
+                                                            const int32_t* __restrict__ restore_map,
+                                                            char* __restrict__ restored, size_t row_bytes,
+                                                            long long rows)
+{
+    const size_t tok = blockIdx.x;
+    const long long row = restore_map[tok];
+    uint4* d = reinterpret_cast<uint4*>(restored + tok * row_bytes);
+    const int n = (int)(row_bytes / 16);
+    const int step = (int)blockDim.x;
+    int q = threadIdx.x;
+    if (row >= 0 && row < rows) {
+        const uint4* s = reinterpret_cast<const uint4*>(tokens + (size_t)row * row_bytes);
+        for (; q + step < n; q += 2 * step) {
+            const uint4 v0 = s[q], v1 = s[q + step];          // cached loads: anchor rows are read many times
+            store16_stream(d + q, v0);
+            store16_stream(d + q + step, v1);
+        }
+        if (q < n) store16_stream(d + q, s[q]);
+    } else {
+        for (; q < n; q += step) store16_stream(d + q, uint4{0u, 0u, 0u, 0u});
     }
 }
 
@@ -73,7 +99,11 @@ hipError_t launch_restore_rows(const ttf_params& p, const void* tokens, long lon
     const unsigned grid = (unsigned)((total + 3) / 4);
     const char* in = static_cast<const char*>(tokens);
     char* out = static_cast<char*>(restored);
-    if (row_bytes % 16 == 0)
+    constexpr size_t kRowBlockMin = 2048;
+    if (row_bytes % 16 == 0 && row_bytes >= kRowBlockMin)
+        k_restore_row_blocks<<<(unsigned)total, (unsigned)(row_bytes >= 4096 ? 256 : 128), 0, s>>>(in, restore_map, out,
+                                                                                                 row_bytes, rows);
+    else if (row_bytes % 16 == 0)
         k_restore_rows<16><<<grid, 256, 0, s>>>(in, restore_map, out, total, row_bytes, rows);
     else if (row_bytes % 4 == 0)
         k_restore_rows<4><<<grid, 256, 0, s>>>(in, restore_map, out, total, row_bytes, rows);

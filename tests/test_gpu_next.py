@@ -35,6 +35,8 @@ SMALL = [
     ("qwen3vl_2b", dict(B=2, F=6)),                                    # matrix-core search path, 16x16 grid
     ("tiny", dict(B=3, F=5, H=7, W=9, C=40, dtype="f32")),             # ragged keep words, scalar rows
     ("tiny", dict(B=2, F=4, H=5, W=13, C=129, dtype="bf16")),          # odd row length (2-byte copies)
+    ("tiny", dict(B=2, F=4, H=5, W=7, C=1540, dtype="f32")),           # long rows: one block per token, 385 pieces
+    ("qwen3vl_2b", dict(B=1, F=4, H=6, W=16, C=1024)),                 # 2 KiB rows: 128-thread blocks in restoration
 ]
 
 
@@ -282,6 +284,7 @@ SEGMENTS = [
     ("qwen3vl_2b", dict(B=2, F=7, H=14, W=14, C=128), 1),              # padded tile rows, external anchor
     ("qwen3vl_2b", dict(B=1, F=4, H=9, W=24, C=256), 2),
     ("qwen3vl_2b", dict(B=1, F=6, H=7, W=44, C=128), 1),               # wider than 32
+    ("tiny", dict(B=2, F=4, H=5, W=7, C=1540, dtype="f32"), 1),        # long rows: one block per token
 ]
 
 
@@ -431,6 +434,7 @@ TIED = [
     ("qwen3vl_2b", dict(B=3, F=3, H=7, W=16, C=128), 0, "auto"),            # 16 wide, partial keep words
     ("tiny", dict(B=3, F=24, H=64, W=16, C=40, dtype="f32"), 1, "auto"),    # large general input: LDS-tiled kernel
     ("highres_wide", dict(B=2, F=18, H=64, C=128), 2, "auto"),              # LDS-shared anchor kernel, all-window form
+    ("tiny", dict(B=3, F=4, H=5, W=7, C=1540, dtype="f32"), 1, "auto"),     # long rows: one block per token
 ]
 
 
