@@ -139,7 +139,7 @@ static ttf_status run_pass(const ttf_params* params, const void* features, const
     mark();
     TTF_STEP(launch_offsets_scan(p, w, out->anchor_index, out->kept_count, out->row_offsets, false, s));
     mark();
-    TTF_STEP(launch_emit_rows(p, features, w, out->anchor_index, out->tokens_out, out->pos_ids,
+    TTF_STEP(launch_emit_rows(p, features, w, out->row_offsets + p.B, out->tokens_out, out->pos_ids,
                               out->src_index, frame_offset, false, s));
     mark();                                                    // end of stage 5
     if (out->host_counts) {
@@ -221,7 +221,7 @@ ttf_status ttf_compress_tied(const ttf_params* params, const void* features, voi
     TTF_STEP(launch_tie(p, w, tw.win_sim, out->anchor_index, out->fuse_map, out->best_sim, out->best_idx,
                         out->mean_sim, s));
     TTF_STEP(launch_offsets_scan(p, w, out->anchor_index, out->kept_count, tw.row_offsets, true, s));
-    TTF_STEP(launch_emit_rows(p, features, w, out->anchor_index, out->tokens_out, out->pos_ids, out->src_index, 0,
+    TTF_STEP(launch_emit_rows(p, features, w, tw.row_offsets + 1, out->tokens_out, out->pos_ids, out->src_index, 0,
                               true, s));
     if (out->host_counts)
         TTF_STEP(hipMemcpyAsync(out->host_counts, out->kept_count, sizeof(int32_t), hipMemcpyDeviceToHost, s));
@@ -315,7 +315,7 @@ ttf_status ttf_regate(const ttf_params* params, const void* features, const floa
     if (e == hipSuccess)
         e = launch_offsets_scan(p, w, out->anchor_index, out->kept_count, out->row_offsets, false, s);
     if (e == hipSuccess)
-        e = launch_emit_rows(p, features, w, out->anchor_index, out->tokens_out, out->pos_ids, out->src_index, 0,
+        e = launch_emit_rows(p, features, w, out->row_offsets + p.B, out->tokens_out, out->pos_ids, out->src_index, 0,
                              false, s);
     if (e == hipSuccess && out->host_counts) {
         e = hipMemcpyAsync(out->host_counts, out->kept_count, sizeof(int32_t) * p.B, hipMemcpyDeviceToHost, s);

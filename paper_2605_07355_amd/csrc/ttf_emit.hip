@@ -116,52 +116,63 @@ __global__ __launch_bounds__(256) void k_emit_rows(const char* __restrict__ x,
     }
 }
 
-// Long rows (at least 4 KiB): one block per token; the block of a kept token copies the row
-// together, two 16-byte pieces per thread in flight, and the blocks of fused tokens leave at once.
-// Many small blocks with little work per thread is the shape in which a plain device copy runs
-// fastest on this chip (measured on 1 GiB: one or two pieces per thread 6.4-6.5 TB/s, eight pieces
-// per lane in a loop 5.8; against the wave-per-row kernel above on 8 KiB rows: 0.138 -> 0.123 ms at
-// 35 % kept rows, 0.345 -> 0.303 ms at 90 %; 2, 4, 8 or 16 tokens per block, 128 or 512 threads and
-// rows split over two blocks were all slower).  Meaning of tied_rows as in k_emit_rows.
-__global__ __launch_bounds__(256) void k_emit_row_blocks(const char* __restrict__ x,
-                                                         const uint64_t* __restrict__ keep_bits,
-                                                         const int32_t* __restrict__ frame_base,
-                                                         char* __restrict__ tokens_out,
-                                                         int32_t* __restrict__ pos_ids,
-                                                         int32_t* __restrict__ src_index,
-                                                         int F, int N, int W, int NW, size_t row_bytes, size_t cap,
-                                                         int frame_offset, size_t tied_rows)
+// Rows of 1 KiB and more are emitted in two steps, so that the copy runs in the shape a plain device
+// copy is fastest in on this chip -- many small blocks, a whole block on one row, one or two 16-byte
+// pieces per thread (measured on 1 GiB: 6.4-6.5 TB/s against 5.8 for eight pieces per lane in a
+// loop) -- without launching blocks for fused tokens (a block per input token costs 0.17 ms of
+// launches alone on 262 144 tokens of which 17 % are kept).
+//
+// Step 1, one wave per keep word: the ids of every kept token and, in src_row[r], the input token
+// that output row r copies.  tied_rows > 0: the mask is the shared one ([F,NW]); ids and src_row
+// are those of one clip.
+__global__ __launch_bounds__(256) void k_emit_ids(const uint64_t* __restrict__ keep_bits,
+                                                  const int32_t* __restrict__ frame_base,
+                                                  int32_t* __restrict__ pos_ids, int32_t* __restrict__ src_index,
+                                                  int32_t* __restrict__ src_row, int F, int N, int W, int NW,
+                                                  size_t words, size_t cap, int frame_offset)
 {
-    const int bit = blockIdx.x & 63;
-    const int word = (blockIdx.x >> 6) % NW;
-    const size_t frame = (blockIdx.x >> 6) / NW;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t wd = (size_t)blockIdx.x * 4 + wave;
+    if (wd >= words) return;
+    const int word = (int)(wd % NW);
+    const size_t frame = wd / NW;
     const int k = (int)(frame % F);
-    const size_t meta = tied_rows ? (size_t)k : frame;
-    const uint64_t* kb = keep_bits + meta * (size_t)NW;
+    const uint64_t* kb = keep_bits + frame * (size_t)NW;
     const uint64_t wbits = kb[word];
-    if (((wbits >> bit) & 1ull) == 0) return;
-    int before = frame_base[meta];
+    if (((wbits >> lane) & 1ull) == 0) return;
+    int before = frame_base[frame];
     for (int q = 0; q < word; ++q) before += __popcll(kb[q]);
-    before += __popcll(wbits & ((1ull << bit) - 1ull));
-    const int i = word * 64 + bit;
-    const size_t row = (size_t)before;
-    const size_t row0 = tied_rows ? (frame / F) * tied_rows : 0;
-    const uint4* s = reinterpret_cast<const uint4*>(x + (frame * (size_t)N + i) * row_bytes);
-    uint4* d = reinterpret_cast<uint4*>(tokens_out + (row0 + row) * row_bytes);
+    const size_t row = (size_t)before + __popcll(wbits & ((1ull << lane) - 1ull));
+    const int i = word * 64 + lane;
+    pos_ids[row] = k + frame_offset;
+    pos_ids[cap + row] = i / W;
+    pos_ids[2 * cap + row] = i % W;
+    src_index[row] = k * N + i;
+    src_row[row] = (int32_t)(frame * (size_t)N + i);
+}
+
+// Step 2: block j copies output rows j, j + gridDim.x, ... below *total_rows.  blockIdx.y = clip in
+// tied-batch mode (input tokens src_clip_stride apart, output rows dst_clip_stride apart), 0 otherwise.
+__global__ __launch_bounds__(256) void k_copy_rows(const char* __restrict__ x, const int32_t* __restrict__ src_row,
+                                                   const int32_t* __restrict__ total_rows,
+                                                   char* __restrict__ tokens_out, size_t row_bytes,
+                                                   size_t src_clip_stride, size_t dst_clip_stride)
+{
+    const int total = *total_rows;
     const int n = (int)(row_bytes / 16);
-    const int step = (int)blockDim.x;                         // 64..256 threads
-    int q = threadIdx.x;
-    for (; q + step < n; q += 2 * step) {
-        const uint4 v0 = load16_stream(s + q), v1 = load16_stream(s + q + step);
-        store16_stream(d + q, v0);
-        store16_stream(d + q + step, v1);
-    }
-    if (q < n) store16_stream(d + q, load16_stream(s + q));
-    if (threadIdx.x == 0 && (!tied_rows || frame < (size_t)F)) {
-        pos_ids[row] = k + frame_offset;
-        pos_ids[cap + row] = i / W;
-        pos_ids[2 * cap + row] = i % W;
-        src_index[row] = k * N + i;
+    const int step = (int)blockDim.x;
+    const char* xs = x + blockIdx.y * src_clip_stride * row_bytes;
+    char* out = tokens_out + blockIdx.y * dst_clip_stride * row_bytes;
+    for (int r = blockIdx.x; r < total; r += gridDim.x) {
+        const uint4* s = reinterpret_cast<const uint4*>(xs + (size_t)src_row[r] * row_bytes);
+        uint4* d = reinterpret_cast<uint4*>(out + (size_t)r * row_bytes);
+        int q = threadIdx.x;
+        for (; q + step < n; q += 2 * step) {
+            const uint4 v0 = load16_stream(s + q), v1 = load16_stream(s + q + step);
+            store16_stream(d + q, v0);
+            store16_stream(d + q + step, v1);
+        }
+        if (q < n) store16_stream(d + q, load16_stream(s + q));
     }
 }
 
@@ -178,10 +189,9 @@ hipError_t launch_offsets_scan(const ttf_params& p, const Workspace& w, const in
 }
 
 hipError_t launch_emit_rows(const ttf_params& p, const void* x, const Workspace& w,
-                            const int32_t* anchor_index, void* tokens_out, int32_t* pos_ids,
+                            const int32_t* total_rows, void* tokens_out, int32_t* pos_ids,
                             int32_t* src_index, int frame_offset, bool tied, hipStream_t s)
 {
-    (void)anchor_index;
     const int N = p.H * p.W, NW = (N + 63) / 64;
     const size_t row_bytes = (size_t)p.C * (p.dtype == TTF_BF16 ? 2 : 4);
     const size_t tied_rows = tied ? (size_t)p.F * N : 0;
@@ -189,15 +199,22 @@ hipError_t launch_emit_rows(const ttf_params& p, const void* x, const Workspace&
     const unsigned grid = (unsigned)((size_t)p.B * p.F * NW * 4);
     const char* xs = static_cast<const char*>(x);
     char* out = static_cast<char*>(tokens_out);
-    // rows of 6 KiB and more: one block per token (below that the launch of the blocks of fused tokens
-    // costs more than the denser copy gains; measured cross-over between 5 and 6 KiB at 35 % kept rows)
-    constexpr size_t kRowBlockMin = 6144;
-    const unsigned threads = (unsigned)(row_bytes / 16 >= 256 ? 256 : (row_bytes / 16 + 63) / 64 * 64);
-    if (row_bytes % 16 == 0 && row_bytes >= kRowBlockMin)
-        k_emit_row_blocks<<<(unsigned)((size_t)p.B * p.F * NW * 64), threads, 0, s>>>(
-            xs, w.keep_bits, w.frame_base, out, pos_ids, src_index, p.F, N, p.W, NW, row_bytes, cap, frame_offset,
-            tied_rows);
-    else if (row_bytes % 16 == 0)
+    constexpr size_t kRowBlockMin = 1024;
+    if (row_bytes % 16 == 0 && row_bytes >= kRowBlockMin && (!tied || p.B <= 65535)) {   // (clips ride on gridDim.y)
+        const size_t words = (size_t)(tied ? 1 : p.B) * p.F * NW;
+        k_emit_ids<<<(unsigned)((words + 3) / 4), 256, 0, s>>>(w.keep_bits, w.frame_base, pos_ids, src_index, w.src_row,
+                                                              p.F, N, p.W, NW, words, cap, frame_offset);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        // a quarter as many blocks as there could be rows: at the usual kept fractions every block has
+        // one to four rows; 64 threads per KiB of row, at most 256
+        const unsigned threads = (unsigned)(row_bytes >= 4096 ? 256 : row_bytes / 1024 * 64);
+        const unsigned blocks = (unsigned)((cap + 3) / 4);
+        k_copy_rows<<<dim3(blocks, tied ? p.B : 1), threads, 0, s>>>(xs, w.src_row, total_rows, out, row_bytes,
+                                                                     tied_rows, tied_rows);
+        return hipGetLastError();
+    }
+    if (row_bytes % 16 == 0)
         k_emit_rows<16><<<grid, 256, 0, s>>>(xs, w.keep_bits, w.frame_base, out, pos_ids, src_index,
                                              p.F, N, p.W, NW, row_bytes, cap, frame_offset, tied_rows);
     else if (row_bytes % 4 == 0)

@@ -24,6 +24,7 @@ struct Workspace {
     uint16_t* anchor_frag;   // [B,NP/16,C/32,64,8] bf16 anchor frame in MFMA fragment order (matrix-core path)
     uint64_t* keep_bits;     // [B,F,NW] bit i%64 of word i/64 set iff token i is kept (NW=ceil(N/64))
     int32_t*  frame_base;    // [B,F]    output row of the first kept token of every frame
+    int32_t*  src_row;       // [B*F*N]  input token (flat over clips and frames) that output row r copies
     size_t    bytes;
 };
 
@@ -41,6 +42,7 @@ inline Workspace carve(const ttf_params& p, void* base)
     const size_t o_af = take(p.dtype == TTF_BF16 ? B * NP * C * sizeof(uint16_t) : 0);
     const size_t o_kb = take(B * F * NW * sizeof(uint64_t));
     const size_t o_fb = take(B * F * sizeof(int32_t));
+    const size_t o_sr = take(B * F * N * sizeof(int32_t));
     char* c = static_cast<char*>(base);
     Workspace w;
     w.frame_sum   = reinterpret_cast<float*>(c + o_fs);
@@ -50,6 +52,7 @@ inline Workspace carve(const ttf_params& p, void* base)
     w.anchor_frag = reinterpret_cast<uint16_t*>(c + o_af);
     w.keep_bits   = reinterpret_cast<uint64_t*>(c + o_kb);
     w.frame_base  = reinterpret_cast<int32_t*>(c + o_fb);
+    w.src_row     = reinterpret_cast<int32_t*>(c + o_sr);
     w.bytes = off;
     return w;
 }
@@ -79,8 +82,10 @@ hipError_t launch_pack_keep(const ttf_params& p, const int32_t* fuse_map, const 
                             const Workspace& w, hipStream_t s);
 hipError_t launch_offsets_scan(const ttf_params& p, const Workspace& w, const int32_t* anchor_index,
                                int32_t* kept_count, int32_t* row_offsets, bool tied, hipStream_t s);
+// `total_rows`: device address of the number of output rows (of one clip's share in tied-batch mode),
+// as the offsets scan has left it.
 hipError_t launch_emit_rows(const ttf_params& p, const void* x, const Workspace& w,
-                            const int32_t* anchor_index, void* tokens_out, int32_t* pos_ids,
+                            const int32_t* total_rows, void* tokens_out, int32_t* pos_ids,
                             int32_t* src_index, int frame_offset, bool tied, hipStream_t s);
 
 // Tied-batch mode.  Workspace behind the common sections: every window similarity of every
