@@ -65,6 +65,40 @@ __global__ __launch_bounds__(256) void k_frame_sums(const T* __restrict__ x, flo
     }
 }
 
+// The same sums for rows that are whole 4 KiB slabs: a block owns one frame and one slab, every
+// thread its 16 bytes of the slab for all N rows (eight rows in flight), so the four waves of a block
+// read 4 KiB of one row together and no cross-wave sum is needed.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void k_frame_sums_slab(const T* __restrict__ x, float* __restrict__ frame_sum,
+                                                         int N, int C)
+{
+    const size_t frame = blockIdx.x;
+    const int c0 = (blockIdx.y * 256 + threadIdx.x) * V;
+    const T* base = x + frame * (size_t)N * C + c0;
+    float acc[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[e] = 0.f;
+    int i = 0;
+    for (; i + 8 <= N; i += 8) {
+        RowVec<T, V> r[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) r[u].template load<true>(base + (size_t)(i + u) * C);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+#pragma unroll
+            for (int e = 0; e < V; ++e) acc[e] += r[u].v[e];
+        }
+    }
+    for (; i < N; ++i) {
+        RowVec<T, V> r0;
+        r0.template load<true>(base + (size_t)i * C);
+#pragma unroll
+        for (int e = 0; e < V; ++e) acc[e] += r0.v[e];
+    }
+#pragma unroll
+    for (int e = 0; e < V; ++e) frame_sum[frame * (size_t)C + c0 + e] = acc[e];
+}
+
 // Per clip and 256-channel slice, in fp64: the clip sum g = sum_k frame_sum[k] (k ascending inside
 // each of sixteen interleaved groups, groups added in order), then for every frame the slice's share
 // of <frame_sum_k, g> and |frame_sum_k|^2, and the slice's share of |g|^2.  The cosine of the
@@ -377,6 +411,11 @@ hipError_t launch_frame_sums(const ttf_params& p, const void* x, const Workspace
     return by_layout(p, [&](auto tag, auto vtag) {
         using T = decltype(tag);
         constexpr int V = decltype(vtag)::value;
+        if (V > 1 && p.C % (256 * V) == 0 && (size_t)p.B * p.F * (p.C / (256 * V)) >= 512) {
+            dim3 slabs((unsigned)(p.B * p.F), (unsigned)(p.C / (256 * V)));
+            k_frame_sums_slab<T, V><<<slabs, 256, 0, s>>>(static_cast<const T*>(x), w.frame_sum, N, p.C);
+            return hipGetLastError();
+        }
         dim3 grid((unsigned)(p.B * p.F), (unsigned)((p.C + 64 * V - 1) / (64 * V)));
         k_frame_sums<T, V><<<grid, 256, 0, s>>>(static_cast<const T*>(x), w.frame_sum, N, p.C);
         return hipGetLastError();

@@ -133,7 +133,10 @@ SHAPES = [
     (4, 31, 63, 17, 264, "f32", 1),      # ragged keep words, two channel chunks
     (2, 40, 90, 20, 8, "bf16", 0),       # 1x1 window, a single 16-byte piece per row
     (3, 12, 64, 64, 16, "f32", 1),       # halo too large for LDS at this width: direct kernel on a large input
-    # rows of 6 KiB and more are emitted by one block per token
+    # whole 4 KiB slabs per row and at least 512 (frame, slab) pairs: the slab form of the frame sums
+    (8, 32, 4, 4, 2048, "f32", 1),       # fp32, N = 16: two rounds of eight rows
+    (4, 64, 3, 5, 4096, "bf16", 1),      # bf16, N = 15: one round and a tail of seven rows
+    # long rows: ids first, then a copy driven by output rows
     (2, 4, 5, 7, 1536, "f32", 1),        # 6 KiB fp32 rows, N = 35: one ragged keep word, general path
     (1, 3, 9, 9, 3072, "bf16", 1),       # 6 KiB bf16 rows on padded tile rows
     (2, 3, 3, 70, 1540, "f32", 2),       # rows that are not a whole number of 256-piece rounds (385 pieces)
