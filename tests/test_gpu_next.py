@@ -336,10 +336,11 @@ def test_rolling_anchor_chain():
     assert 0 < stream_rows < 2 * cfg.B * (cfg.F - 1) * cfg.H * cfg.W
 
 
-def test_static_stream_appends_nothing():
+@pytest.mark.parametrize("C", [256, 1024])             # short rows, and long rows (copy driven by a row count of 0)
+def test_static_stream_appends_nothing(C):
     import paper_2605_07355_amd as ttf
     from workloads.ttf_gen import identical_frames, f32_to_bf16_bits
-    cfg = CONFIGS["qwen3vl_2b"].scaled(B=2, F=4, C=256)
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=2, F=4, C=C)
     x = f32_to_bf16_bits(identical_frames(cfg, seed=5))
     out = _run_segment(x[:, 1:], x[:, 0], 1, 1, 0.9)
     assert out.total_rows == 0

@@ -172,10 +172,11 @@ def test_single_frame(oracle):
     assert res.kept_count[0] == cfg.N
 
 
+@pytest.mark.parametrize("C", [128, 1024])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_identical_frames_fuse_everything(oracle, dtype):
+def test_identical_frames_fuse_everything(oracle, dtype, C):
     """Every source token equals its anchor token: cos = 1 at dst = i, everything fused."""
-    cfg = CONFIGS["tiny"].scaled(B=2, F=5, H=9, W=9, C=128)
+    cfg = CONFIGS["tiny"].scaled(B=2, F=5, H=9, W=9, C=C)
     x = identical_frames(cfg, seed=3)
     x = f32_to_bf16_bits(x) if dtype == "bf16" else x
     res, out = _direct(x, 1, 0.7, 2, oracle)         # anchor fixed: all frame scores tie
