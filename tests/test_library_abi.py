@@ -49,6 +49,13 @@ def test_workspace_size_and_argument_checks():
         with pytest.raises(ttf.TTFError) as e:
             ttf.ttf_workspace_size(**kw)
         assert e.value.status == 1, bad
+    # token counts are also bounded with every frame rounded up to whole 64-token keep words
+    kw = dict(B=2**10, F=2**10, H=1, W=65, C=64, dtype=torch.bfloat16, r=1, t=0.7, anchor="auto")
+    assert ttf.ttf_workspace_size(**kw) > 0                      # 2^20 frames x 128 = 2^27
+    kw.update(B=2**14)                                           # 2^24 frames x 65 tokens < 2^31, x 128 = 2^31
+    with pytest.raises(ttf.TTFError) as e:
+        ttf.ttf_workspace_size(**kw)
+    assert e.value.status == 1
 
 
 def test_compress_rejects_null_pointers_without_a_gpu():
