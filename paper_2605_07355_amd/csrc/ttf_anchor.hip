@@ -105,29 +105,50 @@ __global__ __launch_bounds__(256) void k_frame_sums_slab(const T* __restrict__ x
 // anchor rule is assembled from these shares by pick_anchor().
 __global__ __launch_bounds__(1024) void k_anchor_partials(const float* __restrict__ frame_sum,
                                                          double* __restrict__ score_part,
-                                                         double* __restrict__ clip_part, int F, int C, int S)
+                                                         double* __restrict__ clip_part, int F, int C, int S,
+                                                         int FG)
 {
+    // Long clips: FG blocks share a (clip, slice); each forms the clip sum itself (frame sums come
+    // from L2) and scores its own run of frames, so that few clips still fill the chip.
     constexpr int NWV = 16, UN = 8;                     // waves per block, frames in flight per wave
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int slice = blockIdx.x % S;
-    const size_t b = blockIdx.x / S;
+    const int fg = blockIdx.x % FG;
+    const int slice = (blockIdx.x / FG) % S;
+    const size_t b = blockIdx.x / FG / S;
+    const int per = (F + FG - 1) / FG;                  // frames scored by one block
+    const int k_lo = fg * per, k_hi = min(F, k_lo + per);
     const float* fs = frame_sum + b * (size_t)F * C;
     __shared__ double gsh[NWV][256];
     int c[4];
     bool ok[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        c[e] = slice * 256 + lane + 64 * e;
+        c[e] = slice * 256 + lane * 4 + e;             // four consecutive channels per lane: one 16-byte load
         ok[e] = c[e] < C;
     }
+    // this lane's four channels of one frame sum: one 16-byte load when the row allows it
+    const bool vec = (C % 4 == 0) && ok[3];
+    auto load4 = [&](const float* row, float* out) {
+        if (vec) {
+            const float4 q = *reinterpret_cast<const float4*>(row + c[0]);
+            out[0] = q.x; out[1] = q.y; out[2] = q.z; out[3] = q.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (ok[e]) out[e] = row[c[e]];
+        }
+    };
+    // short clips: every wave's frames fit its registers, so the second pass re-uses the first's loads
+    const bool resident = F <= NWV * UN && FG == 1;
+    float v[UN][4];
     double gp[4] = {0.0, 0.0, 0.0, 0.0};
     for (int k0 = wave; k0 < F; k0 += NWV * UN) {
-        float v[UN][4];
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
             const int k = k0 + NWV * u;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[u][e] = (k < F && ok[e]) ? fs[(size_t)k * C + c[e]] : 0.f;
+            for (int e = 0; e < 4; ++e) v[u][e] = 0.f;
+            if (k < F) load4(fs + (size_t)k * C, v[u]);
         }
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
@@ -136,12 +157,12 @@ __global__ __launch_bounds__(1024) void k_anchor_partials(const float* __restric
         }
     }
 #pragma unroll
-    for (int e = 0; e < 4; ++e) gsh[wave][lane + 64 * e] = gp[e];
+    for (int e = 0; e < 4; ++e) gsh[wave][lane * 4 + e] = gp[e];
     __syncthreads();
     double g[4], vv = 0.0;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        const int q = lane + 64 * e;
+        const int q = lane * 4 + e;
         double t = gsh[0][q];
 #pragma unroll
         for (int w = 1; w < NWV; ++w) t += gsh[w][q];
@@ -149,14 +170,16 @@ __global__ __launch_bounds__(1024) void k_anchor_partials(const float* __restric
         vv += t * t;
     }
     vv = wave_sum(vv);
-    if (threadIdx.x == 0) clip_part[b * S + slice] = vv;
-    for (int k0 = wave; k0 < F; k0 += NWV * UN) {
-        float v[UN][4];
+    if (threadIdx.x == 0 && fg == 0) clip_part[b * S + slice] = vv;
+    for (int k0 = k_lo + wave; k0 < k_hi; k0 += NWV * UN) {
+        if (!resident) {
 #pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int k = k0 + NWV * u;
+            for (int u = 0; u < UN; ++u) {
+                const int k = k0 + NWV * u;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[u][e] = (k < F && ok[e]) ? fs[(size_t)k * C + c[e]] : 0.f;
+                for (int e = 0; e < 4; ++e) v[u][e] = 0.f;
+                if (k < k_hi) load4(fs + (size_t)k * C, v[u]);
+            }
         }
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
@@ -170,7 +193,7 @@ __global__ __launch_bounds__(1024) void k_anchor_partials(const float* __restric
             }
             uv = wave_sum(uv);
             uu = wave_sum(uu);
-            if (lane == 0 && k < F) {
+            if (lane == 0 && k < k_hi) {
                 double* o = score_part + ((b * S + slice) * (size_t)F + k) * 2;
                 o[0] = uv;
                 o[1] = uu;
@@ -425,8 +448,11 @@ hipError_t launch_frame_sums(const ttf_params& p, const void* x, const Workspace
 hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, hipStream_t s)
 {
     const int S = (p.C + 255) / 256;
-    k_anchor_partials<<<(unsigned)((size_t)S * p.B), 1024, 0, s>>>(w.frame_sum, w.score_part, w.clip_part,
-                                                                       p.F, p.C, S);
+    // runs of at least 32 frames, and no more blocks than fill the chip a few times
+    int FG = 1;
+    while (FG < 16 && (size_t)S * p.B * FG < 512 && p.F >= 64 * FG) FG *= 2;
+    k_anchor_partials<<<(unsigned)((size_t)S * p.B * FG), 1024, 0, s>>>(w.frame_sum, w.score_part, w.clip_part,
+                                                                            p.F, p.C, S, FG);
     return hipGetLastError();
 }
 
