@@ -3,13 +3,17 @@
     python -m paper_2605_07355_amd.build
 
 The result, ``libttf.so``, is placed inside the package directory and loaded from there.
+Every source file is compiled to an object of its own (in parallel) and the objects are linked.
 """
 from __future__ import annotations
 
 import glob
 import os
+import shutil
 import subprocess
 import sys
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
@@ -18,28 +22,44 @@ LIB_PATH = os.path.join(PKG_DIR, "libttf.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # keep the compiler from forming packed-fp32 VALU instructions out of ordinary float code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
 ]
+_NOISE = "is not a recognized feature for this target"   # host pass does not know the GPU feature
 
 
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build_library(verbose: bool = True) -> str:
-    cmd = [HIPCC, *FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB_PATH, *sources()]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    noise = "is not a recognized feature for this target"   # host pass does not know the GPU feature
-    out = "\n".join(l for l in proc.stdout.splitlines() if noise not in l)
+    out = "\n".join(l for l in proc.stdout.splitlines() if _NOISE not in l)
     if verbose and out.strip():
-        print(out)
+        print(out, flush=True)
     if proc.returncode != 0:
-        raise RuntimeError(f"hipcc failed ({proc.returncode}):\n{out}")
+        raise RuntimeError(f"hipcc failed ({proc.returncode}): {' '.join(cmd)}\n{out}")
+
+
+def build_library(verbose: bool = True, jobs: int | None = None) -> str:
+    jobs = jobs or max(1, min(8, os.cpu_count() or 1))
+    tmp = tempfile.mkdtemp(prefix="ttf_build_")
+    try:
+        objs = []
+        cmds = []
+        for src in sources():
+            obj = os.path.join(tmp, os.path.basename(src)[:-4] + ".o")
+            objs.append(obj)
+            cmds.append([HIPCC, *FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c", src, "-o", obj])
+        with ThreadPoolExecutor(max_workers=jobs) as pool:
+            list(pool.map(lambda c: _run(c, verbose), cmds))
+        _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs], verbose)
+    finally:
+        shutil.rmtree(tmp, ignore_errors=True)
     return LIB_PATH
 
 
