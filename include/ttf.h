@@ -120,6 +120,25 @@ ttf_status ttf_compress(const ttf_params* params, const void* features,
                         const ttf_outputs* out, void* hip_stream);
 
 /*
+ * ttf_compress for callers that cannot allocate device memory or hand over a workspace: code
+ * running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, outputs, kernels and errors as ttf_compress, but the workspace is a fixed array of
+ * TTF_STATIC_WORKSPACE_BYTES that lives in the library's device image (every GPU the library is
+ * used on holds its own copy from the first use until the process ends).  The call allocates and
+ * frees nothing.
+ *   - Problems whose ttf_workspace_size() exceeds TTF_STATIC_WORKSPACE_BYTES are refused with
+ *     TTF_ERR_WORKSPACE_TOO_SMALL before anything is launched.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two threads) race and give undefined outputs; order them on one stream or with events.
+ *     The array keeps the previous call's contents; nothing in it needs to start at zero.
+ *   - The first call on a device looks up the array's device address (hipGetSymbolAddress); make
+ *     that call outside any stream capture.  TTF_ERR_HIP if the lookup fails.
+ */
+#define TTF_STATIC_WORKSPACE_BYTES (16u << 20)
+ttf_status ttf_compress_static(const ttf_params* params, const void* features,
+                               const ttf_outputs* out, void* hip_stream);
+
+/*
  * One segment of a stream (Discussion D3: the last frame of each segment is the rolling anchor of
  * the next; new frames are compressed against it and only the short result is appended).
  * Every one of the F frames of `features` is a source frame matched against `anchor_frame`; the

@@ -13,6 +13,8 @@ from .binding import (  # noqa: F401
     library_path,
     load_library,
     ttf_compress,
+    ttf_compress_static,
+    TTF_STATIC_WORKSPACE_BYTES,
     ttf_workspace_size,
     ttf_status_string,
     ttf_last_hip_error,

@@ -63,6 +63,8 @@ def load_library() -> ctypes.CDLL:
         lib.ttf_compress.argtypes = [ctypes.POINTER(_Params), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                                      ctypes.POINTER(_Outputs), ctypes.c_void_p]
         vp, i64 = ctypes.c_void_p, ctypes.c_int64
+        lib.ttf_compress_static.restype = ctypes.c_int
+        lib.ttf_compress_static.argtypes = [ctypes.POINTER(_Params), vp, ctypes.POINTER(_Outputs), vp]
         lib.ttf_compress_segment.restype = ctypes.c_int
         lib.ttf_compress_segment.argtypes = [ctypes.POINTER(_Params), vp, vp, ctypes.c_int32, vp, ctypes.c_size_t,
                                              ctypes.POINTER(_Outputs), vp]
@@ -111,7 +113,7 @@ def _check(status: int) -> None:
 def _stage_names():
     try:
         lib = load_library()
-    except (FileNotFoundError, OSError):
+    except (FileNotFoundError, OSError, AttributeError):   # not built yet, or an older build
         return tuple(f"stage{i}" for i in range(TTF_NUM_STAGES))
     return tuple(lib.ttf_stage_name(i).decode() for i in range(TTF_NUM_STAGES))
 
@@ -236,6 +238,26 @@ def ttf_compress(features: torch.Tensor, r: int = 1, t: float = 0.70, anchor: Un
     with torch.cuda.device(features.device):
         _check(load_library().ttf_compress(ctypes.byref(p), features.data_ptr(), ws_ptr, ws_bytes,
                                            ctypes.byref(o), ctypes.c_void_p(s.cuda_stream)))
+    return TTFOutput(buffers, B, F, H, W, C)
+
+
+TTF_STATIC_WORKSPACE_BYTES = 16 << 20
+
+
+def ttf_compress_static(features: torch.Tensor, buffers: TTFBuffers, r: int = 1, t: float = 0.70,
+                        anchor: Union[str, int] = "auto",
+                        stream: Optional[torch.cuda.Stream] = None) -> TTFOutput:
+    """``ttf_compress`` on the library's built-in workspace: nothing is allocated by the call, so
+    ``buffers`` (outputs; its ``workspace`` field is not used) must be given.  Problems that need more
+    than ``TTF_STATIC_WORKSPACE_BYTES`` of workspace raise ``TTFError`` (status 3)."""
+    if features.dim() != 5 or not features.is_cuda or not features.is_contiguous():
+        raise ValueError("features must be a contiguous [B,F,H,W,C] GPU tensor")
+    B, F, H, W, C = (int(v) for v in features.shape)
+    p = _make_params(B, F, H, W, C, _dtype_code(features.dtype), r, t, anchor)
+    o = _outputs_of(buffers)
+    with torch.cuda.device(features.device):
+        _check(load_library().ttf_compress_static(ctypes.byref(p), features.data_ptr(), ctypes.byref(o),
+                                                  _stream_ptr(stream, features.device)))
     return TTFOutput(buffers, B, F, H, W, C)
 
 

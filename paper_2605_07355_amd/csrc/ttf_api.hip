@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "ttf_internal.h"
 
@@ -161,6 +162,45 @@ ttf_status ttf_compress(const ttf_params* params, const void* features, void* wo
                         size_t workspace_bytes, const ttf_outputs* out, void* hip_stream)
 {
     return run_pass(params, features, nullptr, 0, workspace, workspace_bytes, out, hip_stream);
+}
+
+// Workspace of ttf_compress_static.  In host code this name is only a handle for the runtime's symbol
+// lookup, never a device address: host code uses the pointer hipGetSymbolAddress returns for the
+// current device (every GPU holds its own copy of the array at its own address).
+static __device__ __align__(256) unsigned char scratch[TTF_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` per device, looked up once
+}  // namespace
+
+ttf_status ttf_compress_static(const ttf_params* params, const void* features, const ttf_outputs* out,
+                               void* hip_stream)
+{
+    const ttf_status st = check_params(params);
+    if (st != TTF_OK) return st;
+    if (!features || !out) return TTF_ERR_INVALID_ARG;
+    if (carve(*params, nullptr).bytes > (size_t)TTF_STATIC_WORKSPACE_BYTES) return TTF_ERR_WORKSPACE_TOO_SMALL;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) e = hipErrorInvalidDevice;
+    void* ptr = nullptr;
+    if (e == hipSuccess) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void* found = nullptr;
+            e = hipGetSymbolAddress(&found, HIP_SYMBOL(scratch));
+            if (e == hipSuccess && !found) e = hipErrorInvalidSymbol;
+            if (e == hipSuccess) g_scratch_ptr[dev] = found;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    if (e != hipSuccess) {
+        g_last_hip_error = static_cast<int>(e);
+        return TTF_ERR_HIP;
+    }
+    return run_pass(params, features, nullptr, 0, ptr, (size_t)TTF_STATIC_WORKSPACE_BYTES, out, hip_stream);
 }
 
 ttf_status ttf_compress_segment(const ttf_params* params, const void* features, const void* anchor_frame,
