@@ -95,7 +95,7 @@ typedef struct {
                                an asynchronous copy on the stream.  May be NULL.                       */
 } ttf_outputs;
 
-/* Bytes of device workspace ttf_compress needs for these sizes (depends on B,F,H,W,C only).
+/* Bytes of device workspace ttf_compress needs for these sizes (depends on B,F,H,W,C and dtype only).
  * The workspace must be 256-byte aligned.  INVALID_ARG on bad sizes or NULL pointers. */
 ttf_status ttf_workspace_size(const ttf_params* params, size_t* bytes);
 
@@ -262,9 +262,32 @@ const char* ttf_status_string(ttf_status status);
 int ttf_last_hip_error(void);
 
 /*
+ * How ttf_compress evaluates the automatic anchor rule (the anchor-frame-selection equation needs the
+ * mean of every frame, i.e. a pass over the whole input before the search can start).
+ *   two-pass      frame sums over the whole input, then the search.
+ *   speculative   the rule is first evaluated on 256 of the C channels (four runs of 64 channels,
+ *                 run j starting at channel (2j+1)*C/8 rounded down to a multiple of 64).  A clip
+ *                 whose guessed best frame beats the runner-up by at least 0.1 in that cosine is
+ *                 searched against the guess at once, the search adds up the exact sums of every
+ *                 frame on the side, and the exact rule is evaluated from them afterwards: it
+ *                 confirms the guess, or the clip's search is repeated against the exact anchor.
+ *                 Clips without a clear guess take the two-pass route.  Outputs are those of the
+ *                 exact rule in every case; only the time differs (one pass over the input instead
+ *                 of two when the guesses hold, up to one extra search when they do not).
+ *                 Available for bf16 input on grids 16 or 32 wide with H*W % 64 == 0, C % 128 == 0,
+ *                 C >= 1024, r <= 2, F >= 2, automatic anchor.
+ * mode  0 (default): speculative for inputs of 256 MiB and more where available, else two-pass;
+ *       1: speculative wherever available;  -1: always two-pass.
+ * Process-wide; takes effect for calls made after it returns.  INVALID_ARG for other values.
+ */
+ttf_status ttf_set_speculation(int mode);
+
+/*
  * Per-stage timing, for benchmarks.  Stages, in launch order:
- *   0 frame sums   1 anchor scores   2 anchor choice + norms   3 window search + gate
- *   4 offsets scan 5 row emission
+ *   0 frame sums (speculative route: the anchor guess, and exact sums of the clips without a clear
+ *     guess)   1 anchor scores   2 anchor choice + norms   3 window search + gate
+ *   4 anchor verification (speculative route only: exact rule from the search's sums, repeated
+ *     search of refuted clips)   5 offsets scan   6 row emission
  * ttf_profile_enable(slots), 1 <= slots <= TTF_PROFILE_MAX_SLOTS, makes every following
  * ttf_compress on the calling thread record HIP events around each stage on the call's
  * stream; successive calls use `slots` event sets round-robin (created once, reused), so up to
@@ -275,7 +298,7 @@ int ttf_last_hip_error(void);
  * run report ~0.  Event records sit between the kernels; profiling is off by default.
  * Errors: INVALID_ARG (bad slot count, NULL, call not available), HIP.
  */
-#define TTF_NUM_STAGES 6
+#define TTF_NUM_STAGES 7
 #define TTF_PROFILE_MAX_SLOTS 256
 ttf_status ttf_profile_enable(int slots);
 ttf_status ttf_profile_read(int call, float* ms_out, int n);

@@ -27,6 +27,7 @@ from .binding import (  # noqa: F401
     ttf_decode_alignment,
     ttf_select_threshold,
     ttf_regate,
+    ttf_set_speculation,
     ttf_profile_enable,
     ttf_profile_read,
 )

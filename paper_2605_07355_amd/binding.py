@@ -14,7 +14,7 @@ _LIB_PATH = os.path.join(_PKG_DIR, "libttf.so")
 TTF_OK, TTF_ERR_INVALID_ARG, TTF_ERR_UNSUPPORTED, TTF_ERR_WORKSPACE_TOO_SMALL, TTF_ERR_HIP = range(5)
 TTF_BF16, TTF_F32 = 0, 1
 TTF_ANCHOR_AUTO, TTF_ANCHOR_FIXED = 0, 1
-TTF_NUM_STAGES = 6
+TTF_NUM_STAGES = 7
 
 
 class TTFError(RuntimeError):
@@ -84,6 +84,8 @@ def load_library() -> ctypes.CDLL:
         lib.ttf_regate.restype = ctypes.c_int
         lib.ttf_regate.argtypes = [ctypes.POINTER(_Params), vp, vp, vp, ctypes.c_size_t,
                                    ctypes.POINTER(_Outputs), vp]
+        lib.ttf_set_speculation.restype = ctypes.c_int
+        lib.ttf_set_speculation.argtypes = [ctypes.c_int]
         lib.ttf_status_string.restype = ctypes.c_char_p
         lib.ttf_status_string.argtypes = [ctypes.c_int]
         lib.ttf_last_hip_error.restype = ctypes.c_int
@@ -436,6 +438,12 @@ def ttf_regate(features: torch.Tensor, out: TTFOutput, thresholds: Optional[torc
         _check(load_library().ttf_regate(ctypes.byref(p), features.data_ptr(), _ptr(thresholds), ws_ptr, ws_bytes,
                                          ctypes.byref(o), _stream_ptr(stream, features.device)))
     return out
+
+
+def ttf_set_speculation(mode: int) -> None:
+    """How the automatic anchor rule is evaluated: 0 speculative single pass for large inputs where
+    available (default), 1 wherever available, -1 always the two-pass route.  Outputs never differ."""
+    _check(load_library().ttf_set_speculation(int(mode)))
 
 
 def ttf_profile_enable(slots: int) -> None:

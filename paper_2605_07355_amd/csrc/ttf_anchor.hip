@@ -17,12 +17,15 @@ constexpr int kAnchorGiven = -2;   // "fixed_anchor" value: the anchor of every 
 
 // One block = one frame x one slice of 64*V channels.  Wave w adds rows w, w+4, ...; the four
 // partial sums are combined through LDS in wave order, so the result is order-stable.
+// `spec` (may be null): per clip {guessed anchor, guess trusted, ...}; clips whose guess is trusted
+// need no exact sums before the search and are skipped.
 template <typename T, int V>
 __global__ __launch_bounds__(256) void k_frame_sums(const T* __restrict__ x, float* __restrict__ frame_sum,
-                                                    int N, int C)
+                                                    int N, int C, int F, const int32_t* __restrict__ spec)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t frame = blockIdx.x;
+    if (spec && spec[4 * (frame / F) + 1]) return;
     const int c0 = (blockIdx.y * 64 + lane) * V;
     __shared__ float part[4][64 * V];
     float acc[V];
@@ -70,9 +73,10 @@ __global__ __launch_bounds__(256) void k_frame_sums(const T* __restrict__ x, flo
 // read 4 KiB of one row together and no cross-wave sum is needed.
 template <typename T, int V>
 __global__ __launch_bounds__(256) void k_frame_sums_slab(const T* __restrict__ x, float* __restrict__ frame_sum,
-                                                         int N, int C)
+                                                         int N, int C, int F, const int32_t* __restrict__ spec)
 {
     const size_t frame = blockIdx.x;
+    if (spec && spec[4 * (frame / F) + 1]) return;
     const int c0 = (blockIdx.y * 256 + threadIdx.x) * V;
     const T* base = x + frame * (size_t)N * C + c0;
     float acc[V];
@@ -103,21 +107,31 @@ __global__ __launch_bounds__(256) void k_frame_sums_slab(const T* __restrict__ x
 // each of sixteen interleaved groups, groups added in order), then for every frame the slice's share
 // of <frame_sum_k, g> and |frame_sum_k|^2, and the slice's share of |g|^2.  The cosine of the
 // anchor rule is assembled from these shares by pick_anchor().
+// STRIPPED: a frame sum is not stored as such but as `strips` partial sums (one per 32-token strip,
+// written by the window search, [B,F,strips,C]); they are added in ascending strip order (fp32) as
+// they are loaded.  skip_mode 1: clips whose anchor guess is trusted are skipped; 2: only those
+// clips are done (spec[b] = {guessed anchor, guess trusted, ...}).
+template <bool STRIPPED>
 __global__ __launch_bounds__(1024) void k_anchor_partials(const float* __restrict__ frame_sum,
                                                          double* __restrict__ score_part,
                                                          double* __restrict__ clip_part, int F, int C, int S,
-                                                         int FG)
+                                                         int FG, int strips, const int32_t* __restrict__ spec,
+                                                         int skip_mode)
 {
     // Long clips: FG blocks share a (clip, slice); each forms the clip sum itself (frame sums come
     // from L2) and scores its own run of frames, so that few clips still fill the chip.
-    constexpr int NWV = 16, UN = 8;                     // waves per block, frames in flight per wave
+    constexpr int NWV = 16;                             // waves per block
+    constexpr int UN = STRIPPED ? 2 : 8;                // frames in flight per wave
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int fg = blockIdx.x % FG;
     const int slice = (blockIdx.x / FG) % S;
     const size_t b = blockIdx.x / FG / S;
+    if (skip_mode == 1 && spec[4 * b + 1]) return;
+    if (skip_mode == 2 && !spec[4 * b + 1]) return;
     const int per = (F + FG - 1) / FG;                  // frames scored by one block
     const int k_lo = fg * per, k_hi = min(F, k_lo + per);
-    const float* fs = frame_sum + b * (size_t)F * C;
+    const size_t fstride = STRIPPED ? (size_t)strips * C : (size_t)C;   // floats between consecutive frames
+    const float* fs = frame_sum + b * (size_t)F * fstride;
     __shared__ double gsh[NWV][256];
     int c[4];
     bool ok[4];
@@ -129,7 +143,18 @@ __global__ __launch_bounds__(1024) void k_anchor_partials(const float* __restric
     // this lane's four channels of one frame sum: one 16-byte load when the row allows it
     const bool vec = (C % 4 == 0) && ok[3];
     auto load4 = [&](const float* row, float* out) {
-        if (vec) {
+        if constexpr (STRIPPED) {                      // (C % 128 == 0 on this path: always 16-byte loads)
+            if (!ok[3]) return;                        // the last slice may reach beyond C
+            for (int s0 = 0; s0 < strips; s0 += 8) {
+                float4 q[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (s0 + u < strips) q[u] = *reinterpret_cast<const float4*>(row + (size_t)(s0 + u) * C + c[0]);
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (s0 + u < strips) { out[0] += q[u].x; out[1] += q[u].y; out[2] += q[u].z; out[3] += q[u].w; }
+            }
+        } else if (vec) {
             const float4 q = *reinterpret_cast<const float4*>(row + c[0]);
             out[0] = q.x; out[1] = q.y; out[2] = q.z; out[3] = q.w;
         } else {
@@ -148,7 +173,7 @@ __global__ __launch_bounds__(1024) void k_anchor_partials(const float* __restric
             const int k = k0 + NWV * u;
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[u][e] = 0.f;
-            if (k < F) load4(fs + (size_t)k * C, v[u]);
+            if (k < F) load4(fs + (size_t)k * fstride, v[u]);
         }
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
@@ -178,7 +203,7 @@ __global__ __launch_bounds__(1024) void k_anchor_partials(const float* __restric
                 const int k = k0 + NWV * u;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[u][e] = 0.f;
-                if (k < k_hi) load4(fs + (size_t)k * C, v[u]);
+                if (k < k_hi) load4(fs + (size_t)k * fstride, v[u]);
             }
         }
 #pragma unroll
@@ -199,6 +224,120 @@ __global__ __launch_bounds__(1024) void k_anchor_partials(const float* __restric
                 o[1] = uu;
             }
         }
+    }
+}
+
+// Anchor guess, step 1 (bf16 rows): sums over the N tokens of a frame of the kGuessChannels guess
+// channels only (kGuessSegments runs of 128 bytes per token row).  One block per frame: thread t
+// reads 16-byte piece t%32 of the guess channels of tokens t/32, t/32 + 8, ...; the eight token
+// groups are added through LDS in order.
+__global__ __launch_bounds__(256) void k_guess_sums(const uint16_t* __restrict__ x, float* __restrict__ guess_sum,
+                                                    int N, int C)
+{
+    static_assert(kGuessSegChannels == 64 && kGuessSegments * 8 == 32, "32 sixteen-byte pieces per token");
+    const size_t frame = blockIdx.x;
+    const int ts = threadIdx.x >> 5, q = threadIdx.x & 31;
+    const int ch = guess_segment_start(C, q >> 3) + (q & 7) * 8;
+    const uint16_t* base = x + frame * (size_t)N * C + ch;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    for (int i0 = ts; i0 < N; i0 += 64) {
+        RowVec<bf16_t, 8> r[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + 8 * u;
+            if (i < N) r[u].template load<false>(reinterpret_cast<const bf16_t*>(base + (size_t)i * C));
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (i0 + 8 * u < N) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] += r[u].v[e];
+            }
+        }
+    }
+    __shared__ float part[8][kGuessChannels];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part[ts][q * 8 + e] = acc[e];
+    __syncthreads();
+    float t = part[0][threadIdx.x];
+#pragma unroll
+    for (int w = 1; w < 8; ++w) t += part[w][threadIdx.x];
+    guess_sum[frame * kGuessChannels + threadIdx.x] = t;
+}
+
+// Anchor guess, step 2: the anchor rule evaluated on the guess channels alone (fp64 from the fp32
+// sums of step 1).  One block per clip.  The guess is trusted when its score beats the runner-up's by
+// at least kGuessMinGap and no score is NaN; the search then runs against it before the exact rule
+// has been evaluated, and the exact rule (from sums the search produces on the side) confirms it or
+// triggers a second search.  spec[b] = {guessed frame (lowest k on ties), trusted, 0, 0}.
+constexpr double kGuessMinGap = 0.1;
+__global__ __launch_bounds__(1024) void k_guess_pick(const float* __restrict__ guess_sum, int32_t* __restrict__ spec,
+                                                    int F)
+{
+    constexpr int NWV = 16;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t b = blockIdx.x;
+    const float* gs = guess_sum + b * (size_t)F * kGuessChannels + lane * 4;
+    __shared__ double gsh[NWV][kGuessChannels];
+    __shared__ double s_best[NWV], s_second[NWV];
+    __shared__ int s_arg[NWV], s_nan[NWV];
+    double gp[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int k = wave; k < F; k += NWV) {
+        const float4 q = *reinterpret_cast<const float4*>(gs + (size_t)k * kGuessChannels);
+        gp[0] += (double)q.x; gp[1] += (double)q.y; gp[2] += (double)q.z; gp[3] += (double)q.w;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) gsh[wave][lane * 4 + e] = gp[e];
+    __syncthreads();
+    double g[4], vv = 0.0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        double t = gsh[0][lane * 4 + e];
+#pragma unroll
+        for (int w = 1; w < NWV; ++w) t += gsh[w][lane * 4 + e];
+        g[e] = t;
+        vv += t * t;
+    }
+    vv = wave_sum(vv);
+    double best = -1.0e300, second = -1.0e300;          // wave-uniform running top two of this wave's frames
+    int arg = 0x7fffffff, nan = 0;
+    for (int k = wave; k < F; k += NWV) {               // ascending k: strict > keeps the lowest on ties
+        const float4 q = *reinterpret_cast<const float4*>(gs + (size_t)k * kGuessChannels);
+        const double xv[4] = {(double)q.x, (double)q.y, (double)q.z, (double)q.w};
+        double uv = 0.0, uu = 0.0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { uv += xv[e] * g[e]; uu += xv[e] * xv[e]; }
+        uv = wave_sum(uv);
+        uu = wave_sum(uu);
+        const double den = sqrt(uu) * sqrt(vv);
+        const double score = den > 0.0 ? uv / den : 0.0;
+        if (!(score == score)) nan = 1;
+        if (score > best) { second = best; best = score; arg = k; }
+        else if (score > second) second = score;
+    }
+    if (lane == 0) { s_best[wave] = best; s_second[wave] = second; s_arg[wave] = arg; s_nan[wave] = nan; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double bb = -1.0e300, sec = -1.0e300;
+        int aa = 0x7fffffff, nn = 0;
+        for (int w = 0; w < NWV; ++w) {
+            nn |= s_nan[w];
+            if (s_best[w] > bb || (s_best[w] == bb && s_arg[w] < aa)) {
+                sec = fmax(sec, bb);
+                bb = s_best[w];
+                aa = s_arg[w];
+            } else {
+                sec = fmax(sec, s_best[w]);
+            }
+            sec = fmax(sec, s_second[w]);
+        }
+        const bool trusted = !nn && aa != 0x7fffffff && (F == 1 || bb - sec >= kGuessMinGap);
+        spec[4 * b + 0] = aa == 0x7fffffff ? 0 : aa;
+        spec[4 * b + 1] = trusted ? 1 : 0;
+        spec[4 * b + 2] = 0;
+        spec[4 * b + 3] = 0;
     }
 }
 
@@ -347,16 +486,31 @@ __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restri
                                                         int32_t* __restrict__ fuse_map, float* __restrict__ best_sim,
                                                         int32_t* __restrict__ best_idx, uint16_t* __restrict__ keep16,
                                                         int F, int N, int C, int S, int fixed_anchor, int tiles,
-                                                        int Wg, int CT)
+                                                        int Wg, int CT, int32_t* __restrict__ spec, int spec_mode)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int b = blockIdx.x / tiles, tile = blockIdx.x % tiles;
     // the anchor is a frame of x (fixed, picked here, or already chosen: kAnchorGiven), or frame b
     // of ext_anchor (published as -1)
-    const int a = ext_anchor ? -1
-                : fixed_anchor >= 0 ? fixed_anchor
-                : fixed_anchor == kAnchorGiven ? anchor_index[b]
-                                               : pick_anchor(score_part, clip_part, b, F, S, lane);
+    int a;
+    if (spec_mode == 0) {
+        a = ext_anchor ? -1
+          : fixed_anchor >= 0 ? fixed_anchor
+          : fixed_anchor == kAnchorGiven ? anchor_index[b]
+                                         : pick_anchor(score_part, clip_part, b, F, S, lane);
+    } else if (spec_mode == 1) {
+        // speculative pass: a trusted guess stands in for the anchor rule until the search has produced
+        // exact frame sums; clips without one had their exact scores computed beforehand
+        a = spec[4 * b + 1] ? spec[4 * b] : pick_anchor(score_part, clip_part, b, F, S, lane);
+    } else {
+        // after the search: the exact rule for the clips that ran on a guess.  Confirmed: nothing to do.
+        // Refuted: publish the exact anchor, mark the clip for a second search and prepare its anchor.
+        if (!spec[4 * b + 1]) return;
+        a = pick_anchor(score_part, clip_part, b, F, S, lane);
+        const bool redo = a != spec[4 * b];
+        if (tile == 0 && threadIdx.x == 0) spec[4 * b + 2] = redo ? 1 : 0;
+        if (!redo) return;
+    }
     if (fixed_anchor != kAnchorGiven && tile == 0 && threadIdx.x == 0) anchor_index[b] = a;
     // flat index of the tile's first token, and how many of its 16 columns exist
     const int first = PAD ? (tile / CT) * Wg + 16 * (tile % CT) : 16 * tile;
@@ -428,31 +582,49 @@ hipError_t by_layout(const ttf_params& p, F&& f)
 
 }  // namespace
 
-hipError_t launch_frame_sums(const ttf_params& p, const void* x, const Workspace& w, hipStream_t s)
+hipError_t launch_frame_sums(const ttf_params& p, const void* x, const Workspace& w, bool skip_trusted, hipStream_t s)
 {
     const int N = p.H * p.W;
+    const int32_t* spec = skip_trusted ? w.spec : nullptr;
     return by_layout(p, [&](auto tag, auto vtag) {
         using T = decltype(tag);
         constexpr int V = decltype(vtag)::value;
         if (V > 1 && p.C % (256 * V) == 0 && (size_t)p.B * p.F * (p.C / (256 * V)) >= 512) {
             dim3 slabs((unsigned)(p.B * p.F), (unsigned)(p.C / (256 * V)));
-            k_frame_sums_slab<T, V><<<slabs, 256, 0, s>>>(static_cast<const T*>(x), w.frame_sum, N, p.C);
+            k_frame_sums_slab<T, V><<<slabs, 256, 0, s>>>(static_cast<const T*>(x), w.frame_sum, N, p.C, p.F, spec);
             return hipGetLastError();
         }
         dim3 grid((unsigned)(p.B * p.F), (unsigned)((p.C + 64 * V - 1) / (64 * V)));
-        k_frame_sums<T, V><<<grid, 256, 0, s>>>(static_cast<const T*>(x), w.frame_sum, N, p.C);
+        k_frame_sums<T, V><<<grid, 256, 0, s>>>(static_cast<const T*>(x), w.frame_sum, N, p.C, p.F, spec);
         return hipGetLastError();
     });
 }
 
-hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, hipStream_t s)
+// mode 0: every clip, from the frame sums; 1: the same, skipping clips whose anchor guess is trusted;
+// 2: only those clips, from the strip sums the search wrote.
+hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, int mode, hipStream_t s)
 {
     const int S = (p.C + 255) / 256;
     // runs of at least 32 frames, and no more blocks than fill the chip a few times
     int FG = 1;
     while (FG < 16 && (size_t)S * p.B * FG < 512 && p.F >= 64 * FG) FG *= 2;
-    k_anchor_partials<<<(unsigned)((size_t)S * p.B * FG), 1024, 0, s>>>(w.frame_sum, w.score_part, w.clip_part,
-                                                                            p.F, p.C, S, FG);
+    const unsigned grid = (unsigned)((size_t)S * p.B * FG);
+    if (mode == 2)
+        k_anchor_partials<true><<<grid, 1024, 0, s>>>(w.strip_sum, w.score_part, w.clip_part, p.F, p.C, S, FG,
+                                                      p.H * p.W / 32, w.spec, 2);
+    else
+        k_anchor_partials<false><<<grid, 1024, 0, s>>>(w.frame_sum, w.score_part, w.clip_part, p.F, p.C, S, FG, 1,
+                                                       w.spec, mode);
+    return hipGetLastError();
+}
+
+// The anchor rule on the guess channels: spec[b] = {guessed frame, trusted, 0, 0} for every clip.
+hipError_t launch_anchor_guess(const ttf_params& p, const void* x, const Workspace& w, hipStream_t s)
+{
+    k_guess_sums<<<(unsigned)(p.B * p.F), 256, 0, s>>>(static_cast<const uint16_t*>(x), w.guess_sum, p.H * p.W, p.C);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    k_guess_pick<<<(unsigned)p.B, 1024, 0, s>>>(w.guess_sum, w.spec, p.F);
     return hipGetLastError();
 }
 
@@ -488,7 +660,7 @@ hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const void* e
 
 hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                       int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
-                                      int32_t* best_idx, bool anchor_given, hipStream_t s)
+                                      int32_t* best_idx, bool anchor_given, int spec_mode, hipStream_t s)
 {
     const int N = p.H * p.W;
     const int fixed = anchor_given ? kAnchorGiven : fixed_frame(p);
@@ -500,7 +672,8 @@ hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const 
                                                        static_cast<const uint16_t*>(ext_anchor), w.score_part,
                                                        w.clip_part, anchor_index, w.anchor_inv, w.anchor_frag, fuse_map,
                                                        best_sim, best_idx, reinterpret_cast<uint16_t*>(w.keep_bits),
-                                                       p.F, N, p.C, (p.C + 255) / 256, fixed, tiles, p.W, CT);
+                                                       p.F, N, p.C, (p.C + 255) / 256, fixed, tiles, p.W, CT,
+                                                       spec_mode ? w.spec : nullptr, spec_mode);
         return hipGetLastError();
     };
     return pad ? go(k_anchor_prepare<true>) : go(k_anchor_prepare<false>);

@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <atomic>
 #include <mutex>
 
 #include "ttf_internal.h"
@@ -16,16 +17,19 @@ hipError_t launch_window_search_generic(const ttf_params& p, const void* x, cons
 
 hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,
                                      const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
-                                     int32_t* best_idx, float* win_sim, hipStream_t s);
+                                     int32_t* best_idx, float* win_sim, int spec_mode, hipStream_t s);
+bool mfma_search_speculative(const ttf_params& p);
 
 // bf16 tokens with r <= 2 and C % 128 == 0 take the matrix-core kernels (grids exactly 16 or 32 wide
 // with whole keep words the aligned ones, every other grid the padded-tile ones); fp32 input, larger radii and other channel counts take the general
-// wave-per-token kernel.  Setting the environment variable TTF_SEARCH=general forces the general
-// kernels (for comparisons).
+// wave-per-token kernel.  The environment variable TTF_SEARCH=general, read once per process, forces
+// the general kernels (for comparisons).
 bool use_mfma_path(const ttf_params& p)
 {
-    const char* force = std::getenv("TTF_SEARCH");
-    const bool general = force && std::strcmp(force, "general") == 0;
+    static const bool general = [] {
+        const char* force = std::getenv("TTF_SEARCH");
+        return force && std::strcmp(force, "general") == 0;
+    }();
     return !general && (mfma_search_supported(p) || mfma_search_padded(p));
 }
 
@@ -35,13 +39,17 @@ hipError_t launch_window_search(const ttf_params& p, const void* x, const void* 
 {
     if (use_mfma_path(p))
         return launch_window_search_mfma(p, x, ext_anchor != nullptr, w, anchor_index, fuse_map, best_sim, best_idx,
-                                         win_sim, s);
+                                         win_sim, 0, s);
     return launch_window_search_generic(p, x, ext_anchor, w, anchor_index, fuse_map, best_sim, best_idx, win_sim, s);
 }
 
 namespace {
 
 thread_local int g_last_hip_error = 0;
+
+// Speculative anchor: -1 never, 0 for inputs of at least kSpeculationMinBytes, 1 whenever the shape allows.
+std::atomic<int> g_speculation{0};
+constexpr unsigned long long kSpeculationMinBytes = 256ull << 20;
 
 // Event sets for stage timing: `slots` sets of TTF_NUM_STAGES+1 events, used round-robin by
 // successive profiled calls so that a benchmark can time many calls and read them afterwards.
@@ -125,24 +133,50 @@ static ttf_status run_pass(const ttf_params* params, const void* features, const
         if (e == hipSuccess) e = (call); \
     } while (0)
 
+    // The automatic anchor rule needs the sum of every frame, i.e. a pass over the whole input before
+    // the search can start.  Large inputs on the aligned matrix-core path avoid that pass: the rule is
+    // first evaluated on a few channels only (4 x 128 bytes of every token row); where that guess wins
+    // clearly the search runs against it at once and adds up, on the side, the exact sums of every
+    // 32-token strip it reads.  The exact rule is then evaluated from those sums: it confirms the
+    // guess (the usual case: nothing else to do) or refutes it, and then the clip's anchor is prepared
+    // again and its search repeated.  Clips whose guess is not clear-cut take the two-pass route.
+    // Either way every output is what the exact rule gives.
+    const int spec_pref = g_speculation.load(std::memory_order_relaxed);
+    const unsigned long long in_bytes = (unsigned long long)p.B * p.F * p.H * p.W * p.C * 2ull;
+    const bool spec = pick && use_mfma_path(p) && mfma_search_speculative(p) &&
+                      (spec_pref > 0 || (spec_pref == 0 && in_bytes >= kSpeculationMinBytes));
+
     mark();                                                    // start of stage 0
-    if (pick) TTF_STEP(launch_frame_sums(p, features, w, s));
+    if (spec) TTF_STEP(launch_anchor_guess(p, features, w, s));
+    if (pick) TTF_STEP(launch_frame_sums(p, features, w, spec, s));
     mark();
-    if (pick) TTF_STEP(launch_anchor_scores(p, w, s));
+    if (pick) TTF_STEP(launch_anchor_scores(p, w, spec ? 1 : 0, s));
     mark();
     if (use_mfma_path(p))
         TTF_STEP(launch_anchor_prepare_mfma(p, features, ext_anchor, w, out->anchor_index, out->fuse_map,
-                                            out->best_sim, out->best_idx, false, s));
+                                            out->best_sim, out->best_idx, false, spec ? 1 : 0, s));
     else TTF_STEP(launch_anchor_norms(p, features, ext_anchor, w, out->anchor_index, false, s));
     mark();
-    TTF_STEP(launch_window_search(p, features, ext_anchor, w, out->anchor_index, out->fuse_map, out->best_sim,
-                                  out->best_idx, nullptr, s));
+    if (spec)
+        TTF_STEP(launch_window_search_mfma(p, features, false, w, out->anchor_index, out->fuse_map, out->best_sim,
+                                           out->best_idx, nullptr, 1, s));
+    else
+        TTF_STEP(launch_window_search(p, features, ext_anchor, w, out->anchor_index, out->fuse_map, out->best_sim,
+                                      out->best_idx, nullptr, s));
+    mark();
+    if (spec) {
+        TTF_STEP(launch_anchor_scores(p, w, 2, s));
+        TTF_STEP(launch_anchor_prepare_mfma(p, features, nullptr, w, out->anchor_index, out->fuse_map,
+                                            out->best_sim, out->best_idx, false, 2, s));
+        TTF_STEP(launch_window_search_mfma(p, features, false, w, out->anchor_index, out->fuse_map, out->best_sim,
+                                           out->best_idx, nullptr, 2, s));
+    }
     mark();
     TTF_STEP(launch_offsets_scan(p, w, out->anchor_index, out->kept_count, out->row_offsets, false, s));
     mark();
     TTF_STEP(launch_emit_rows(p, features, w, out->row_offsets + p.B, out->tokens_out, out->pos_ids,
                               out->src_index, frame_offset, false, s));
-    mark();                                                    // end of stage 5
+    mark();                                                    // end of the last stage
     if (out->host_counts) {
         TTF_STEP(hipMemcpyAsync(out->host_counts, out->kept_count, sizeof(int32_t) * p.B,
                                 hipMemcpyDeviceToHost, s));
@@ -248,13 +282,13 @@ ttf_status ttf_compress_tied(const ttf_params* params, const void* features, voi
         if (e == hipSuccess) e = (call); \
     } while (0)
     if (p.anchor_mode == TTF_ANCHOR_AUTO) {
-        TTF_STEP(launch_frame_sums(p, features, w, s));
-        TTF_STEP(launch_anchor_scores(p, w, s));
+        TTF_STEP(launch_frame_sums(p, features, w, false, s));
+        TTF_STEP(launch_anchor_scores(p, w, 0, s));
     }
     TTF_STEP(launch_tied_anchor(p, w, out->anchor_index, s));
     if (use_mfma_path(p))
         TTF_STEP(launch_anchor_prepare_mfma(p, features, nullptr, w, out->anchor_index, nullptr, nullptr, nullptr,
-                                            true, s));
+                                            true, 0, s));
     else TTF_STEP(launch_anchor_norms(p, features, nullptr, w, out->anchor_index, true, s));
     TTF_STEP(launch_window_search(p, features, nullptr, w, out->anchor_index, nullptr, nullptr, nullptr,
                                   tw.win_sim, s));
@@ -370,6 +404,13 @@ ttf_status ttf_regate(const ttf_params* params, const void* features, const floa
     return TTF_OK;
 }
 
+ttf_status ttf_set_speculation(int mode)
+{
+    if (mode < -1 || mode > 1) return TTF_ERR_INVALID_ARG;
+    g_speculation.store(mode, std::memory_order_relaxed);
+    return TTF_OK;
+}
+
 const char* ttf_status_string(ttf_status status)
 {
     switch (status) {
@@ -421,8 +462,8 @@ ttf_status ttf_profile_read(int call, float* ms_out, int n)
 
 const char* ttf_stage_name(int stage)
 {
-    static const char* names[TTF_NUM_STAGES] = {"frame_sums", "anchor_scores", "anchor_norms",
-                                                "window_search", "offsets_scan", "emit_rows"};
+    static const char* names[TTF_NUM_STAGES] = {"frame_sums", "anchor_scores", "anchor_norms", "window_search",
+                                                "anchor_verify", "offsets_scan", "emit_rows"};
     return (stage >= 0 && stage < TTF_NUM_STAGES) ? names[stage] : "";
 }
 

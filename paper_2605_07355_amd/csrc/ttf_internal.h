@@ -25,8 +25,30 @@ struct Workspace {
     uint64_t* keep_bits;     // [B,F,NW] bit i%64 of word i/64 set iff token i is kept (NW=ceil(N/64))
     int32_t*  frame_base;    // [B,F]    output row of the first kept token of every frame
     int32_t*  src_row;       // [B*F*N]  input token (flat over clips and frames) that output row r copies
+    // Speculative anchor (single pass over the input, see ttf_api.hip); sized 0 where it cannot apply
+    float*    guess_sum;     // [B,F,kGuessChannels] frame sums over the guess channels only
+    int32_t*  spec;          // [B,4]    guessed anchor, guess trusted (1/0), search to be redone (1/0), unused
+    float*    strip_sum;     // [B,F,N/32,C] sum of every 32-token strip of every frame, written by the search
     size_t    bytes;
 };
+
+// Channels the anchor guess looks at: kGuessSegments runs of kGuessSegChannels channels, run j starting
+// at channel (2j+1)*C/(2*kGuessSegments) rounded down to a multiple of kGuessSegChannels.
+constexpr int kGuessSegments = 4;
+constexpr int kGuessSegChannels = 64;
+constexpr int kGuessChannels = kGuessSegments * kGuessSegChannels;
+__host__ __device__ inline int guess_segment_start(int C, int j)
+{
+    return (int)(((long long)(2 * j + 1) * C / (2 * kGuessSegments)) / kGuessSegChannels * kGuessSegChannels);
+}
+// Shapes the speculative anchor path exists for: the aligned matrix-core search kernels (bf16, grid
+// 16 or 32 wide with whole keep words, C % 128 == 0) with at least 1024 channels, so that the guess
+// channels are a small part of a row.  The radius is not looked at (the workspace must not depend on it).
+inline bool speculation_shape(const ttf_params& p)
+{
+    if (p.dtype != TTF_BF16 || p.C % 128 != 0 || p.C < 1024 || p.F < 2) return false;
+    return (p.W == 16 && p.H % 4 == 0) || (p.W == 32 && p.H % 2 == 0);
+}
 
 inline Workspace carve(const ttf_params& p, void* base)
 {
@@ -43,6 +65,10 @@ inline Workspace carve(const ttf_params& p, void* base)
     const size_t o_kb = take(B * F * NW * sizeof(uint64_t));
     const size_t o_fb = take(B * F * sizeof(int32_t));
     const size_t o_sr = take(B * F * N * sizeof(int32_t));
+    const bool spec = speculation_shape(p);
+    const size_t o_gs = take(spec ? B * F * kGuessChannels * sizeof(float) : 0);
+    const size_t o_sp2 = take(spec ? B * 4 * sizeof(int32_t) : 0);
+    const size_t o_ss = take(spec ? B * F * (N / 32) * C * sizeof(float) : 0);
     char* c = static_cast<char*>(base);
     Workspace w;
     w.frame_sum   = reinterpret_cast<float*>(c + o_fs);
@@ -53,13 +79,21 @@ inline Workspace carve(const ttf_params& p, void* base)
     w.keep_bits   = reinterpret_cast<uint64_t*>(c + o_kb);
     w.frame_base  = reinterpret_cast<int32_t*>(c + o_fb);
     w.src_row     = reinterpret_cast<int32_t*>(c + o_sr);
+    w.guess_sum   = reinterpret_cast<float*>(c + o_gs);
+    w.spec        = reinterpret_cast<int32_t*>(c + o_sp2);
+    w.strip_sum   = reinterpret_cast<float*>(c + o_ss);
     w.bytes = off;
     return w;
 }
 
 // Stage launchers.  Each enqueues on `s` and returns the launch status.
-hipError_t launch_frame_sums(const ttf_params& p, const void* x, const Workspace& w, hipStream_t s);
-hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, hipStream_t s);
+// `skip_trusted`: clips whose anchor guess is trusted (w.spec) are left out.
+hipError_t launch_frame_sums(const ttf_params& p, const void* x, const Workspace& w, bool skip_trusted, hipStream_t s);
+// mode 0: every clip, from w.frame_sum; 1: the same without the clips whose guess is trusted; 2: only
+// those clips, from w.strip_sum.
+hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, int mode, hipStream_t s);
+// The anchor rule evaluated on a few channels only: w.spec[b] = {guessed frame, trusted, 0, 0}.
+hipError_t launch_anchor_guess(const ttf_params& p, const void* x, const Workspace& w, hipStream_t s);
 // `ext_anchor` (here and below): nullptr when the anchor is a frame of x; otherwise the anchor
 // frames [B,N,C] of a segment, in which case anchor_index is written as -1 and every frame of x
 // is a source frame.
@@ -71,7 +105,7 @@ hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const void* e
 // the anchor-frame rows of fuse_map / best_sim / best_idx / keep bits.
 hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                       int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
-                                      int32_t* best_idx, bool anchor_given, hipStream_t s);
+                                      int32_t* best_idx, bool anchor_given, int spec_mode, hipStream_t s);
 bool mfma_search_supported(const ttf_params& p);   // grids exactly 16 or 32 wide with whole keep words
 bool mfma_search_padded(const ttf_params& p);      // every other grid (tile rows padded to 16 columns)
 hipError_t launch_window_search(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,

@@ -96,9 +96,16 @@ __device__ __forceinline__ void row_argmax_step(float& best, int& arg)
     arg = take ? oa : arg;
 }
 
-__device__ __forceinline__ bf16x8 load_frag(const uint16_t* p)
+// Buffer descriptor over `bytes` bytes at `base` (raw: no stride, byte offsets; reads beyond the
+// range return zero).  Loads through it take one 32-bit per-lane offset and one wave-uniform offset.
+typedef __amdgpu_buffer_rsrc_t BufferRsrc;
+__device__ __forceinline__ BufferRsrc make_rsrc(const void* base, unsigned bytes)
 {
-    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p));
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ u32x4 buffer_load16(BufferRsrc rs, unsigned lane_bytes, unsigned uniform_bytes)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(rs, (int)lane_bytes, (int)uniform_bytes, 0);
 }
 
 // Final step for one source tile (16 tokens of one frame): v[q] are the complete 16x16 products
@@ -223,14 +230,37 @@ __device__ __forceinline__ void finish_tile(const f32x4* v, const float* nn, int
     if (lane == 0 && live) keep16[o0 / 16] = (uint16_t)keep;
 }
 
+// B operand that picks 16 of the 32 channels of a K-step: E_h[k][n] = 1 iff k == 16h + n (operand
+// order: lane n + 16g holds rows k = 8g .. 8g+7 of column n).  A source tile times E_h is that
+// tile's tokens x channels 16h .. 16h+15 in the MFMA result layout, i.e. a lane then holds four
+// TOKENS of one channel: the form in which a sum over tokens is cheap.
+__device__ __forceinline__ bf16x8 channel_picker(int h, int lane)
+{
+    const int n = lane & 15, g = lane >> 4;
+    const bool mine = g == 2 * h + (n >> 3);
+    const int e = n & 7;
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = (mine && (e >> 1) == i) ? ((e & 1) ? 0x3F800000u : 0x00003F80u) : 0u;
+    return __builtin_bit_cast(bf16x8, uint4{w[0], w[1], w[2], w[3]});
+}
+
 // FRO: source frames per workgroup, 0 = the shape's default.  Small inputs use 1 frame and long
 // passes (more workgroups, fewer dependent rounds of loads per workgroup).
-template <int CT, int RAD, int KSW, int NW, bool ALL, int FRO = 0>
+// SPEC 0: the plain search.  SPEC 1: the search of the speculative pass -- the anchor in
+// anchor_index may be a guess, so every frame of the clip, the anchor frame included, is walked
+// (its outputs are not written) and the sum over the 32 tokens of every (frame, strip) is written to
+// strip_sum[b][k][strip][channel], from which the exact anchor rule is evaluated afterwards.  The
+// sums come from two extra MFMAs per source tile and K-step (channel_picker) whose accumulators add
+// the two tiles of a strip; four in-lane adds and two cross-row steps finish them.
+// SPEC 2: the plain search for the clips marked in spec[b][2] only (guess refuted); other clips exit.
+template <int CT, int RAD, int KSW, int NW, bool ALL, int FRO = 0, int SPEC = 0>
 __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ anchor_frag,
     const int32_t* __restrict__ anchor_index, const float* __restrict__ anchor_inv,
     int32_t* __restrict__ fuse_map, float* __restrict__ best_sim, int32_t* __restrict__ best_idx,
-    uint16_t* __restrict__ keep16, float* __restrict__ win_sim, int F, int H, int C, float t, int passes, int groups)
+    uint16_t* __restrict__ keep16, float* __restrict__ win_sim, int F, int H, int C, float t, int passes, int groups,
+    const int32_t* __restrict__ spec, float* __restrict__ strip_sum)
 {
     using S = Shape<CT, RAD>;
     constexpr int W = S::W, NA = S::NA, NPS = S::NPS, PF = S::PF;
@@ -239,7 +269,8 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
     constexpr int RT = S::RT < NS ? S::RT : NS;              // source tiles per LDS round
     constexpr int NB = PF + 1;                               // anchor fragment ring
     const int N = H * W;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: per-wave offsets stay scalar
     const int m = lane & 15, g = lane >> 4;
     const int tpf = N / 32;                                  // workgroups per frame group
     // Workgroup -> (clip, frame group, 32-cell strip).  Workgroups are dealt to the 8 XCDs round
@@ -258,35 +289,51 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
         grp = (blockIdx.x / tpf) % groups;
         b = blockIdx.x / tpf / groups;
     }
+    if constexpr (SPEC == 2) {
+        if (spec[4 * b + 2] == 0) return;                    // guess confirmed (or never used): nothing to redo
+    }
     const int a_in = anchor_index[b];                        // < 0: the anchor frame lies outside x (segment mode)
-    const int a = a_in < 0 ? F : a_in;                       // then no frame of x is skipped
+    // frame slot -> frame: the anchor frame is skipped, except in the speculative pass, which walks
+    // every frame (a_skip beyond every frame index)
+    const int a_skip = (SPEC == 1 || a_in < 0) ? 0x7fffffff : a_in;
     const int i0 = tp * 32;                                  // first grid cell of this workgroup
 
     const int y0 = i0 / W;                                   // first (or only) source row
     const int ylo = y0 - RAD;
     const int slice = C / NW;                                // channels per wave
     const int KS = C / 32;                                   // K-steps per token
-    const int nsrc = a_in < 0 ? F : F - 1;                   // source frames of the clip (>= 1 here)
+    const int nsrc = (SPEC == 1 || a_in < 0) ? F : F - 1;    // frames walked per clip (>= 1 here)
 
-    // source frame of slot f: the f-th source frame of this group, the last one repeated past the end
-    const uint16_t* sp[NS];                                  // load order: lane -> token lane/4, chunk lane%4
+    // source frame of slot f: the f-th walked frame of this group, the last one repeated past the end.
+    // Loads go through buffer descriptors: one per-lane byte offset shared by every tile (load order:
+    // lane -> token lane/4, 16-byte chunk lane%4) plus a wave-uniform offset per tile in scalar
+    // registers, instead of a 64-bit address per tile in vector registers.  The source descriptor
+    // starts at the group's first frame and ends with the clip; reads past its end would return zero.
+    const int k_first = min(grp * FR, nsrc - 1) + (min(grp * FR, nsrc - 1) >= a_skip ? 1 : 0);
+    const size_t frame_elems = (size_t)N * C;
+    const size_t src_bytes = (size_t)(F - k_first) * frame_elems * 2;
+    const BufferRsrc src_rs = make_rsrc(x + ((size_t)b * F + k_first) * frame_elems,
+                                        src_bytes > 0xffffffffull ? 0xffffffffu : (unsigned)src_bytes);
+    unsigned sp[NS];                                         // byte offset of tile s from the descriptor base
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
         const int si = min(grp * FR + s / 2, nsrc - 1);
-        const int k = si + (si >= a ? 1 : 0);
-        sp[s] = x + (((size_t)b * F + k) * N + i0 + 16 * (s % 2) + (lane >> 2)) * (size_t)C +
-                wave * slice + (lane & 3) * 8;
+        const int k = si + (si >= a_skip ? 1 : 0);
+        sp[s] = (unsigned)((((size_t)(k - k_first) * N + i0 + 16 * (s % 2)) * (size_t)C + wave * slice) * 2);
     }
+    const unsigned lane_src = ((unsigned)(lane >> 2) * (unsigned)C + (unsigned)(lane & 3) * 8u) * 2u;
     const int bperm = (4 * m + g) * 4;                       // operand lane (token m, chunk g) <- load lane 4m+g
-    const uint16_t* ap[NA];
+    const BufferRsrc frag_rs = make_rsrc(anchor_frag + (size_t)b * frame_elems, (unsigned)(frame_elems * 2));
+    unsigned ap[NA];                                         // byte offset of anchor tile q's first fragment of this wave
     float ai_tile[NA];
 #pragma unroll
     for (int q = 0; q < NA; ++q) {
         const int yy = min(max(ylo + S::tile_row(q), 0), H - 1);      // rows outside the grid: clamped, masked later
         const int tile = yy * CT + S::tile_col(q);
-        ap[q] = anchor_frag + (((size_t)b * (N / 16) + tile) * KS + wave * (slice / 32)) * 512 + lane * 8;
+        ap[q] = (unsigned)(((size_t)tile * KS + wave * (slice / 32)) * 1024);
         ai_tile[q] = anchor_inv[(size_t)b * N + 16 * tile + m];       // requested now, used in the epilogue
     }
+    const unsigned lane_frag = (unsigned)lane * 16u;
 
     f32x4 acc[NS][NPS];
     float nv[NS];
@@ -295,6 +342,15 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
         nv[s] = 0.f;
 #pragma unroll
         for (int q = 0; q < NPS; ++q) acc[s][q] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    // speculative pass: the channel pickers, and where this lane's strip sums go (lanes 0..31 hold the
+    // 32 channels of a K-step after the reduction)
+    bf16x8 pick0, pick1;
+    float* sums = nullptr;
+    if constexpr (SPEC == 1) {
+        pick0 = channel_picker(0, lane);
+        pick1 = channel_picker(1, lane);
+        sums = strip_sum + ((((size_t)b * F + (size_t)grp * FR) * tpf + tp) * (size_t)C) + wave * slice + (lane & 31);
     }
 
     for (int pass = 0; pass < passes; ++pass) {
@@ -305,13 +361,14 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
 #pragma unroll
         for (int d = 0; d < PF && d < KSW; ++d) {
 #pragma unroll
-            for (int q = 0; q < NA; ++q) Bt[d][q] = load_frag(ap[q] + (size_t)(ks0 + d) * 512);
+            for (int q = 0; q < NA; ++q)
+                Bt[d][q] = __builtin_bit_cast(bf16x8, buffer_load16(frag_rs, lane_frag, ap[q] + (ks0 + d) * 1024));
         }
-        uint4 A[NS][KSW];
+        u32x4 A[NS][KSW];
 #pragma unroll
         for (int ks = 0; ks < KSW; ++ks) {
 #pragma unroll
-            for (int s = 0; s < NS; ++s) A[s][ks] = *reinterpret_cast<const uint4*>(sp[s] + (ks0 + ks) * 32);
+            for (int s = 0; s < NS; ++s) A[s][ks] = buffer_load16(src_rs, lane_src, sp[s] + (ks0 + ks) * 64);
         }
         // every source load of the pass is issued before any product (the scheduler would
         // otherwise sink them to their uses and serialise on HBM latency)
@@ -320,14 +377,17 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
         for (int ks = 0; ks < KSW; ++ks) {
             if (ks + PF < KSW) {
 #pragma unroll
-                for (int q = 0; q < NA; ++q) Bt[(ks + PF) % NB][q] = load_frag(ap[q] + (size_t)(ks0 + ks + PF) * 512);
+                for (int q = 0; q < NA; ++q)
+                    Bt[(ks + PF) % NB][q] = __builtin_bit_cast(
+                        bf16x8, buffer_load16(frag_rs, lane_frag, ap[q] + (ks0 + ks + PF) * 1024));
             }
             __builtin_amdgcn_sched_barrier(0);
+            f32x4 d0, d1;                                    // SPEC 1: tokens x channels of the current strip
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
                 // (fragments are kept as four plain 32-bit words: v_dot2 on elements extracted from
                 // a bit-cast vector was observed to read element 0 four times)
-                uint32_t r[4] = {A[s][ks].x, A[s][ks].y, A[s][ks].z, A[s][ks].w};
+                uint32_t r[4] = {A[s][ks][0], A[s][ks][1], A[s][ks][2], A[s][ks][3]};
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const bf16x2 p = __builtin_bit_cast(bf16x2, r[e]);
@@ -340,6 +400,26 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
                 for (int q = 0; q < NPS; ++q)
                     acc[s][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, Bt[ks % NB][S::pair_tile(s % 2, q)],
                                                                         acc[s][q], 0, 0, 0);
+                if constexpr (SPEC == 1) {
+                    if (s % 2 == 0) {
+                        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                        d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pick0, zero, 0, 0, 0);
+                        d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pick1, zero, 0, 0, 0);
+                    } else {
+                        d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pick0, d0, 0, 0, 0);
+                        d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pick1, d1, 0, 0, 0);
+                        // lane n + 16g: tokens 4g..4g+3 (both tiles) of channel n (d0) and 16 + n (d1)
+                        const float t0 = (d0[0] + d0[1]) + (d0[2] + d0[3]);
+                        const float t1 = (d1[0] + d1[1]) + (d1[2] + d1[3]);
+                        // rows g = 0, 2 collect channel n, rows 1, 3 channel 16 + n; then rows 0+2, 1+3
+                        float mine = (g & 1) ? t1 : t0;
+                        const float theirs = (g & 1) ? t0 : t1;
+                        mine += __shfl_xor(theirs, 16, 64);
+                        mine += __shfl_xor(mine, 32, 64);
+                        if (lane < 32 && grp * FR + s / 2 < F)
+                            sums[(size_t)(s / 2) * tpf * C + (ks0 + ks) * 32] = mine;
+                    }
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -351,6 +431,12 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
         nv[s] += __shfl_xor(nv[s], 1, 64);
         nv[s] += __shfl_xor(nv[s], 2, 64);
     }
+    // a slot is live when it is a real frame of the clip whose outputs this search owns (in the
+    // speculative pass the anchor frame is walked for its sums only)
+    auto slot_live = [&](int s) {
+        const int si = grp * FR + s / 2;
+        return si < nsrc && (SPEC != 1 || si != a_in);
+    };
     if constexpr (NW == 1) {
         // one wave owns the whole channel axis: its sums are final, the epilogue needs no LDS
 #pragma unroll
@@ -358,8 +444,8 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
             float nn[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) nn[j] = __shfl(nv[s], 4 * (4 * g + j), 64);
-            finish_tile<CT, RAD, ALL>(acc[s], nn, s, grp * FR + s / 2 < nsrc, min(grp * FR + s / 2, nsrc - 1),
-                                      a, b, F, H, i0, t, ai_tile, fuse_map, best_sim, best_idx, keep16, win_sim, lane);
+            finish_tile<CT, RAD, ALL>(acc[s], nn, s, slot_live(s), min(grp * FR + s / 2, nsrc - 1),
+                                      a_skip, b, F, H, i0, t, ai_tile, fuse_map, best_sim, best_idx, keep16, win_sim, lane);
         }
     } else {
         // ---- add the channel slices through LDS (wave order), RT source tiles per round ----
@@ -397,8 +483,8 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
                         v[q][0] += p[0]; v[q][1] += p[1]; v[q][2] += p[2]; v[q][3] += p[3];
                     }
                 }
-                finish_tile<CT, RAD, ALL>(v, nn, s, grp * FR + s / 2 < nsrc, min(grp * FR + s / 2, nsrc - 1),
-                                          a, b, F, H, i0, t, ai_tile, fuse_map, best_sim, best_idx, keep16, win_sim,
+                finish_tile<CT, RAD, ALL>(v, nn, s, slot_live(s), min(grp * FR + s / 2, nsrc - 1),
+                                          a_skip, b, F, H, i0, t, ai_tile, fuse_map, best_sim, best_idx, keep16, win_sim,
                                           lane);
             }
             __syncthreads();
@@ -618,13 +704,29 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
     }
 }
 
+// True when launch_shape<CT, RAD> runs k_search_mfma (and not the LDS-shared kernel) on this
+// problem: the kernel that can also write strip sums.
+template <int CT, int RAD>
+bool shape_uses_plain_kernel(const ttf_params& p, int nsrc)
+{
+    using S = Shape<CT, RAD>;
+    if constexpr (S::NPS > 6) {
+        const int groups8 = (nsrc + 3) / 4;
+        const size_t wgs = (size_t)p.B * groups8 * (p.H * p.W / 32);
+        if (wgs >= 2 * 256 && (p.C / 32) % 2 == 0) return false;
+    }
+    return true;
+}
+
+// spec_mode 0: plain search.  1: speculative pass (every frame walked, strip sums written).  2: plain
+// search restricted to the clips marked for a second search.
 template <int CT, int RAD>
 hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,
                         const int32_t* anchor_index, int32_t* fuse_map, float* best_sim, int32_t* best_idx,
-                        float* win_sim, hipStream_t s)
+                        float* win_sim, int spec_mode, hipStream_t s)
 {
     using S = Shape<CT, RAD>;
-    const int nsrc = external_anchor ? p.F : p.F - 1;        // source frames per clip
+    const int nsrc = (external_anchor || spec_mode == 1) ? p.F : p.F - 1;   // frames walked per clip
     if (nsrc < 1) return hipSuccess;                         // no source frame: the anchor rows are all there is
     const uint16_t* xs = static_cast<const uint16_t*>(x);
     const int N = p.H * p.W;
@@ -633,6 +735,25 @@ hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor
     const unsigned grid = (unsigned)blocks;
     const int ks_total = p.C / 32;                           // K-steps per token
     uint16_t* keep16 = reinterpret_cast<uint16_t*>(w.keep_bits);
+    if (spec_mode != 0) {
+        // the speculative path is for large inputs: the two layouts that serve those, nothing else
+        if (win_sim || !shape_uses_plain_kernel<CT, RAD>(p, p.F - 1)) return hipErrorInvalidValue;
+#define TTF_LAUNCH_SPEC(KSW, NW, SPEC)                                                                            \
+    k_search_mfma<CT, RAD, KSW, NW, false, 0, SPEC><<<grid, NW * 64, 0, s>>>(                                     \
+        xs, w.anchor_frag, anchor_index, w.anchor_inv, fuse_map, best_sim, best_idx, keep16, nullptr, p.F, p.H, p.C, \
+        p.t, ks_total / (NW * KSW), groups, w.spec, w.strip_sum)
+#define TTF_LAUNCH_SPEC_AS(KSW, NW)                        \
+    do {                                                   \
+        if (spec_mode == 1) TTF_LAUNCH_SPEC(KSW, NW, 1);   \
+        else TTF_LAUNCH_SPEC(KSW, NW, 2);                  \
+    } while (0)
+        if (blocks >= 3 * kSimds * S::OCC && ks_total % 2 == 0) TTF_LAUNCH_SPEC_AS(2, 1);
+        else if (ks_total % 8 == 0) TTF_LAUNCH_SPEC_AS(2, 4);
+        else TTF_LAUNCH_SPEC_AS(1, 4);
+#undef TTF_LAUNCH_SPEC_AS
+#undef TTF_LAUNCH_SPEC
+        return hipGetLastError();
+    }
     if constexpr (S::NPS > 6) {
         // many anchor tiles per source tile (32-wide grid, 5x5 window): workgroups of 4 waves x 1 frame
         // sharing the anchor fragments in LDS, as soon as there are enough of them to cover the chip
@@ -660,7 +781,8 @@ hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor
 #define TTF_LAUNCH_AS(KSW, NW, ALL)                                                                           \
     k_search_mfma<CT, RAD, KSW, NW, ALL><<<grid, NW * 64, 0, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv,  \
                                                                   fuse_map, best_sim, best_idx, keep16, win_sim,  \
-                                                                  p.F, p.H, p.C, p.t, ks_total / (NW * KSW), groups)
+                                                                  p.F, p.H, p.C, p.t, ks_total / (NW * KSW), groups,  \
+                                                                  nullptr, nullptr)
 #define TTF_LAUNCH(KSW, NW)                   \
     do {                                      \
         if (win_sim) TTF_LAUNCH_AS(KSW, NW, true); \
@@ -678,11 +800,13 @@ hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor
         if (win_sim)
             k_search_mfma<CT, RAD, 8, 4, true, 1><<<grid1, 256, 0, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv,
                                                                         fuse_map, best_sim, best_idx, keep16, win_sim,
-                                                                        p.F, p.H, p.C, p.t, ks_total / 32, nsrc);
+                                                                        p.F, p.H, p.C, p.t, ks_total / 32, nsrc, nullptr,
+                                                                        nullptr);
         else
             k_search_mfma<CT, RAD, 8, 4, false, 1><<<grid1, 256, 0, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv,
                                                                          fuse_map, best_sim, best_idx, keep16, win_sim,
-                                                                         p.F, p.H, p.C, p.t, ks_total / 32, nsrc);
+                                                                         p.F, p.H, p.C, p.t, ks_total / 32, nsrc, nullptr,
+                                                                        nullptr);
     } else if (blocks >= 3 * kSimds * S::OCC && S::OCC == 1 && ks_total % 4 == 0) TTF_LAUNCH(4, 1);
     else if (blocks >= 3 * kSimds * S::OCC && ks_total % 2 == 0) TTF_LAUNCH(2, 1);
     else if (ks_total % 8 == 0) TTF_LAUNCH(2, 4);
@@ -774,11 +898,29 @@ bool mfma_search_padded(const ttf_params& p)
     return !mfma_search_supported(p);
 }
 
+// True when the speculative anchor path can run this problem's search: an aligned grid served by
+// k_search_mfma.
+bool mfma_search_speculative(const ttf_params& p)
+{
+    if (!mfma_search_supported(p) || !speculation_shape(p) || p.F < 2) return false;
+#define TTF_CASE(CT, RAD) \
+    if (p.W == 16 * CT && p.r == RAD) return shape_uses_plain_kernel<CT, RAD>(p, p.F - 1)
+    TTF_CASE(1, 0);
+    TTF_CASE(1, 1);
+    TTF_CASE(1, 2);
+    TTF_CASE(2, 0);
+    TTF_CASE(2, 1);
+    TTF_CASE(2, 2);
+#undef TTF_CASE
+    return false;
+}
+
 hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,
                                      const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
-                                     int32_t* best_idx, float* win_sim, hipStream_t s)
+                                     int32_t* best_idx, float* win_sim, int spec_mode, hipStream_t s)
 {
     if (mfma_search_padded(p)) {
+        if (spec_mode != 0) return hipErrorInvalidValue;
         const int ct = p.W <= 16 ? 1 : (p.W <= 32 ? 2 : 3);
 #define TTF_PCASE(CT, RAD)                              \
     if (ct == CT && p.r == RAD)                         \
@@ -797,7 +939,8 @@ hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool ex
     }
 #define TTF_CASE(CT, RAD)             \
     if (p.W == 16 * CT && p.r == RAD) \
-    return launch_shape<CT, RAD>(p, x, external_anchor, w, anchor_index, fuse_map, best_sim, best_idx, win_sim, s)
+    return launch_shape<CT, RAD>(p, x, external_anchor, w, anchor_index, fuse_map, best_sim, best_idx, win_sim, \
+                                 spec_mode, s)
     TTF_CASE(1, 0);
     TTF_CASE(1, 1);
     TTF_CASE(1, 2);

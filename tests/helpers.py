@@ -21,8 +21,16 @@ def rows_as_bits(t: torch.Tensor) -> np.ndarray:
     return t.view(torch.int32).cpu().numpy().view(np.uint32)
 
 
-def run_gpu(x_np, r, t, anchor="auto", want_sim=True):
+def run_gpu(x_np, r, t, anchor="auto", want_sim=True, speculation=None):
+    """speculation: None leaves the library's default; 1 / -1 force the speculative single-pass
+    anchor route wherever it exists / the two-pass route for this call."""
     import paper_2605_07355_amd as ttf
+    if speculation is not None:
+        ttf.ttf_set_speculation(speculation)
+        try:
+            return run_gpu(x_np, r, t, anchor, want_sim)
+        finally:
+            ttf.ttf_set_speculation(0)
     x = to_device(x_np)
     B, F, H, W, C = x.shape
     buf = ttf.TTFBuffers.allocate(B, F, H, W, C, x.dtype, x.device, want_sim=want_sim)
