@@ -270,10 +270,12 @@ int ttf_last_hip_error(void);
  *                 whose guessed best frame beats the runner-up by at least 0.1 in that cosine is
  *                 searched against the guess at once, the search adds up the exact sums of every
  *                 frame on the side, and the exact rule is evaluated from them afterwards: it
- *                 confirms the guess, or the clip's search is repeated against the exact anchor.
- *                 Clips without a clear guess take the two-pass route.  Outputs are those of the
+ *                 confirms the guess, or the clip is searched again against the exact anchor.
+ *                 A clip without a clear guess sits out the first search and takes the two-pass
+ *                 route together with the refuted clips.  Outputs are those of the
  *                 exact rule in every case; only the time differs (one pass over the input instead
- *                 of two when the guesses hold, up to one extra search when they do not).
+ *                 of two when the guesses hold, one extra search for a clip whose trusted guess
+ *                 was wrong).
  *                 Available for bf16 input on grids 16 or 32 wide with H*W % 64 == 0, C % 128 == 0,
  *                 C >= 1024, r <= 2, F >= 2, automatic anchor.
  * mode  0 (default): speculative for inputs of 256 MiB and more where available, else two-pass;
@@ -284,8 +286,8 @@ ttf_status ttf_set_speculation(int mode);
 
 /*
  * Per-stage timing, for benchmarks.  Stages, in launch order:
- *   0 frame sums (speculative route: the anchor guess, and exact sums of the clips without a clear
- *     guess)   1 anchor scores   2 anchor choice + norms   3 window search + gate
+ *   0 frame sums (speculative route: over the guess channels only)   1 anchor scores (two-pass
+ *     route only)   2 anchor choice + norms   3 window search + gate
  *   4 anchor verification (speculative route only: exact rule from the search's sums, repeated
  *     search of refuted clips)   5 offsets scan   6 row emission
  * ttf_profile_enable(slots), 1 <= slots <= TTF_PROFILE_MAX_SLOTS, makes every following

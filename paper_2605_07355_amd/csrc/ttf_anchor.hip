@@ -17,8 +17,8 @@ constexpr int kAnchorGiven = -2;   // "fixed_anchor" value: the anchor of every 
 
 // One block = one frame x one slice of 64*V channels.  Wave w adds rows w, w+4, ...; the four
 // partial sums are combined through LDS in wave order, so the result is order-stable.
-// `spec` (may be null): per clip {guessed anchor, guess trusted, ...}; clips whose guess is trusted
-// need no exact sums before the search and are skipped.
+// `spec` (may be null): per clip {guessed anchor, guess trusted, ...}; clips with a trusted guess get
+// their exact sums from the search and are skipped here.
 template <typename T, int V>
 __global__ __launch_bounds__(256) void k_frame_sums(const T* __restrict__ x, float* __restrict__ frame_sum,
                                                     int N, int C, int F, const int32_t* __restrict__ spec)
@@ -107,32 +107,21 @@ __global__ __launch_bounds__(256) void k_frame_sums_slab(const T* __restrict__ x
 // each of sixteen interleaved groups, groups added in order), then for every frame the slice's share
 // of <frame_sum_k, g> and |frame_sum_k|^2, and the slice's share of |g|^2.  The cosine of the
 // anchor rule is assembled from these shares by pick_anchor().
-// STRIPPED: a frame sum is not stored as such but as `strips` partial sums (one per 32-token strip,
-// written by the window search, [B,F,strips,C]); they are added in ascending strip order (fp32) as
-// they are loaded.  skip_mode 1: clips whose anchor guess is trusted are skipped; 2: only those
-// clips are done (spec[b] = {guessed anchor, guess trusted, ...}).
-template <bool STRIPPED>
-__global__ __launch_bounds__(1024) void k_anchor_partials(const float* __restrict__ frame_sum,
-                                                         double* __restrict__ score_part,
-                                                         double* __restrict__ clip_part, int F, int C, int S,
-                                                         int FG, int strips, const int32_t* __restrict__ spec,
-                                                         int skip_mode)
+// STRIPS: a frame sum is not stored as such but as `strips` partial sums (one per 32-token strip, as
+// the window search writes them: fs[k][strip][C]); they are added in ascending strip order (fp32)
+// as they are loaded.  UN: frames in flight per wave.
+template <int UN, bool STRIPS>
+__device__ __forceinline__ void anchor_partials_body(const float* __restrict__ fs, double* __restrict__ score_part,
+                                                     double* __restrict__ clip_part, size_t b, int slice, int fg,
+                                                     int F, int C, int S, int FG, int strips, double (*gsh)[256])
 {
     // Long clips: FG blocks share a (clip, slice); each forms the clip sum itself (frame sums come
     // from L2) and scores its own run of frames, so that few clips still fill the chip.
     constexpr int NWV = 16;                             // waves per block
-    constexpr int UN = STRIPPED ? 2 : 8;                // frames in flight per wave
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int fg = blockIdx.x % FG;
-    const int slice = (blockIdx.x / FG) % S;
-    const size_t b = blockIdx.x / FG / S;
-    if (skip_mode == 1 && spec[4 * b + 1]) return;
-    if (skip_mode == 2 && !spec[4 * b + 1]) return;
     const int per = (F + FG - 1) / FG;                  // frames scored by one block
     const int k_lo = fg * per, k_hi = min(F, k_lo + per);
-    const size_t fstride = STRIPPED ? (size_t)strips * C : (size_t)C;   // floats between consecutive frames
-    const float* fs = frame_sum + b * (size_t)F * fstride;
-    __shared__ double gsh[NWV][256];
+    const size_t fstride = STRIPS ? (size_t)strips * C : (size_t)C;   // floats between consecutive frames
     int c[4];
     bool ok[4];
 #pragma unroll
@@ -143,7 +132,7 @@ __global__ __launch_bounds__(1024) void k_anchor_partials(const float* __restric
     // this lane's four channels of one frame sum: one 16-byte load when the row allows it
     const bool vec = (C % 4 == 0) && ok[3];
     auto load4 = [&](const float* row, float* out) {
-        if constexpr (STRIPPED) {                      // (C % 128 == 0 on this path: always 16-byte loads)
+        if constexpr (STRIPS) {                        // (C % 128 == 0 on this path: always 16-byte loads)
             if (!ok[3]) return;                        // the last slice may reach beyond C
             for (int s0 = 0; s0 < strips; s0 += 8) {
                 float4 q[8];
@@ -227,6 +216,27 @@ __global__ __launch_bounds__(1024) void k_anchor_partials(const float* __restric
     }
 }
 
+// MIXED: clips with a trusted anchor guess (spec[b][1]) have their frame sums as strip sums
+// (strip_sum [B,F,strips,C]), the other clips in frame_sum [B,F,C]; otherwise every clip in frame_sum.
+template <bool MIXED>
+__global__ __launch_bounds__(1024) void k_anchor_partials(const float* __restrict__ frame_sum,
+                                                         double* __restrict__ score_part,
+                                                         double* __restrict__ clip_part, int F, int C, int S,
+                                                         int FG, int strips, const float* __restrict__ strip_sum,
+                                                         const int32_t* __restrict__ spec)
+{
+    const int fg = blockIdx.x % FG;
+    const int slice = (blockIdx.x / FG) % S;
+    const size_t b = blockIdx.x / FG / S;
+    __shared__ double gsh[16][256];
+    if (MIXED && spec[4 * b + 1] != 0)                   // block-uniform
+        anchor_partials_body<2, true>(strip_sum + b * (size_t)F * strips * C, score_part, clip_part, b, slice, fg, F,
+                                      C, S, FG, strips, gsh);
+    else
+        anchor_partials_body<8, false>(frame_sum + b * (size_t)F * C, score_part, clip_part, b, slice, fg, F, C, S, FG,
+                                       1, gsh);
+}
+
 // Anchor guess, step 1 (bf16 rows): sums over the N tokens of a frame of the kGuessChannels guess
 // channels only (kGuessSegments runs of 128 bytes per token row).  One block per frame: thread t
 // reads 16-byte piece t%32 of the guess channels of tokens t/32, t/32 + 8, ...; the eight token
@@ -247,7 +257,7 @@ __global__ __launch_bounds__(256) void k_guess_sums(const uint16_t* __restrict__
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int i = i0 + 8 * u;
-            if (i < N) r[u].template load<false>(reinterpret_cast<const bf16_t*>(base + (size_t)i * C));
+            if (i < N) r[u].template load<true>(reinterpret_cast<const bf16_t*>(base + (size_t)i * C));
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -268,25 +278,38 @@ __global__ __launch_bounds__(256) void k_guess_sums(const uint16_t* __restrict__
 }
 
 // Anchor guess, step 2: the anchor rule evaluated on the guess channels alone (fp64 from the fp32
-// sums of step 1).  One block per clip.  The guess is trusted when its score beats the runner-up's by
-// at least kGuessMinGap and no score is NaN; the search then runs against it before the exact rule
-// has been evaluated, and the exact rule (from sums the search produces on the side) confirms it or
-// triggers a second search.  spec[b] = {guessed frame (lowest k on ties), trusted, 0, 0}.
+// sums of step 1), by all NWV waves of a block together (every thread must call it; it synchronises
+// the block).  The guess is trusted when its score beats the runner-up's by at least kGuessMinGap and
+// no score is NaN; the search then runs against it before the exact rule has been evaluated, and the
+// exact rule (from sums the search produces on the side) confirms it or triggers a second search.
+// Returns the guessed frame (lowest k on ties) and whether it is trusted, to every thread.
 constexpr double kGuessMinGap = 0.1;
-__global__ __launch_bounds__(1024) void k_guess_pick(const float* __restrict__ guess_sum, int32_t* __restrict__ spec,
-                                                    int F)
+template <int NWV>
+__device__ __forceinline__ void guess_pick_block(const float* __restrict__ guess_sum, int b, int F, int& guess,
+                                                 bool& trusted)
 {
-    constexpr int NWV = 16;
+    constexpr int UN = 8;                               // frames in flight per wave
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const size_t b = blockIdx.x;
-    const float* gs = guess_sum + b * (size_t)F * kGuessChannels + lane * 4;
+    const float* gs = guess_sum + (size_t)b * F * kGuessChannels + lane * 4;
     __shared__ double gsh[NWV][kGuessChannels];
     __shared__ double s_best[NWV], s_second[NWV];
     __shared__ int s_arg[NWV], s_nan[NWV];
+    __shared__ int s_out[2];
+    // clips of up to NWV*UN frames: every wave's frames stay in its registers for the second pass
+    const bool resident = F <= NWV * UN;
+    float4 v[UN];
     double gp[4] = {0.0, 0.0, 0.0, 0.0};
-    for (int k = wave; k < F; k += NWV) {
-        const float4 q = *reinterpret_cast<const float4*>(gs + (size_t)k * kGuessChannels);
-        gp[0] += (double)q.x; gp[1] += (double)q.y; gp[2] += (double)q.z; gp[3] += (double)q.w;
+    for (int k0 = wave; k0 < F; k0 += NWV * UN) {
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int k = k0 + NWV * u;
+            v[u] = float4{0.f, 0.f, 0.f, 0.f};
+            if (k < F) v[u] = *reinterpret_cast<const float4*>(gs + (size_t)k * kGuessChannels);
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            gp[0] += (double)v[u].x; gp[1] += (double)v[u].y; gp[2] += (double)v[u].z; gp[3] += (double)v[u].w;
+        }
     }
 #pragma unroll
     for (int e = 0; e < 4; ++e) gsh[wave][lane * 4 + e] = gp[e];
@@ -303,19 +326,32 @@ __global__ __launch_bounds__(1024) void k_guess_pick(const float* __restrict__ g
     vv = wave_sum(vv);
     double best = -1.0e300, second = -1.0e300;          // wave-uniform running top two of this wave's frames
     int arg = 0x7fffffff, nan = 0;
-    for (int k = wave; k < F; k += NWV) {               // ascending k: strict > keeps the lowest on ties
-        const float4 q = *reinterpret_cast<const float4*>(gs + (size_t)k * kGuessChannels);
-        const double xv[4] = {(double)q.x, (double)q.y, (double)q.z, (double)q.w};
-        double uv = 0.0, uu = 0.0;
+    for (int k0 = wave; k0 < F; k0 += NWV * UN) {       // ascending k per wave: strict > keeps the lowest on ties
+        if (!resident) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { uv += xv[e] * g[e]; uu += xv[e] * xv[e]; }
-        uv = wave_sum(uv);
-        uu = wave_sum(uu);
-        const double den = sqrt(uu) * sqrt(vv);
-        const double score = den > 0.0 ? uv / den : 0.0;
-        if (!(score == score)) nan = 1;
-        if (score > best) { second = best; best = score; arg = k; }
-        else if (score > second) second = score;
+            for (int u = 0; u < UN; ++u) {
+                const int k = k0 + NWV * u;
+                v[u] = float4{0.f, 0.f, 0.f, 0.f};
+                if (k < F) v[u] = *reinterpret_cast<const float4*>(gs + (size_t)k * kGuessChannels);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int k = k0 + NWV * u;
+            const double xv[4] = {(double)v[u].x, (double)v[u].y, (double)v[u].z, (double)v[u].w};
+            double uv = 0.0, uu = 0.0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { uv += xv[e] * g[e]; uu += xv[e] * xv[e]; }
+            uv = wave_sum(uv);
+            uu = wave_sum(uu);
+            const double den = sqrt(uu) * sqrt(vv);
+            const double score = den > 0.0 ? uv / den : 0.0;
+            if (k < F) {                                // wave-uniform
+                if (!(score == score)) nan = 1;
+                if (score > best) { second = best; best = score; arg = k; }
+                else if (score > second) second = score;
+            }
+        }
     }
     if (lane == 0) { s_best[wave] = best; s_second[wave] = second; s_arg[wave] = arg; s_nan[wave] = nan; }
     __syncthreads();
@@ -333,12 +369,12 @@ __global__ __launch_bounds__(1024) void k_guess_pick(const float* __restrict__ g
             }
             sec = fmax(sec, s_second[w]);
         }
-        const bool trusted = !nn && aa != 0x7fffffff && (F == 1 || bb - sec >= kGuessMinGap);
-        spec[4 * b + 0] = aa == 0x7fffffff ? 0 : aa;
-        spec[4 * b + 1] = trusted ? 1 : 0;
-        spec[4 * b + 2] = 0;
-        spec[4 * b + 3] = 0;
+        s_out[0] = aa == 0x7fffffff ? 0 : aa;
+        s_out[1] = (!nn && aa != 0x7fffffff && (F == 1 || bb - sec >= kGuessMinGap)) ? 1 : 0;
     }
+    __syncthreads();
+    guess = s_out[0];
+    trusted = s_out[1] != 0;
 }
 
 // Arg max over k of cos(frame_sum_k, clip_sum), assembled in fp64 from the per-slice shares
@@ -486,7 +522,8 @@ __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restri
                                                         int32_t* __restrict__ fuse_map, float* __restrict__ best_sim,
                                                         int32_t* __restrict__ best_idx, uint16_t* __restrict__ keep16,
                                                         int F, int N, int C, int S, int fixed_anchor, int tiles,
-                                                        int Wg, int CT, int32_t* __restrict__ spec, int spec_mode)
+                                                        int Wg, int CT, int32_t* __restrict__ spec, int spec_mode,
+                                                        const float* __restrict__ guess_sum)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int b = blockIdx.x / tiles, tile = blockIdx.x % tiles;
@@ -499,15 +536,23 @@ __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restri
           : fixed_anchor == kAnchorGiven ? anchor_index[b]
                                          : pick_anchor(score_part, clip_part, b, F, S, lane);
     } else if (spec_mode == 1) {
-        // speculative pass: a trusted guess stands in for the anchor rule until the search has produced
-        // exact frame sums; clips without one had their exact scores computed beforehand
-        a = spec[4 * b + 1] ? spec[4 * b] : pick_anchor(score_part, clip_part, b, F, S, lane);
+        // speculative pass: the guess (anchor rule on a few channels), evaluated by every block of the
+        // clip for itself.  A trusted guess stands in for the anchor until the search has produced exact
+        // frame sums; a clip without one is only summed by the coming search, so nothing is prepared.
+        bool trusted;
+        guess_pick_block<8>(guess_sum, b, F, a, trusted);
+        if (tile == 0 && threadIdx.x == 0) {
+            spec[4 * b + 0] = a;
+            spec[4 * b + 1] = trusted ? 1 : 0;
+            spec[4 * b + 2] = 0;
+            spec[4 * b + 3] = 0;
+        }
+        if (!trusted) return;
     } else {
-        // after the search: the exact rule for the clips that ran on a guess.  Confirmed: nothing to do.
-        // Refuted: publish the exact anchor, mark the clip for a second search and prepare its anchor.
-        if (!spec[4 * b + 1]) return;
+        // after the search: the exact rule.  A trusted guess it confirms: nothing to do.  Otherwise
+        // publish the exact anchor, mark the clip for the second search and prepare its anchor.
         a = pick_anchor(score_part, clip_part, b, F, S, lane);
-        const bool redo = a != spec[4 * b];
+        const bool redo = !spec[4 * b + 1] || a != spec[4 * b];
         if (tile == 0 && threadIdx.x == 0) spec[4 * b + 2] = redo ? 1 : 0;
         if (!redo) return;
     }
@@ -600,31 +645,28 @@ hipError_t launch_frame_sums(const ttf_params& p, const void* x, const Workspace
     });
 }
 
-// mode 0: every clip, from the frame sums; 1: the same, skipping clips whose anchor guess is trusted;
-// 2: only those clips, from the strip sums the search wrote.
-hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, int mode, hipStream_t s)
+// mixed: clips with a trusted anchor guess take their frame sums from the strip sums the search wrote
+// (w.strip_sum), the others from w.frame_sum; otherwise every clip from w.frame_sum.
+hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, bool mixed, hipStream_t s)
 {
     const int S = (p.C + 255) / 256;
     // runs of at least 32 frames, and no more blocks than fill the chip a few times
     int FG = 1;
     while (FG < 16 && (size_t)S * p.B * FG < 512 && p.F >= 64 * FG) FG *= 2;
     const unsigned grid = (unsigned)((size_t)S * p.B * FG);
-    if (mode == 2)
-        k_anchor_partials<true><<<grid, 1024, 0, s>>>(w.strip_sum, w.score_part, w.clip_part, p.F, p.C, S, FG,
-                                                      p.H * p.W / 32, w.spec, 2);
+    if (mixed)
+        k_anchor_partials<true><<<grid, 1024, 0, s>>>(w.frame_sum, w.score_part, w.clip_part, p.F, p.C, S, FG,
+                                                      p.H * p.W / 32, w.strip_sum, w.spec);
     else
         k_anchor_partials<false><<<grid, 1024, 0, s>>>(w.frame_sum, w.score_part, w.clip_part, p.F, p.C, S, FG, 1,
-                                                       w.spec, mode);
+                                                       nullptr, nullptr);
     return hipGetLastError();
 }
 
-// The anchor rule on the guess channels: spec[b] = {guessed frame, trusted, 0, 0} for every clip.
-hipError_t launch_anchor_guess(const ttf_params& p, const void* x, const Workspace& w, hipStream_t s)
+// Frame sums over the guess channels only (w.guess_sum), from which the anchor is guessed.
+hipError_t launch_guess_sums(const ttf_params& p, const void* x, const Workspace& w, hipStream_t s)
 {
     k_guess_sums<<<(unsigned)(p.B * p.F), 256, 0, s>>>(static_cast<const uint16_t*>(x), w.guess_sum, p.H * p.W, p.C);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    k_guess_pick<<<(unsigned)p.B, 1024, 0, s>>>(w.guess_sum, w.spec, p.F);
     return hipGetLastError();
 }
 
@@ -673,7 +715,7 @@ hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const 
                                                        w.clip_part, anchor_index, w.anchor_inv, w.anchor_frag, fuse_map,
                                                        best_sim, best_idx, reinterpret_cast<uint16_t*>(w.keep_bits),
                                                        p.F, N, p.C, (p.C + 255) / 256, fixed, tiles, p.W, CT,
-                                                       spec_mode ? w.spec : nullptr, spec_mode);
+                                                       spec_mode ? w.spec : nullptr, spec_mode, w.guess_sum);
         return hipGetLastError();
     };
     return pad ? go(k_anchor_prepare<true>) : go(k_anchor_prepare<false>);

@@ -139,18 +139,19 @@ static ttf_status run_pass(const ttf_params* params, const void* features, const
     // clearly the search runs against it at once and adds up, on the side, the exact sums of every
     // 32-token strip it reads.  The exact rule is then evaluated from those sums: it confirms the
     // guess (the usual case: nothing else to do) or refutes it, and then the clip's anchor is prepared
-    // again and its search repeated.  Clips whose guess is not clear-cut take the two-pass route.
-    // Either way every output is what the exact rule gives.
+    // again and its search repeated.  A clip whose guess is not clear-cut sits out the first search; its
+    // frame sums are then formed the two-pass way and it is searched with the refuted clips.  Either way
+    // every output is what the exact rule gives.
     const int spec_pref = g_speculation.load(std::memory_order_relaxed);
     const unsigned long long in_bytes = (unsigned long long)p.B * p.F * p.H * p.W * p.C * 2ull;
     const bool spec = pick && use_mfma_path(p) && mfma_search_speculative(p) &&
                       (spec_pref > 0 || (spec_pref == 0 && in_bytes >= kSpeculationMinBytes));
 
     mark();                                                    // start of stage 0
-    if (spec) TTF_STEP(launch_anchor_guess(p, features, w, s));
-    if (pick) TTF_STEP(launch_frame_sums(p, features, w, spec, s));
+    if (spec) TTF_STEP(launch_guess_sums(p, features, w, s));
+    else if (pick) TTF_STEP(launch_frame_sums(p, features, w, false, s));
     mark();
-    if (pick) TTF_STEP(launch_anchor_scores(p, w, spec ? 1 : 0, s));
+    if (pick && !spec) TTF_STEP(launch_anchor_scores(p, w, false, s));
     mark();
     if (use_mfma_path(p))
         TTF_STEP(launch_anchor_prepare_mfma(p, features, ext_anchor, w, out->anchor_index, out->fuse_map,
@@ -165,7 +166,8 @@ static ttf_status run_pass(const ttf_params* params, const void* features, const
                                       out->best_idx, nullptr, s));
     mark();
     if (spec) {
-        TTF_STEP(launch_anchor_scores(p, w, 2, s));
+        TTF_STEP(launch_frame_sums(p, features, w, true, s));     // clips without a trusted guess only
+        TTF_STEP(launch_anchor_scores(p, w, true, s));
         TTF_STEP(launch_anchor_prepare_mfma(p, features, nullptr, w, out->anchor_index, out->fuse_map,
                                             out->best_sim, out->best_idx, false, 2, s));
         TTF_STEP(launch_window_search_mfma(p, features, false, w, out->anchor_index, out->fuse_map, out->best_sim,
@@ -283,7 +285,7 @@ ttf_status ttf_compress_tied(const ttf_params* params, const void* features, voi
     } while (0)
     if (p.anchor_mode == TTF_ANCHOR_AUTO) {
         TTF_STEP(launch_frame_sums(p, features, w, false, s));
-        TTF_STEP(launch_anchor_scores(p, w, 0, s));
+        TTF_STEP(launch_anchor_scores(p, w, false, s));
     }
     TTF_STEP(launch_tied_anchor(p, w, out->anchor_index, s));
     if (use_mfma_path(p))

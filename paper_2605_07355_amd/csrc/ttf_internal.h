@@ -27,7 +27,7 @@ struct Workspace {
     int32_t*  src_row;       // [B*F*N]  input token (flat over clips and frames) that output row r copies
     // Speculative anchor (single pass over the input, see ttf_api.hip); sized 0 where it cannot apply
     float*    guess_sum;     // [B,F,kGuessChannels] frame sums over the guess channels only
-    int32_t*  spec;          // [B,4]    guessed anchor, guess trusted (1/0), search to be redone (1/0), unused
+    int32_t*  spec;          // [B,4]    guessed anchor, guess trusted (1/0), second search needed (1/0), unused
     float*    strip_sum;     // [B,F,N/32,C] sum of every 32-token strip of every frame, written by the search
     size_t    bytes;
 };
@@ -87,13 +87,13 @@ inline Workspace carve(const ttf_params& p, void* base)
 }
 
 // Stage launchers.  Each enqueues on `s` and returns the launch status.
-// `skip_trusted`: clips whose anchor guess is trusted (w.spec) are left out.
+// `skip_trusted`: clips with a trusted anchor guess (w.spec) are left out.
 hipError_t launch_frame_sums(const ttf_params& p, const void* x, const Workspace& w, bool skip_trusted, hipStream_t s);
-// mode 0: every clip, from w.frame_sum; 1: the same without the clips whose guess is trusted; 2: only
-// those clips, from w.strip_sum.
-hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, int mode, hipStream_t s);
-// The anchor rule evaluated on a few channels only: w.spec[b] = {guessed frame, trusted, 0, 0}.
-hipError_t launch_anchor_guess(const ttf_params& p, const void* x, const Workspace& w, hipStream_t s);
+// Per-slice shares of the anchor scores from w.frame_sum; `mixed`: from w.strip_sum for the clips with a
+// trusted anchor guess.
+hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, bool mixed, hipStream_t s);
+// Frame sums over the guess channels only (w.guess_sum).
+hipError_t launch_guess_sums(const ttf_params& p, const void* x, const Workspace& w, hipStream_t s);
 // `ext_anchor` (here and below): nullptr when the anchor is a frame of x; otherwise the anchor
 // frames [B,N,C] of a segment, in which case anchor_index is written as -1 and every frame of x
 // is a source frame.
@@ -103,6 +103,11 @@ hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const void* e
                                int32_t* anchor_index, bool anchor_given, hipStream_t s);
 // Matrix-core path: anchor choice, inverse norms, the anchor frame re-laid in fragment order, and
 // the anchor-frame rows of fuse_map / best_sim / best_idx / keep bits.
+// spec_mode 0: the plain rule (fixed, given, or the arg max of the exact scores).  1: speculative pass --
+// the anchor is guessed from w.guess_sum; w.spec[b] = {guess, trusted, 0, 0} is written and only clips
+// with a trusted guess are prepared.  2: after the speculative search -- the exact rule from the
+// scores; clips whose guess it confirms are left alone, the others are marked in w.spec[b][2],
+// get the exact anchor published and prepared.
 hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                       int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                       int32_t* best_idx, bool anchor_given, int spec_mode, hipStream_t s);

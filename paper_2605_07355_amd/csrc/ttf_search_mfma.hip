@@ -96,18 +96,6 @@ __device__ __forceinline__ void row_argmax_step(float& best, int& arg)
     arg = take ? oa : arg;
 }
 
-// Buffer descriptor over `bytes` bytes at `base` (raw: no stride, byte offsets; reads beyond the
-// range return zero).  Loads through it take one 32-bit per-lane offset and one wave-uniform offset.
-typedef __amdgpu_buffer_rsrc_t BufferRsrc;
-__device__ __forceinline__ BufferRsrc make_rsrc(const void* base, unsigned bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
-}
-__device__ __forceinline__ u32x4 buffer_load16(BufferRsrc rs, unsigned lane_bytes, unsigned uniform_bytes)
-{
-    return __builtin_amdgcn_raw_buffer_load_b128(rs, (int)lane_bytes, (int)uniform_bytes, 0);
-}
-
 // Final step for one source tile (16 tokens of one frame): v[q] are the complete 16x16 products
 // with the NPS anchor tiles paired with it (MFMA result layout: lane = anchor column n + 16*g,
 // element j = source token 4g+j), nn[j] the squared norms of tokens 4g+j, ai_tile[a] this lane's
@@ -289,8 +277,11 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
         grp = (blockIdx.x / tpf) % groups;
         b = blockIdx.x / tpf / groups;
     }
+    if constexpr (SPEC == 1) {
+        if (spec[4 * b + 1] == 0) return;                    // no trusted guess: the clip takes the two-pass route
+    }
     if constexpr (SPEC == 2) {
-        if (spec[4 * b + 2] == 0) return;                    // guess confirmed (or never used): nothing to redo
+        if (spec[4 * b + 2] == 0) return;                    // guess confirmed: nothing to redo
     }
     const int a_in = anchor_index[b];                        // < 0: the anchor frame lies outside x (segment mode)
     // frame slot -> frame: the anchor frame is skipped, except in the speculative pass, which walks
@@ -309,31 +300,27 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
     // lane -> token lane/4, 16-byte chunk lane%4) plus a wave-uniform offset per tile in scalar
     // registers, instead of a 64-bit address per tile in vector registers.  The source descriptor
     // starts at the group's first frame and ends with the clip; reads past its end would return zero.
-    const int k_first = min(grp * FR, nsrc - 1) + (min(grp * FR, nsrc - 1) >= a_skip ? 1 : 0);
-    const size_t frame_elems = (size_t)N * C;
-    const size_t src_bytes = (size_t)(F - k_first) * frame_elems * 2;
-    const BufferRsrc src_rs = make_rsrc(x + ((size_t)b * F + k_first) * frame_elems,
-                                        src_bytes > 0xffffffffull ? 0xffffffffu : (unsigned)src_bytes);
-    unsigned sp[NS];                                         // byte offset of tile s from the descriptor base
+    // source frame of slot f: the f-th walked frame of this group, the last one repeated past the end
+    // (plain 64-bit addresses: the same loads through buffer descriptors, with one shared per-lane
+    // offset and scalar per-tile offsets, freed 22 registers but ran 10 % slower)
+    const uint16_t* sp[NS];                                  // load order: lane -> token lane/4, chunk lane%4
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
         const int si = min(grp * FR + s / 2, nsrc - 1);
         const int k = si + (si >= a_skip ? 1 : 0);
-        sp[s] = (unsigned)((((size_t)(k - k_first) * N + i0 + 16 * (s % 2)) * (size_t)C + wave * slice) * 2);
+        sp[s] = x + (((size_t)b * F + k) * N + i0 + 16 * (s % 2) + (lane >> 2)) * (size_t)C +
+                wave * slice + (lane & 3) * 8;
     }
-    const unsigned lane_src = ((unsigned)(lane >> 2) * (unsigned)C + (unsigned)(lane & 3) * 8u) * 2u;
     const int bperm = (4 * m + g) * 4;                       // operand lane (token m, chunk g) <- load lane 4m+g
-    const BufferRsrc frag_rs = make_rsrc(anchor_frag + (size_t)b * frame_elems, (unsigned)(frame_elems * 2));
-    unsigned ap[NA];                                         // byte offset of anchor tile q's first fragment of this wave
+    const uint16_t* ap[NA];
     float ai_tile[NA];
 #pragma unroll
     for (int q = 0; q < NA; ++q) {
         const int yy = min(max(ylo + S::tile_row(q), 0), H - 1);      // rows outside the grid: clamped, masked later
         const int tile = yy * CT + S::tile_col(q);
-        ap[q] = (unsigned)(((size_t)tile * KS + wave * (slice / 32)) * 1024);
+        ap[q] = anchor_frag + (((size_t)b * (N / 16) + tile) * KS + wave * (slice / 32)) * 512 + lane * 8;
         ai_tile[q] = anchor_inv[(size_t)b * N + 16 * tile + m];       // requested now, used in the epilogue
     }
-    const unsigned lane_frag = (unsigned)lane * 16u;
 
     f32x4 acc[NS][NPS];
     float nv[NS];
@@ -347,11 +334,47 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
     // 32 channels of a K-step after the reduction)
     bf16x8 pick0, pick1;
     float* sums = nullptr;
+    float held[FR];                                          // first K-step's totals until the second's are there
     if constexpr (SPEC == 1) {
+        static_assert(KSW <= 2, "strip sums are stored once per pass from the two halves of a wave");
         pick0 = channel_picker(0, lane);
         pick1 = channel_picker(1, lane);
-        sums = strip_sum + ((((size_t)b * F + (size_t)grp * FR) * tpf + tp) * (size_t)C) + wave * slice + (lane & 31);
+        sums = strip_sum + ((((size_t)b * F + (size_t)grp * FR) * tpf + tp) * (size_t)C) + wave * slice +
+               (KSW == 2 ? lane : (lane & 31));
     }
+
+    // One source tile's share of the strip sums (speculative pass).  Even tile of a frame: start the two
+    // token x channel accumulators; odd tile: add to them, finish the strip and store it.
+    //   lane n + 16g of d0 / d1: tokens 4g..4g+3 (both tiles) of channel n / 16 + n; four in-lane adds;
+    //   the four row groups are added by an fp32 MFMA against a matrix of ones (K = the row group), after
+    //   which every lane n + 16g holds the strip's total of its channel (rows 0, 2 keep channel n, rows
+    //   1, 3 channel 16 + n);
+    //   one 256-byte store per frame and pass: lanes 0..31 the first K-step's 32 channels, lanes 32..63
+    //   the second's.  A slot past the clip's end repeats the last frame and stores the same values to
+    //   the same place again.
+    f32x4 d0, d1;
+#define TTF_STRIP_SUM_STEP(av_, s_, ks_, ks0_)                                                                \
+    do {                                                                                                      \
+        const f32x4 zero_ = {0.f, 0.f, 0.f, 0.f};                                                             \
+        if ((s_) % 2 == 0) {                                                                                  \
+            d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av_, pick0, zero_, 0, 0, 0);                         \
+            d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av_, pick1, zero_, 0, 0, 0);                         \
+        } else {                                                                                              \
+            d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av_, pick0, d0, 0, 0, 0);                            \
+            d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av_, pick1, d1, 0, 0, 0);                            \
+            const float t0_ = (d0[0] + d0[1]) + (d0[2] + d0[3]);                                              \
+            const float t1_ = (d1[0] + d1[1]) + (d1[2] + d1[3]);                                              \
+            const f32x4 r0_ = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, t0_, zero_, 0, 0, 0);                \
+            const f32x4 r1_ = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, t1_, zero_, 0, 0, 0);                \
+            const float mine_ = (g & 1) ? r1_[0] : r0_[0];                                                    \
+            if (KSW == 1 || (ks_) == KSW - 1) {                                                               \
+                const float v_ = (KSW == 2 && lane < 32) ? held[(s_) / 2] : mine_;                            \
+                sums[(size_t)min((s_) / 2, F - 1 - grp * FR) * tpf * C + (ks0_) * 32] = v_;                   \
+            } else {                                                                                          \
+                held[(s_) / 2] = mine_;                                                                       \
+            }                                                                                                 \
+        }                                                                                                     \
+    } while (0)
 
     for (int pass = 0; pass < passes; ++pass) {
         const int ks0 = pass * KSW;
@@ -362,13 +385,13 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
         for (int d = 0; d < PF && d < KSW; ++d) {
 #pragma unroll
             for (int q = 0; q < NA; ++q)
-                Bt[d][q] = __builtin_bit_cast(bf16x8, buffer_load16(frag_rs, lane_frag, ap[q] + (ks0 + d) * 1024));
+                Bt[d][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(ap[q] + (size_t)(ks0 + d) * 512));
         }
         u32x4 A[NS][KSW];
 #pragma unroll
         for (int ks = 0; ks < KSW; ++ks) {
 #pragma unroll
-            for (int s = 0; s < NS; ++s) A[s][ks] = buffer_load16(src_rs, lane_src, sp[s] + (ks0 + ks) * 64);
+            for (int s = 0; s < NS; ++s) A[s][ks] = *reinterpret_cast<const u32x4*>(sp[s] + (ks0 + ks) * 32);
         }
         // every source load of the pass is issued before any product (the scheduler would
         // otherwise sink them to their uses and serialise on HBM latency)
@@ -378,11 +401,9 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
             if (ks + PF < KSW) {
 #pragma unroll
                 for (int q = 0; q < NA; ++q)
-                    Bt[(ks + PF) % NB][q] = __builtin_bit_cast(
-                        bf16x8, buffer_load16(frag_rs, lane_frag, ap[q] + (ks0 + ks + PF) * 1024));
+                    Bt[(ks + PF) % NB][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(ap[q] + (size_t)(ks0 + ks + PF) * 512));
             }
             __builtin_amdgcn_sched_barrier(0);
-            f32x4 d0, d1;                                    // SPEC 1: tokens x channels of the current strip
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
                 // (fragments are kept as four plain 32-bit words: v_dot2 on elements extracted from
@@ -400,30 +421,13 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
                 for (int q = 0; q < NPS; ++q)
                     acc[s][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, Bt[ks % NB][S::pair_tile(s % 2, q)],
                                                                         acc[s][q], 0, 0, 0);
-                if constexpr (SPEC == 1) {
-                    if (s % 2 == 0) {
-                        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-                        d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pick0, zero, 0, 0, 0);
-                        d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pick1, zero, 0, 0, 0);
-                    } else {
-                        d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pick0, d0, 0, 0, 0);
-                        d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pick1, d1, 0, 0, 0);
-                        // lane n + 16g: tokens 4g..4g+3 (both tiles) of channel n (d0) and 16 + n (d1)
-                        const float t0 = (d0[0] + d0[1]) + (d0[2] + d0[3]);
-                        const float t1 = (d1[0] + d1[1]) + (d1[2] + d1[3]);
-                        // rows g = 0, 2 collect channel n, rows 1, 3 channel 16 + n; then rows 0+2, 1+3
-                        float mine = (g & 1) ? t1 : t0;
-                        const float theirs = (g & 1) ? t0 : t1;
-                        mine += __shfl_xor(theirs, 16, 64);
-                        mine += __shfl_xor(mine, 32, 64);
-                        if (lane < 32 && grp * FR + s / 2 < F)
-                            sums[(size_t)(s / 2) * tpf * C + (ks0 + ks) * 32] = mine;
-                    }
-                }
+                if constexpr (SPEC == 1) TTF_STRIP_SUM_STEP(av, s, ks, ks0);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
     }
+
+#undef TTF_STRIP_SUM_STEP
 
     // squared-norm partials: lanes 4i..4i+3 hold the four chunks of token i
 #pragma unroll
