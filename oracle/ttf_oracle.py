@@ -23,14 +23,16 @@ ANCHOR_AUTO, ANCHOR_FIXED = 0, 1
 
 _lib: Optional[ctypes.CDLL] = None
 
+# code-generation flags of the oracle library (reported next to its timing)
+BUILD_FLAGS = ("-O2", "-std=c11", "-fopenmp", "-ffp-contract=off")
+
 
 def build(force: bool = True) -> str:
     """Compile the oracle.  Portable flags on purpose: the library is built on one machine
     and may run on another; no fast-math and no contraction, so every operation is the
     plain IEEE double one the source spells out."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
-               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        cmd = ["gcc", *BUILD_FLAGS, "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
