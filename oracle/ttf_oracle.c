@@ -19,7 +19,8 @@
  *     offset order stays and the others are masked; they have equal similarity and equal
  *     dst, so the choice cannot show in any output;
  *   - arg max ties (anchor frame, or distinct anchor tokens) go to the lowest index;
- *   - cos(u,v) is taken as 0 when either vector has zero norm;
+ *   - cos(u,v) is taken as 0 when either vector has zero norm, and only then: non-finite entries go
+ *     through the printed quotient as IEEE arithmetic takes them (a NaN cosine wins no comparison);
  *   - fused means s^ > t strictly (Eq. gating keeps s^ <= t); t is the float32 the caller
  *     passed, widened to double;
  *   - the frame mean in the anchor rule is over raw (un-normalised) tokens, as printed;
@@ -71,7 +72,7 @@ static double cosine_rows(const void *x, int dtype, size_t row_u, size_t row_v, 
         vv += v * v;
     }
     double den = sqrt(uu) * sqrt(vv);
-    return den > 0.0 ? uv / den : 0.0;
+    return den == 0.0 ? 0.0 : uv / den;
 }
 
 static double cosine_vec(const double *u, const double *v, int C)
@@ -83,7 +84,7 @@ static double cosine_vec(const double *u, const double *v, int C)
         vv += v[c] * v[c];
     }
     double den = sqrt(uu) * sqrt(vv);
-    return den > 0.0 ? uv / den : 0.0;
+    return den == 0.0 ? 0.0 : uv / den;
 }
 
 /* Integer projection onto [lo, hi]  (the clamp defined before the flat-index map). */

@@ -460,3 +460,23 @@ def test_random_small_problems_match_bruteforce(oracle, B, F, H, W, C, dtype, r,
     np.testing.assert_allclose(res.best_sim, ref["best_sim"], rtol=0, atol=1e-12)
     assert res.kept_count == len(ref["src_index"])
     np.testing.assert_array_equal(res.src_index[:res.kept_count], ref["src_index"])
+
+
+def test_nonfinite_entries_follow_ieee_arithmetic(oracle):
+    """The similarity is the printed quotient evaluated in IEEE arithmetic: a source token with a NaN
+    or infinite entry has a NaN cosine with every candidate, wins no comparison and is kept with
+    s^ = -inf, dst = -1; an anchor token with such an entry is simply never the arg max.  Only an
+    exactly zero norm gives cos = 0."""
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((1, 3, 4, 4, 16)).astype(np.float32)
+    x[0, 1, 1, 1, 3] = np.nan          # source token 5 of frame 1
+    x[0, 1, 2, 2, 0] = np.inf          # source token 10 of frame 1
+    x[0, 2, 0, 0, :] = 0.0             # zero source token 0 of frame 2
+    x[0, 0, 3, 3, 7] = -np.inf         # anchor token 15
+    res = oracle.compress(x, 1, -0.5, 1, 0, want_tokens=False)      # anchor fixed to frame 0
+    for i in (5, 10):
+        assert res.best_sim[0, 1, i] == -np.inf and res.best_idx[0, 1, i] == -1 and res.fuse_map[0, 1, i] == -1
+    assert res.best_sim[0, 2, 0] == 0.0 and res.fuse_map[0, 2, 0] >= 0          # cos = 0 > t = -0.5: fused
+    assert (res.best_idx[0, 1:] != 15).all()                                    # the infinite anchor token never wins
+    clean = np.delete(np.arange(16), [5, 10])
+    assert np.isfinite(res.best_sim[0, 1, clean]).all()
