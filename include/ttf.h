@@ -37,9 +37,13 @@
  *     failed launch or copy part-way through the sequence (outputs are then undefined).
  *   - Same inputs give bit-identical outputs on every call (no floating-point atomics, fixed
  *     reduction orders).
- *   - Input values are not scanned.  A NaN similarity compares false against "> t", so the
- *     token is kept.  Dot products and squared norms are accumulated in fp32: token rows whose
- *     squared norm overflows fp32 (entries around 1e17 and beyond) give NaN similarities.
+ *   - Input values are not scanned.  A candidate whose cosine is NaN (a NaN or infinite entry in
+ *     the source token or in that anchor token) wins no comparison.  A source token all of whose
+ *     candidates are like that is kept and reports best_sim = -inf, best_idx = -1, fuse_map = -1.
+ *     A NaN or infinite entry anywhere in a clip makes every anchor score NaN; the automatic
+ *     rule then picks frame 0.  Dot products and squared norms are accumulated in fp32: token rows
+ *     whose squared norm overflows fp32 (entries around 1e17 and beyond) behave like rows with
+ *     infinite entries.  Only an exactly zero norm gives cosine 0.
  */
 #ifndef TTF_H
 #define TTF_H
