@@ -5,7 +5,9 @@
 #include <cstdlib>
 #include <cstring>
 #include <atomic>
+#include <map>
 #include <mutex>
+#include <utility>
 
 #include "ttf_internal.h"
 
@@ -41,6 +43,21 @@ hipError_t launch_window_search(const ttf_params& p, const void* x, const void* 
         return launch_window_search_mfma(p, x, ext_anchor != nullptr, w, anchor_index, fuse_map, best_sim, best_idx,
                                          win_sim, 0, s);
     return launch_window_search_generic(p, x, ext_anchor, w, anchor_index, fuse_map, best_sim, best_idx, win_sim, s);
+}
+
+hipError_t allow_dynamic_lds(const void* kernel, size_t bytes)
+{
+    static std::mutex mutex;
+    static std::map<std::pair<const void*, int>, size_t> granted;   // (function, device) -> bytes allowed so far
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mutex);
+    size_t& have = granted[{kernel, dev}];
+    if (bytes <= have) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) have = bytes;
+    return e;
 }
 
 namespace {

@@ -14,6 +14,10 @@ constexpr int kWave = 64;
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Lets `kernel` use `bytes` of dynamic LDS.  The limit is a property of the function on a device, so it
+// is raised once (per function, device and size reached) and not on every launch.
+hipError_t allow_dynamic_lds(const void* kernel, size_t bytes);
+
 // Device scratch carved out of the caller's workspace.  All sections are 256-byte aligned.
 struct Workspace {
     float*    frame_sum;     // [B,F,C]  sum over the N tokens of every frame (anchor rule, inner sum)

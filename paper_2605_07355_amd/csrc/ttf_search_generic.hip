@@ -331,8 +331,7 @@ hipError_t launch_window_search_generic(const ttf_params& p, const void* x, cons
                     using P = decltype(patch);
                     const int tiles_x = (p.W + P::PT - 1) / P::PT, tiles = tiles_x * ((p.H + P::ROWS - 1) / P::ROWS);
                     const size_t lds = (size_t)P::CELLS * 1024;
-                    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kernel), lds);
                     if (e != hipSuccess) return e;
                     kernel<<<(unsigned)((size_t)p.B * p.F * tiles), 512, lds, s>>>(
                         static_cast<const T*>(x), static_cast<const T*>(ext_anchor), anchor_index, w.anchor_inv,

@@ -770,8 +770,7 @@ hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor
         if (wgs >= 2 * 256 && ks_total % KSWS == 0) {
             const size_t lds = 2 * KSWS * (size_t)S::NA * 1024;
             auto go = [&](auto kernel) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kernel), lds);
                 if (e != hipSuccess) return e;
                 kernel<<<(unsigned)wgs, 256, lds, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv, fuse_map,
                                                        best_sim, best_idx, keep16, win_sim, p.F, p.H, p.C, p.t, groups8,
@@ -855,8 +854,7 @@ hipError_t launch_padded(const ttf_params& p, const void* x, bool external_ancho
         const size_t wgs = (size_t)p.B * groups * strips;
         const size_t lds = 2 * KSWS * (size_t)S::NA * 1024;
         auto go = [&](auto kernel) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kernel), lds);
             if (e != hipSuccess) return e;
             kernel<<<(unsigned)wgs, 256, lds, s>>>(static_cast<const uint16_t*>(x), w.anchor_frag, anchor_index,
                                                    w.anchor_inv, fuse_map, best_sim, best_idx, nullptr, win_sim, p.F,

@@ -301,36 +301,53 @@ def test_stage_profile_reports_every_stage():
     assert all(v >= 0 for v in ms.values()) and ms["window_search"] > 0
 
 
-def test_graph_capture_and_replay():
+GRAPH_CASES = [
+    # name,                      B, F,  H,  W,    C, dtype,  r, speculation
+    ("aligned matrix cores",     2, 6, 16, 16,  256, "bf16", 1, None),
+    ("padded tile rows",         2, 6, 14, 14,  128, "bf16", 1, None),       # dynamic LDS, k_pack_keep
+    ("5x5 shared anchors",       2, 18, 64, 32, 128, "bf16", 2, None),       # dynamic LDS
+    ("general LDS-tiled",        4, 33, 64, 16,  40, "f32",  1, None),       # dynamic LDS
+    ("speculative anchor route", 2, 6, 16, 16, 1024, "bf16", 1, 1),
+]
+
+
+@pytest.mark.parametrize("name,B,F,H,W,C,dtype,r,spec", GRAPH_CASES, ids=[c[0] for c in GRAPH_CASES])
+def test_graph_capture_and_replay(name, B, F, H, W, C, dtype, r, spec):
     """The call only enqueues kernels on the caller's stream (no allocation, no synchronisation), so
     it can be captured into a HIP graph.  Replays on new input contents, with eager work and
     synchronisations in between, must give what an eager call gives on the same contents."""
     import paper_2605_07355_amd as ttf
-    cfg = CONFIGS["qwen3vl_2b"].scaled(B=2, F=6, C=256)
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=B, F=F, H=H, W=W, C=C, dtype=dtype, r=r, max_offset=min(max(r, 1), 2))
     xs = [to_device(make_clip_batch(cfg, seed=900 + i).x) for i in range(3)]
     x = torch.empty_like(xs[0])
-    B, F, H, W, C = x.shape
     buf = ttf.TTFBuffers.allocate(B, F, H, W, C, x.dtype, x.device)
     ref = ttf.TTFBuffers.allocate(B, F, H, W, C, x.dtype, x.device)
-    x.copy_(xs[0])
-    ttf.ttf_compress(x, r=1, t=0.7, buffers=buf)                  # warm-up outside the capture
-    torch.cuda.synchronize()
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
-        ttf.ttf_compress(x, r=1, t=0.7, buffers=buf)
-    for i in (1, 2, 0, 1):
-        x.copy_(xs[i])
-        graph.replay()
+    if spec is not None:
+        ttf.ttf_set_speculation(spec)
+    try:
+        x.copy_(xs[0])
+        ttf.ttf_compress(x, r=r, t=0.7, buffers=buf)                  # warm-up outside the capture
         torch.cuda.synchronize()
-        ttf.ttf_compress(xs[i], r=1, t=0.7, buffers=ref)          # eager, separate buffers
-        torch.cuda.synchronize()
-        rows = int(ref.row_offsets[-1])
-        assert int(buf.row_offsets[-1]) == rows
-        for name in ("anchor_index", "fuse_map", "kept_count", "row_offsets", "best_idx", "best_sim"):
-            assert torch.equal(getattr(buf, name), getattr(ref, name)), name
-        assert torch.equal(buf.src_index[:rows], ref.src_index[:rows])
-        assert torch.equal(buf.pos_ids[:, :rows], ref.pos_ids[:, :rows])
-        assert torch.equal(buf.tokens_out[:rows].view(torch.int16), ref.tokens_out[:rows].view(torch.int16))
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            ttf.ttf_compress(x, r=r, t=0.7, buffers=buf)
+        for i in (1, 2, 0, 1):
+            x.copy_(xs[i])
+            graph.replay()
+            torch.cuda.synchronize()
+            ttf.ttf_compress(xs[i], r=r, t=0.7, buffers=ref)          # eager, separate buffers
+            torch.cuda.synchronize()
+            rows = int(ref.row_offsets[-1])
+            assert int(buf.row_offsets[-1]) == rows
+            for field in ("anchor_index", "fuse_map", "kept_count", "row_offsets", "best_idx", "best_sim"):
+                assert torch.equal(getattr(buf, field), getattr(ref, field)), field
+            assert torch.equal(buf.src_index[:rows], ref.src_index[:rows])
+            assert torch.equal(buf.pos_ids[:, :rows], ref.pos_ids[:, :rows])
+            bits = torch.int16 if x.dtype == torch.bfloat16 else torch.int32
+            assert torch.equal(buf.tokens_out[:rows].view(bits), ref.tokens_out[:rows].view(bits))
+    finally:
+        if spec is not None:
+            ttf.ttf_set_speculation(0)
 
 
 def _random_shapes(n, seed):
