@@ -67,8 +67,8 @@ typedef enum { TTF_BF16 = 0, TTF_F32 = 1 } ttf_dtype;
 
 typedef enum { TTF_ANCHOR_AUTO = 0, TTF_ANCHOR_FIXED = 1 } ttf_anchor_mode;
 
-/* Problem description.  B*F*H*W must be < 2^31, and so must B*F*ceil(H*W/64)*64 (the token count with
- * every frame rounded up to whole 64-token groups). */
+/* Problem description.  B*F*ceil(H*W/64)*64 (the token count with every frame rounded up to whole
+ * 64-token groups) must be below 2^25 = 33 554 432, and H*W below 2^31. */
 typedef struct {
     int32_t B, F, H, W, C;    /* clips, frames, token-grid height and width, channels; all >= 1 */
     int32_t dtype;            /* ttf_dtype of `features` and `tokens_out`                        */
@@ -112,7 +112,7 @@ ttf_status ttf_workspace_size(const ttf_params* params, size_t* bytes);
  *   out        see ttf_outputs; all but the three optional fields are required.
  *   hip_stream hipStream_t (NULL = the default stream).
  * Errors: INVALID_ARG (NULL params/features/workspace/out or required output, a size < 1,
- * B*F*H*W >= 2^31, r < 0, t not finite, anchor_index outside [-F,F) in FIXED mode, unknown
+ * more than 2^25 tokens (frames rounded up to 64), r < 0, t not finite, anchor_index outside [-F,F) in FIXED mode, unknown
  * anchor_mode), UNSUPPORTED (unknown dtype; features, tokens_out or workspace misaligned),
  * WORKSPACE_TOO_SMALL, HIP.  Any C, grid and radius work.  Fast paths: bf16 input with
  * C % 128 == 0 and r <= 2 runs the window search on the matrix cores (any grid; grids exactly 16
@@ -236,7 +236,8 @@ ttf_status ttf_decode_alignment(int64_t l_prime, int64_t text_tokens, int64_t st
  * thresholds[b] = the rank-th smallest s^ of clip b.  Tokens strictly above it fuse, so at most
  * floor(phi*M) do, exactly that many when the values next to the rank are distinct.  F = 1 gives
  * thresholds[b] = 1.  Values are ordered as real numbers (-0 just below +0; a NaN with the sign
- * bit clear sorts above +inf, with it set below -inf).
+ * bit clear sorts above +inf, with it set below -inf).  Outputs of ttf_compress_segment
+ * (anchor_index[b] = -1) work too: all F frames are then source frames, M = F*N.
  *   best_sim, anchor_index   DEVICE, as written by ttf_compress (best_sim requested there)
  *   thresholds               DEVICE float [B]
  * Errors: INVALID_ARG (NULL pointer, bad sizes, phi outside [0,1] or NaN), HIP.
@@ -302,6 +303,11 @@ ttf_status ttf_set_speculation(int mode);
  * number `call` (0-based since enabling; must be one of the last `slots` calls) and writes its
  * stage durations in milliseconds to ms_out[0..min(n, TTF_NUM_STAGES)); stages that did not
  * run report ~0.  Event records sit between the kernels; profiling is off by default.
+ * This is a measurement hook, not part of the pass: it is the one place where the library creates
+ * HIP objects (events, at most TTF_PROFILE_MAX_SLOTS sets per thread, created by the first
+ * ttf_profile_enable that needs them and kept until the process ends); ttf_compress and
+ * ttf_compress_segment record into them only while profiling is enabled on the calling thread,
+ * the other entry points never do.  Do not enable it around a stream capture.
  * Errors: INVALID_ARG (bad slot count, NULL, call not available), HIP.
  */
 #define TTF_NUM_STAGES 7

@@ -30,11 +30,19 @@ __device__ __forceinline__ float key_value(uint32_t k)
 __global__ __launch_bounds__(1024) void k_select_threshold(const float* __restrict__ best_sim,
                                                            const int32_t* __restrict__ anchor_index,
                                                            float* __restrict__ thresholds,
-                                                           int F, int N, long long rank)
+                                                           int F, int N, double keep_fraction)
 {
     const int b = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int a = anchor_index[b];
+    const int a = anchor_index[b];                   // < 0 (segment outputs): every frame is a source frame
+    // rank of the order statistic among the clip's M source tokens: clamp(ceil((1 - phi) M), 1, M)
+    const long long M = (long long)(a < 0 ? F : F - 1) * N;
+    if (M == 0) {                                    // no source token: the documented default
+        if (threadIdx.x == 0) thresholds[b] = 1.0f;
+        return;
+    }
+    long long rank = (long long)ceil(keep_fraction * (double)M);
+    rank = rank < 1 ? 1 : (rank > M ? M : rank);
     const float* sim = best_sim + (size_t)b * F * N;
     const long long FN = (long long)F * N;
     const long long skip_lo = (long long)a * N, skip_hi = skip_lo + N;   // the anchor frame is not a source
@@ -116,11 +124,6 @@ __global__ __launch_bounds__(1024) void k_select_threshold(const float* __restri
     if (threadIdx.x == 0) thresholds[b] = key_value(s_prefix);
 }
 
-__global__ __launch_bounds__(64) void k_fill_thresholds(float* __restrict__ thresholds, int B, float v)
-{
-    for (int b = threadIdx.x; b < B; b += 64) thresholds[b] = v;
-}
-
 // Gate from stored similarities: one wave per 64-token keep word.
 __global__ __launch_bounds__(256) void k_regate(const float* __restrict__ best_sim,
                                                 const int32_t* __restrict__ best_idx,
@@ -151,14 +154,10 @@ __global__ __launch_bounds__(256) void k_regate(const float* __restrict__ best_s
 }  // namespace
 
 hipError_t launch_select_threshold(const ttf_params& p, const float* best_sim, const int32_t* anchor_index,
-                                   long long rank, float* thresholds, hipStream_t s)
+                                   double keep_fraction, float* thresholds, hipStream_t s)
 {
-    const int N = p.H * p.W;
-    if (p.F < 2) {                                            // no source tokens: the documented default
-        k_fill_thresholds<<<1, 64, 0, s>>>(thresholds, p.B, 1.0f);
-        return hipGetLastError();
-    }
-    k_select_threshold<<<(unsigned)p.B, 1024, 0, s>>>(best_sim, anchor_index, thresholds, p.F, N, rank);
+    k_select_threshold<<<(unsigned)p.B, 1024, 0, s>>>(best_sim, anchor_index, thresholds, p.F, p.H * p.W,
+                                                      keep_fraction);
     return hipGetLastError();
 }
 

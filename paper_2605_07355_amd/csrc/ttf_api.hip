@@ -85,8 +85,9 @@ ttf_status check_params(const ttf_params* p)
     const long long tokens = (long long)p->B * p->F * p->H * p->W;
     if ((long long)p->H * p->W >= (1ll << 31) || tokens >= (1ll << 31)) return TTF_ERR_INVALID_ARG;
     if (p->C > (1 << 21)) return TTF_ERR_INVALID_ARG;       // keeps every launch grid inside HIP limits
-    // one block per bit of the 64-token keep words (row emission)
-    if ((long long)p->B * p->F * (((long long)p->H * p->W + 63) / 64) * 64 >= (1ll << 31)) return TTF_ERR_INVALID_ARG;
+    // every launch stays below 2^32 threads: the densest grids take a 256-thread block per 16 tokens of a
+    // frame rounded up to whole 64-token keep words, or per 4 anchor tokens
+    if ((long long)p->B * p->F * (((long long)p->H * p->W + 63) / 64) * 64 >= (1ll << 25)) return TTF_ERR_INVALID_ARG;
     if (p->r < 0) return TTF_ERR_INVALID_ARG;
     if (!std::isfinite(p->t)) return TTF_ERR_INVALID_ARG;
     if (p->anchor_mode != TTF_ANCHOR_AUTO && p->anchor_mode != TTF_ANCHOR_FIXED) return TTF_ERR_INVALID_ARG;
@@ -376,10 +377,8 @@ ttf_status ttf_select_threshold(const ttf_params* params, const float* best_sim,
     if (st != TTF_OK) return st;
     if (!best_sim || !anchor_index || !thresholds) return TTF_ERR_INVALID_ARG;
     if (!(fused_fraction >= 0.0f && fused_fraction <= 1.0f)) return TTF_ERR_INVALID_ARG;
-    const long long M = (long long)(params->F - 1) * params->H * params->W;
-    long long rank = (long long)std::ceil((1.0 - (double)fused_fraction) * (double)M);
-    rank = rank < 1 ? 1 : (rank > M ? M : rank);
-    const hipError_t e = launch_select_threshold(*params, best_sim, anchor_index, rank, thresholds,
+    const hipError_t e = launch_select_threshold(*params, best_sim, anchor_index, 1.0 - (double)fused_fraction,
+                                                 thresholds,
                                                  static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) {
         g_last_hip_error = static_cast<int>(e);

@@ -209,7 +209,8 @@ hipError_t launch_emit_rows(const ttf_params& p, const void* x, const Workspace&
         // a quarter as many blocks as there could be rows: at the usual kept fractions every block has
         // one to four rows; 64 threads per KiB of row, at most 256
         const unsigned threads = (unsigned)(row_bytes >= 4096 ? 256 : row_bytes / 1024 * 64);
-        const unsigned blocks = (unsigned)((cap + 3) / 4);
+        const size_t want = (cap + 3) / 4;
+        const unsigned blocks = (unsigned)(want < kMaxBlocks256 ? want : kMaxBlocks256);
         k_copy_rows<<<dim3(blocks, tied ? p.B : 1), threads, 0, s>>>(xs, w.src_row, total_rows, out, row_bytes,
                                                                      tied_rows, tied_rows);
         return hipGetLastError();

@@ -14,6 +14,10 @@ constexpr int kWave = 64;
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// A launch may not have 2^32 threads or more: the most blocks of up to 256 threads.  Kernels that take
+// a block per row are launched with at most this many blocks and walk on by the grid size.
+constexpr size_t kMaxBlocks256 = (1u << 24) - 1;
+
 // Lets `kernel` use `bytes` of dynamic LDS.  The limit is a property of the function on a device, so it
 // is raised once (per function, device and size reached) and not on every launch.
 hipError_t allow_dynamic_lds(const void* kernel, size_t bytes);
@@ -166,8 +170,10 @@ hipError_t launch_restore_rows(const ttf_params& p, const void* tokens, long lon
                                const int32_t* restore_map, void* restored, hipStream_t s);
 // Adaptive threshold: exact order statistic of the source similarities per clip, and the gate
 // redone from stored similarities (fills fuse_map and the keep bits).
+// keep_fraction = 1 - requested fused fraction (double); the rank is formed per clip on the device,
+// from the clip's own number of source tokens.
 hipError_t launch_select_threshold(const ttf_params& p, const float* best_sim, const int32_t* anchor_index,
-                                   long long rank, float* thresholds, hipStream_t s);
+                                   double keep_fraction, float* thresholds, hipStream_t s);
 hipError_t launch_regate(const ttf_params& p, const Workspace& w, const float* best_sim, const int32_t* best_idx,
                          const int32_t* anchor_index, const float* thresholds, int32_t* fuse_map, hipStream_t s);
 

@@ -53,29 +53,31 @@ __global__ __launch_bounds__(256) void k_restore_rows(const char* __restrict__ t
     }
 }
 
-// Long rows: one block per original token, the whole block copies the row (the copy shape that runs
-// fastest on this chip; see k_emit_row_blocks).
+// Long rows: one block per original token (blocks beyond the launch limit walk on by the grid size),
+// the whole block copies the row: many small blocks with one or two 16-byte pieces per thread is the
+// copy shape that runs fastest on this chip.
 __global__ __launch_bounds__(256) void k_restore_row_blocks(const char* __restrict__ tokens,
                                                             const int32_t* __restrict__ restore_map,
                                                             char* __restrict__ restored, size_t row_bytes,
-                                                            long long rows)
+                                                            long long rows, size_t total)
 {
-    const size_t tok = blockIdx.x;
-    const long long row = restore_map[tok];
-    uint4* d = reinterpret_cast<uint4*>(restored + tok * row_bytes);
-    const int n = (int)(row_bytes / 16);
-    const int step = (int)blockDim.x;
-    int q = threadIdx.x;
-    if (row >= 0 && row < rows) {
-        const uint4* s = reinterpret_cast<const uint4*>(tokens + (size_t)row * row_bytes);
-        for (; q + step < n; q += 2 * step) {
-            const uint4 v0 = s[q], v1 = s[q + step];          // cached loads: anchor rows are read many times
-            store16_stream(d + q, v0);
-            store16_stream(d + q + step, v1);
+    for (size_t tok = blockIdx.x; tok < total; tok += gridDim.x) {
+        const long long row = restore_map[tok];
+        uint4* d = reinterpret_cast<uint4*>(restored + tok * row_bytes);
+        const int n = (int)(row_bytes / 16);
+        const int step = (int)blockDim.x;
+        int q = threadIdx.x;
+        if (row >= 0 && row < rows) {
+            const uint4* s = reinterpret_cast<const uint4*>(tokens + (size_t)row * row_bytes);
+            for (; q + step < n; q += 2 * step) {
+                const uint4 v0 = s[q], v1 = s[q + step];      // cached loads: anchor rows are read many times
+                store16_stream(d + q, v0);
+                store16_stream(d + q + step, v1);
+            }
+            if (q < n) store16_stream(d + q, s[q]);
+        } else {
+            for (; q < n; q += step) store16_stream(d + q, uint4{0u, 0u, 0u, 0u});
         }
-        if (q < n) store16_stream(d + q, s[q]);
-    } else {
-        for (; q < n; q += step) store16_stream(d + q, uint4{0u, 0u, 0u, 0u});
     }
 }
 
@@ -101,8 +103,9 @@ hipError_t launch_restore_rows(const ttf_params& p, const void* tokens, long lon
     char* out = static_cast<char*>(restored);
     constexpr size_t kRowBlockMin = 2048;
     if (row_bytes % 16 == 0 && row_bytes >= kRowBlockMin)
-        k_restore_row_blocks<<<(unsigned)total, (unsigned)(row_bytes >= 4096 ? 256 : 128), 0, s>>>(in, restore_map, out,
-                                                                                                 row_bytes, rows);
+        k_restore_row_blocks<<<(unsigned)(total < kMaxBlocks256 ? total : kMaxBlocks256),
+                               (unsigned)(row_bytes >= 4096 ? 256 : 128), 0, s>>>(in, restore_map, out, row_bytes, rows,
+                                                                                   total);
     else if (row_bytes % 16 == 0)
         k_restore_rows<16><<<grid, 256, 0, s>>>(in, restore_map, out, total, row_bytes, rows);
     else if (row_bytes % 4 == 0)

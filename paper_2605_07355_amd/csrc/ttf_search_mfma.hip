@@ -1,5 +1,8 @@
-// Window search and gate for bf16 tokens on grids 16 or 32 tokens wide (Section 3, "Pointwise
-// Matching with Local Window Search" and "Threshold Gating"), on the gfx950 matrix cores.
+// Window search and gate for bf16 tokens with windows up to 5x5 on any grid (Section 3, "Pointwise
+// Matching with Local Window Search" and "Threshold Gating"), on the gfx950 matrix cores.  Grids
+// exactly 16 or 32 tokens wide with whole 64-token keep words take k_search_mfma (the 5x5 window on
+// large 32-wide inputs k_search_mfma_shared); every other grid runs k_search_mfma_shared on tile rows
+// padded to whole 16-column tiles.
 //
 // Why matrix cores for a banded product: the (2r+1)^2 dot products per source token cost
 // 2(2r+1)^2 C + 2C flops per 2C input bytes.  On the plain vector ALUs (78.6 TFLOP/s fp32
@@ -295,11 +298,6 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
     const int KS = C / 32;                                   // K-steps per token
     const int nsrc = (SPEC == 1 || a_in < 0) ? F : F - 1;    // frames walked per clip (>= 1 here)
 
-    // source frame of slot f: the f-th walked frame of this group, the last one repeated past the end.
-    // Loads go through buffer descriptors: one per-lane byte offset shared by every tile (load order:
-    // lane -> token lane/4, 16-byte chunk lane%4) plus a wave-uniform offset per tile in scalar
-    // registers, instead of a 64-bit address per tile in vector registers.  The source descriptor
-    // starts at the group's first frame and ends with the clip; reads past its end would return zero.
     // source frame of slot f: the f-th walked frame of this group, the last one repeated past the end
     // (plain 64-bit addresses: the same loads through buffer descriptors, with one shared per-lane
     // offset and scalar per-tile offsets, freed 22 registers but ran 10 % slower)
@@ -897,6 +895,9 @@ bool mfma_search_supported(const ttf_params& p)
 bool mfma_search_padded(const ttf_params& p)
 {
     if (p.dtype != TTF_BF16 || p.r > 2 || p.C % 128 != 0) return false;
+    // the padded kernels index a clip's anchor fragments with 32-bit offsets
+    const long long padded_tokens = (long long)p.H * ((p.W + 15) / 16) * 16;
+    if (padded_tokens * p.C >= (1ll << 31)) return false;
     return !mfma_search_supported(p);
 }
 

@@ -146,6 +146,47 @@ def test_selected_threshold_without_source_frames():
     np.testing.assert_array_equal(t.cpu().numpy(), np.ones(4, np.float32))
 
 
+@pytest.mark.parametrize("B,F,H,W", [(3, 5, 7, 9), (2, 1, 4, 6), (4, 12, 16, 16)])
+@pytest.mark.parametrize("fraction", [0.0, 0.3, 0.67, 1.0])
+def test_selected_threshold_on_segment_outputs(B, F, H, W, fraction):
+    """anchor_index = -1 (outputs of ttf_compress_segment): every frame is a source frame, M = F*N,
+    also for a one-frame segment."""
+    import paper_2605_07355_amd as ttf
+    from oracle import adaptive as A
+    sim, _ = similarity_field(B, F, H * W, seed=B * 10 + F)
+    anchor = np.full(B, -1, np.int32)
+    t = ttf.ttf_select_threshold(_FakeOut(sim, anchor, H, W), fraction)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(t.cpu().numpy(), A.select_threshold(sim, anchor, fraction))
+
+
+def test_segment_select_and_regate():
+    """Threshold selection and re-gating on a segment's outputs: the threshold is the oracle's order
+    statistic of the library's own similarities over all F*N tokens, and the re-gated segment fuses
+    exactly the tokens above it."""
+    import paper_2605_07355_amd as ttf
+    from oracle import adaptive as A
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=2, F=6, C=256)
+    batch = make_clip_batch(cfg)
+    anchor, seg = np.ascontiguousarray(batch.x[:, 0]), np.ascontiguousarray(batch.x[:, 1:])
+    out = _run_segment(seg, anchor, 3, cfg.r, cfg.t[0])
+    phi = 0.5
+    t = ttf.ttf_select_threshold(out, phi)
+    torch.cuda.synchronize()
+    sim = out.buffers.best_sim.cpu().numpy()
+    np.testing.assert_array_equal(t.cpu().numpy(), A.select_threshold(sim, np.full(cfg.B, -1, np.int32), phi))
+    ttf.ttf_regate(to_device(seg), out, t)
+    torch.cuda.synchronize()
+    M = (cfg.F - 1) * cfg.N                                        # the segment has F-1 frames, all sources
+    for b in range(cfg.B):
+        fused = out.buffers.fuse_map[b] >= 0
+        assert torch.equal(fused, out.buffers.best_sim[b] > t[b])
+        n = int(fused.sum())
+        assert int(0.49 * M) <= n <= int(np.floor(float(np.float32(phi)) * M))
+        assert int(out.buffers.kept_count[b]) == M - n
+    assert (out.buffers.anchor_index == -1).all()
+
+
 @pytest.mark.parametrize("name,scale", SMALL + [("qwen3vl_8b_batched", {})])
 def test_regate_per_clip_thresholds(name, scale):
     """Search once at the workload's threshold, then re-gate at a different threshold per clip:

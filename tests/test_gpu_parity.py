@@ -132,7 +132,7 @@ SHAPES = [
     (4, 33, 64, 16, 72, "bf16", 2),      # bf16 with C % 128 != 0, 5x5 window
     (4, 31, 63, 17, 264, "f32", 1),      # ragged keep words, two channel chunks
     (2, 40, 90, 20, 8, "bf16", 0),       # 1x1 window, a single 16-byte piece per row
-    (3, 12, 64, 64, 16, "f32", 1),       # halo too large for LDS at this width: direct kernel on a large input
+    (3, 12, 64, 64, 16, "f32", 1),       # the LDS-tiled kernel on a 64-wide grid (eight patches per grid row)
     # whole 4 KiB slabs per row and at least 512 (frame, slab) pairs: the slab form of the frame sums
     (8, 32, 4, 4, 2048, "f32", 1),       # fp32, N = 16: two rounds of eight rows
     (4, 64, 3, 5, 4096, "bf16", 1),      # bf16, N = 15: one round and a tail of seven rows

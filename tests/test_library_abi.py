@@ -46,16 +46,16 @@ def test_workspace_size_and_argument_checks():
     assert 4 * 2**20 <= ttf.ttf_workspace_size(16, 32, 16, 16, 2048, torch.float32) <= 5 * 2**20
     assert ttf.ttf_workspace_size(1, 1, 1, 1, 1, torch.float32) > 0
     for bad in (dict(B=0), dict(F=0), dict(H=-1), dict(C=0), dict(r=-1), dict(t=float("inf")),
-                dict(anchor=40), dict(anchor=-33), dict(B=2**16, F=2**15)):
+                dict(anchor=40), dict(anchor=-33), dict(B=2**12, F=2**11)):
         kw = dict(B=2, F=32, H=16, W=16, C=64, dtype=torch.bfloat16, r=1, t=0.7, anchor="auto")
         kw.update(bad)
         with pytest.raises(ttf.TTFError) as e:
             ttf.ttf_workspace_size(**kw)
         assert e.value.status == 1, bad
-    # token counts are also bounded with every frame rounded up to whole 64-token keep words
-    kw = dict(B=2**10, F=2**10, H=1, W=65, C=64, dtype=torch.bfloat16, r=1, t=0.7, anchor="auto")
-    assert ttf.ttf_workspace_size(**kw) > 0                      # 2^20 frames x 128 = 2^27
-    kw.update(B=2**14)                                           # 2^24 frames x 65 tokens < 2^31, x 128 = 2^31
+    # token counts are bounded with every frame rounded up to whole 64-token keep words: below 2^25
+    kw = dict(B=2**8, F=2**8, H=1, W=65, C=64, dtype=torch.bfloat16, r=1, t=0.7, anchor="auto")
+    assert ttf.ttf_workspace_size(**kw) > 0                      # 2^16 frames x 128 = 2^23
+    kw.update(B=2**10)                                           # 2^18 frames x 65 tokens < 2^25, x 128 = 2^25
     with pytest.raises(ttf.TTFError) as e:
         ttf.ttf_workspace_size(**kw)
     assert e.value.status == 1
