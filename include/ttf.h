@@ -143,8 +143,9 @@ ttf_status ttf_compress_static(const ttf_params* params, const void* features,
                                const ttf_outputs* out, void* hip_stream);
 
 /*
- * One segment of a stream (Discussion D3: the last frame of each segment is the rolling anchor of
- * the next; new frames are compressed against it and only the short result is appended).
+ * One segment of a stream (the streaming use sketched in Discussion D3): video arrives in pieces, and
+ * each piece is matched not against a frame of its own but against the frame that closed the
+ * previous piece, so that earlier context never has to be encoded again.
  * Every one of the F frames of `features` is a source frame matched against `anchor_frame`; the
  * output holds only the preserved source rows, in ascending flat order k*N+i, so it is what
  * ttf_compress gives for the (F+1)-frame clip [anchor_frame ; features] with its anchor fixed to
@@ -165,10 +166,12 @@ ttf_status ttf_compress_segment(const ttf_params* params, const void* features, 
                                 const ttf_outputs* out, void* hip_stream);
 
 /*
- * Tied-batch mode (Section 3: for B > 1 the same offset is chosen for all batch elements by
- * maximising the mean similarity at each (k,i), s^ is read per element at that offset, and the
- * preserve rule unites the keep masks over the batch).  All B elements therefore keep the same
- * index set and the output is rectangular.  Choices the text leaves open: the anchor frame is
+ * Tied-batch mode (Section 3, the remark on B > 1 after the s^/dst equations, and the gating
+ * paragraph): the B elements are treated as views of one sequence.  For every source position the
+ * candidate cell is scored by the average of the B elements' cosines and one cell is picked for all of
+ * them; each element reports its own cosine at that shared cell; a position is dropped only when
+ * every element's cosine exceeds t.  All B elements therefore keep the same index set and the
+ * output is rectangular.  Choices the text leaves open: the anchor frame is
  * shared -- under the automatic rule the frame with the largest batch-mean anchor score (lowest
  * k on ties), else the fixed frame; the mean is the arithmetic mean of the B cosines of one
  * candidate cell; first maximum in row-major offset order.  Radius r <= 3 (UNSUPPORTED beyond).

@@ -1,8 +1,8 @@
 """Oracle for segment-wise (streaming) compression.  TEST INFRASTRUCTURE ONLY.
 
-Discussion D3: frames arrive in segments; the last frame of the previous segment is the
-rolling anchor, the new frames are compressed against it and only the resulting short token
-sequence is appended.  A segment of F frames with an external anchor frame is therefore the
+The streaming use of Discussion D3: a video is handled piece by piece, and a piece is matched
+against the frame that closed the piece before it instead of a frame of its own, so that nothing
+already emitted is touched again.  A segment of F frames with an external anchor frame is therefore the
 plain pass on the (F+1)-frame clip [anchor ; segment] with the anchor fixed to its first
 frame, minus the N anchor rows (they were emitted when that frame was a source frame of the
 previous segment): every segment frame is a source frame, the output holds only the preserved

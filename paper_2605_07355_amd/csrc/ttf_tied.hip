@@ -1,6 +1,7 @@
-// Tied-batch matching and gating (Section 3: for B > 1 one offset per source position is chosen by
-// maximising the mean similarity across the batch elements, every element reads its s^ at that
-// offset, and the preserve rule unites the keep masks over the batch).
+// Tied-batch matching and gating (Section 3, the B > 1 remark after the s^/dst equations and the
+// gating paragraph): the B elements share one candidate cell per source position -- the cell whose
+// cosines average highest over the elements -- each element reports its own cosine there, and a
+// position is dropped only if all elements exceed the threshold.
 //
 // The window search has left every element's cosines of the whole window in
 // win_sim[b][k][(dy+r)*(2r+1) + (dx+r)][i] (entries of cells outside the grid are never written
