@@ -237,44 +237,74 @@ __global__ __launch_bounds__(1024) void k_anchor_partials(const float* __restric
                                        1, gsh);
 }
 
-// Anchor guess, step 1 (bf16 rows): sums over the N tokens of a frame of the kGuessChannels guess
-// channels only (kGuessSegments runs of 128 bytes per token row).  One block per frame: thread t
-// reads 16-byte piece t%32 of the guess channels of tokens t/32, t/32 + 8, ...; the eight token
-// groups are added through LDS in order.
+// Strip sums -> frame sums for the clips with a trusted anchor guess (grids with many strips per
+// frame: a plain streaming reduction ahead of k_anchor_partials<false> keeps the chip full, where the
+// fused form has too few blocks).  Block (frame, 1024-channel slab): thread t adds its four channels
+// over the strips in ascending order, eight loads in flight.
+__global__ __launch_bounds__(256) void k_reduce_strips(const float* __restrict__ strip_sum,
+                                                       float* __restrict__ frame_sum,
+                                                       const int32_t* __restrict__ spec, int F, int C, int strips)
+{
+    const size_t frame = blockIdx.x;
+    if (!spec[4 * (frame / F) + 1]) return;             // this clip's frame sums come from k_frame_sums
+    const int c = (blockIdx.y * 256 + threadIdx.x) * 4;
+    if (c >= C) return;
+    const float* row = strip_sum + frame * (size_t)strips * C + c;
+    float4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < strips; s0 += 8) {
+        float4 q[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (s0 + u < strips) q[u] = *reinterpret_cast<const float4*>(row + (size_t)(s0 + u) * C);
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (s0 + u < strips) { acc.x += q[u].x; acc.y += q[u].y; acc.z += q[u].z; acc.w += q[u].w; }
+    }
+    *reinterpret_cast<float4*>(frame_sum + frame * (size_t)C + c) = acc;
+}
+
+// Anchor guess, step 1 (bf16 rows): sums over the tokens of a frame of the kGuessChannels guess
+// channels only (kGuessSegments runs of 128 bytes per token row).  Block (frame, part) covers tokens
+// part*per .. (part+1)*per - 1: thread t reads 16-byte piece t%32 of the guess channels of its tokens
+// t/32, t/32 + 8, ...; the eight token groups are added through LDS in order.  The parts of a frame
+// are added by guess_pick_block.
 __global__ __launch_bounds__(256) void k_guess_sums(const uint16_t* __restrict__ x, float* __restrict__ guess_sum,
-                                                    int N, int C)
+                                                    int N, int C, int parts)
 {
     static_assert(kGuessSegChannels == 64 && kGuessSegments * 8 == 32, "32 sixteen-byte pieces per token");
-    const size_t frame = blockIdx.x;
+    const size_t frame = blockIdx.x / parts;
+    const int part = blockIdx.x % parts;
+    const int per = (N + parts - 1) / parts;
+    const int n_lo = part * per, n_hi = min(N, n_lo + per);
     const int ts = threadIdx.x >> 5, q = threadIdx.x & 31;
     const int ch = guess_segment_start(C, q >> 3) + (q & 7) * 8;
     const uint16_t* base = x + frame * (size_t)N * C + ch;
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    for (int i0 = ts; i0 < N; i0 += 64) {
+    for (int i0 = n_lo + ts; i0 < n_hi; i0 += 64) {
         RowVec<bf16_t, 8> r[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int i = i0 + 8 * u;
-            if (i < N) r[u].template load<true>(reinterpret_cast<const bf16_t*>(base + (size_t)i * C));
+            if (i < n_hi) r[u].template load<true>(reinterpret_cast<const bf16_t*>(base + (size_t)i * C));
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            if (i0 + 8 * u < N) {
+            if (i0 + 8 * u < n_hi) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) acc[e] += r[u].v[e];
             }
         }
     }
-    __shared__ float part[8][kGuessChannels];
+    __shared__ float part_s[8][kGuessChannels];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) part[ts][q * 8 + e] = acc[e];
+    for (int e = 0; e < 8; ++e) part_s[ts][q * 8 + e] = acc[e];
     __syncthreads();
-    float t = part[0][threadIdx.x];
+    float t = part_s[0][threadIdx.x];
 #pragma unroll
-    for (int w = 1; w < 8; ++w) t += part[w][threadIdx.x];
-    guess_sum[frame * kGuessChannels + threadIdx.x] = t;
+    for (int w = 1; w < 8; ++w) t += part_s[w][threadIdx.x];
+    guess_sum[(size_t)blockIdx.x * kGuessChannels + threadIdx.x] = t;
 }
 
 // Anchor guess, step 2: the anchor rule evaluated on the guess channels alone (fp64 from the fp32
@@ -285,12 +315,22 @@ __global__ __launch_bounds__(256) void k_guess_sums(const uint16_t* __restrict__
 // Returns the guessed frame (lowest k on ties) and whether it is trusted, to every thread.
 constexpr double kGuessMinGap = 0.1;
 template <int NWV>
-__device__ __forceinline__ void guess_pick_block(const float* __restrict__ guess_sum, int b, int F, int& guess,
-                                                 bool& trusted)
+__device__ __forceinline__ void guess_pick_block(const float* __restrict__ guess_sum, int b, int F, int parts,
+                                                 int& guess, bool& trusted)
 {
     constexpr int UN = 8;                               // frames in flight per wave
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const float* gs = guess_sum + (size_t)b * F * kGuessChannels + lane * 4;
+    const size_t fstride = (size_t)parts * kGuessChannels;
+    const float* gs = guess_sum + (size_t)b * F * fstride + lane * 4;
+    // this lane's four guess channels of frame k: its parts added in order
+    auto load4 = [&](int k) {
+        float4 v = *reinterpret_cast<const float4*>(gs + (size_t)k * fstride);
+        for (int pp = 1; pp < parts; ++pp) {
+            const float4 q = *reinterpret_cast<const float4*>(gs + (size_t)k * fstride + (size_t)pp * kGuessChannels);
+            v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
+        }
+        return v;
+    };
     __shared__ double gsh[NWV][kGuessChannels];
     __shared__ double s_best[NWV], s_second[NWV];
     __shared__ int s_arg[NWV], s_nan[NWV];
@@ -304,7 +344,7 @@ __device__ __forceinline__ void guess_pick_block(const float* __restrict__ guess
         for (int u = 0; u < UN; ++u) {
             const int k = k0 + NWV * u;
             v[u] = float4{0.f, 0.f, 0.f, 0.f};
-            if (k < F) v[u] = *reinterpret_cast<const float4*>(gs + (size_t)k * kGuessChannels);
+            if (k < F) v[u] = load4(k);
         }
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
@@ -332,7 +372,7 @@ __device__ __forceinline__ void guess_pick_block(const float* __restrict__ guess
             for (int u = 0; u < UN; ++u) {
                 const int k = k0 + NWV * u;
                 v[u] = float4{0.f, 0.f, 0.f, 0.f};
-                if (k < F) v[u] = *reinterpret_cast<const float4*>(gs + (size_t)k * kGuessChannels);
+                if (k < F) v[u] = load4(k);
             }
         }
 #pragma unroll
@@ -523,7 +563,7 @@ __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restri
                                                         int32_t* __restrict__ best_idx, uint16_t* __restrict__ keep16,
                                                         int F, int N, int C, int S, int fixed_anchor, int tiles,
                                                         int Wg, int CT, int32_t* __restrict__ spec, int spec_mode,
-                                                        const float* __restrict__ guess_sum)
+                                                        const float* __restrict__ guess_sum, int guess_parts)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int b = blockIdx.x / tiles, tile = blockIdx.x % tiles;
@@ -540,7 +580,7 @@ __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restri
         // clip for itself.  A trusted guess stands in for the anchor until the search has produced exact
         // frame sums; a clip without one is only summed by the coming search, so nothing is prepared.
         bool trusted;
-        guess_pick_block<8>(guess_sum, b, F, a, trusted);
+        guess_pick_block<8>(guess_sum, b, F, guess_parts, a, trusted);
         if (tile == 0 && threadIdx.x == 0) {
             spec[4 * b + 0] = a;
             spec[4 * b + 1] = trusted ? 1 : 0;
@@ -654,9 +694,16 @@ hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, bool mi
     int FG = 1;
     while (FG < 16 && (size_t)S * p.B * FG < 512 && p.F >= 64 * FG) FG *= 2;
     const unsigned grid = (unsigned)((size_t)S * p.B * FG);
-    if (mixed)
-        k_anchor_partials<true><<<grid, 1024, 0, s>>>(w.frame_sum, w.score_part, w.clip_part, p.F, p.C, S, FG,
-                                                      p.H * p.W / 32, w.strip_sum, w.spec);
+    const int strips = p.H * p.W / 32;
+    if (mixed && strips > 8) {
+        k_reduce_strips<<<dim3((unsigned)(p.B * p.F), (unsigned)((p.C + 1023) / 1024)), 256, 0, s>>>(
+            w.strip_sum, w.frame_sum, w.spec, p.F, p.C, strips);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (mixed && strips <= 8)
+        k_anchor_partials<true><<<grid, 1024, 0, s>>>(w.frame_sum, w.score_part, w.clip_part, p.F, p.C, S, FG, strips,
+                                                      w.strip_sum, w.spec);
     else
         k_anchor_partials<false><<<grid, 1024, 0, s>>>(w.frame_sum, w.score_part, w.clip_part, p.F, p.C, S, FG, 1,
                                                        nullptr, nullptr);
@@ -666,7 +713,9 @@ hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, bool mi
 // Frame sums over the guess channels only (w.guess_sum), from which the anchor is guessed.
 hipError_t launch_guess_sums(const ttf_params& p, const void* x, const Workspace& w, hipStream_t s)
 {
-    k_guess_sums<<<(unsigned)(p.B * p.F), 256, 0, s>>>(static_cast<const uint16_t*>(x), w.guess_sum, p.H * p.W, p.C);
+    const int parts = guess_parts(p);
+    k_guess_sums<<<(unsigned)(p.B * p.F * parts), 256, 0, s>>>(static_cast<const uint16_t*>(x), w.guess_sum, p.H * p.W,
+                                                               p.C, parts);
     return hipGetLastError();
 }
 
@@ -715,7 +764,8 @@ hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const 
                                                        w.clip_part, anchor_index, w.anchor_inv, w.anchor_frag, fuse_map,
                                                        best_sim, best_idx, reinterpret_cast<uint16_t*>(w.keep_bits),
                                                        p.F, N, p.C, (p.C + 255) / 256, fixed, tiles, p.W, CT,
-                                                       spec_mode ? w.spec : nullptr, spec_mode, w.guess_sum);
+                                                       spec_mode ? w.spec : nullptr, spec_mode, w.guess_sum,
+                                                       guess_parts(p));
         return hipGetLastError();
     };
     return pad ? go(k_anchor_prepare<true>) : go(k_anchor_prepare<false>);

@@ -34,7 +34,8 @@ struct Workspace {
     int32_t*  frame_base;    // [B,F]    output row of the first kept token of every frame
     int32_t*  src_row;       // [B*F*N]  input token (flat over clips and frames) that output row r copies
     // Speculative anchor (single pass over the input, see ttf_api.hip); sized 0 where it cannot apply
-    float*    guess_sum;     // [B,F,kGuessChannels] frame sums over the guess channels only
+    float*    guess_sum;     // [B,F,P,kGuessChannels] frame sums over the guess channels only, in P = guess_parts()
+                             // shares (one per run of tokens)
     int32_t*  spec;          // [B,4]    guessed anchor, guess trusted (1/0), second search needed (1/0), unused
     float*    strip_sum;     // [B,F,N/32,C] sum of every 32-token strip of every frame, written by the search
     size_t    bytes;
@@ -48,6 +49,13 @@ constexpr int kGuessChannels = kGuessSegments * kGuessSegChannels;
 __host__ __device__ inline int guess_segment_start(int C, int j)
 {
     return (int)(((long long)(2 * j + 1) * C / (2 * kGuessSegments)) / kGuessSegChannels * kGuessSegChannels);
+}
+// The guess sums of a frame are formed by this many blocks, each over a run of the frame's tokens (more
+// blocks for big grids, so that few frames still fill the chip), and added when the guess is picked.
+inline int guess_parts(const ttf_params& p)
+{
+    const long long n = (long long)p.H * p.W;
+    return n >= 2048 ? 8 : (n >= 1024 ? 4 : (n >= 512 ? 2 : 1));
 }
 // Shapes the speculative anchor path exists for: the aligned matrix-core search kernels (bf16, grid
 // 16 or 32 wide with whole keep words, C % 128 == 0) with at least 1024 channels, so that the guess
@@ -74,7 +82,7 @@ inline Workspace carve(const ttf_params& p, void* base)
     const size_t o_fb = take(B * F * sizeof(int32_t));
     const size_t o_sr = take(B * F * N * sizeof(int32_t));
     const bool spec = speculation_shape(p);
-    const size_t o_gs = take(spec ? B * F * kGuessChannels * sizeof(float) : 0);
+    const size_t o_gs = take(spec ? B * F * guess_parts(p) * kGuessChannels * sizeof(float) : 0);
     const size_t o_sp2 = take(spec ? B * 4 * sizeof(int32_t) : 0);
     const size_t o_ss = take(spec ? B * F * (N / 32) * C * sizeof(float) : 0);
     char* c = static_cast<char*>(base);

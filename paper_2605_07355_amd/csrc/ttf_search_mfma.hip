@@ -514,13 +514,17 @@ __device__ __forceinline__ void lds_barrier()
 // of the anchor fragments of the pass after next and then the source fragments two passes ahead,
 // and computes the current pass from LDS and registers.
 // PAD: grids narrower than the tile row (Wg <= 16*CT) and of any height; see finish_tile.
-template <int CT, int RAD, int KSW, int FW, bool ALL, bool PAD = false>
+// SPEC: as for k_search_mfma (1: speculative pass -- every frame walked, strip sums written, clips
+// without a trusted guess skipped; 2: second search of the marked clips only).
+template <int CT, int RAD, int KSW, int FW, bool ALL, bool PAD = false, int SPEC = 0>
 __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ anchor_frag,
     const int32_t* __restrict__ anchor_index, const float* __restrict__ anchor_inv,
     int32_t* __restrict__ fuse_map, float* __restrict__ best_sim, int32_t* __restrict__ best_idx,
-    uint16_t* __restrict__ keep16, float* __restrict__ win_sim, int F, int H, int C, float t, int groups, int Wg)
+    uint16_t* __restrict__ keep16, float* __restrict__ win_sim, int F, int H, int C, float t, int groups, int Wg,
+    const int32_t* __restrict__ spec, float* __restrict__ strip_sum)
 {
+    static_assert(SPEC == 0 || (!PAD && !ALL && CT <= 2 && KSW <= 2), "speculative pass: aligned grids only");
     using S = Shape<CT, RAD>;
     constexpr int W = S::W, NA = S::NA, NPS = S::NPS;
     constexpr int NS = 2 * FW;                               // source tiles per wave (FW frames)
@@ -549,9 +553,15 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
         grp = (blockIdx.x / tpf) % groups;
         b = blockIdx.x / tpf / groups;
     }
+    if constexpr (SPEC == 1) {
+        if (spec[4 * b + 1] == 0) return;                    // no trusted guess: the clip takes the two-pass route
+    }
+    if constexpr (SPEC == 2) {
+        if (spec[4 * b + 2] == 0) return;                    // guess confirmed: nothing to redo
+    }
     const int a_in = anchor_index[b];
-    const int a = a_in < 0 ? F : a_in;
-    const int nsrc = a_in < 0 ? F : F - 1;
+    const int a = (SPEC == 1 || a_in < 0) ? 0x7fffffff : a_in;   // the speculative pass walks the anchor frame too
+    const int nsrc = (SPEC == 1 || a_in < 0) ? F : F - 1;
     // first source row y0 and first column tile c0 of the strip; i0 = y0 * W is what finish_tile decodes
     const int y0 = CT == 3 ? tp / spr : tp * 32 / W;
     const int c0 = CT == 3 ? 2 * (tp % spr) : 0;
@@ -618,7 +628,18 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
         _Pragma("unroll") for (int i = 0; i < GL; ++i)                                                        \
             frag_lds[(buf_) * (KSW * NA * 64) + gslot[i] + lane] = G[i];                                      \
     } while (0)
-    auto compute = [&](int buf, const u32x4 (&Abuf)[NS][KSW]) {
+    // speculative pass: channel pickers, where this lane's strip sums go (as in k_search_mfma; here a
+    // wave owns whole frames and the whole channel axis), and the first K-step's totals of a pass
+    bf16x8 pick0, pick1;
+    float* sums = nullptr;
+    float held[FW];
+    if constexpr (SPEC == 1) {
+        pick0 = channel_picker(0, lane);
+        pick1 = channel_picker(1, lane);
+        const int k0 = min(grp * FRG + wave * FW, F - 1);
+        sums = strip_sum + ((((size_t)b * F + k0) * tpf + tp) * (size_t)C) + (KSW == 2 ? lane : (lane & 31));
+    }
+    auto compute = [&](int buf, const u32x4 (&Abuf)[NS][KSW], int ks0) {
 #pragma unroll
         for (int ks = 0; ks < KSW; ++ks) {
             bf16x8 av[NS];                                   // source tiles in operand order
@@ -647,6 +668,32 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
                     }
                 }
             }
+            if constexpr (SPEC == 1) {
+                // strip sums of this K-step: tokens x channels of both tiles of a frame through the channel
+                // pickers, four in-lane adds, the four row groups by an fp32 MFMA against ones; one
+                // 256-byte store per frame and pass (lanes 0..31 first K-step, 32..63 second).  A slot past
+                // the clip's end repeats the last frame and stores the same values to the same place.
+#pragma unroll
+                for (int f = 0; f < FW; ++f) {
+                    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                    f32x4 d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[2 * f], pick0, zero, 0, 0, 0);
+                    f32x4 d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[2 * f], pick1, zero, 0, 0, 0);
+                    d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[2 * f + 1], pick0, d0, 0, 0, 0);
+                    d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[2 * f + 1], pick1, d1, 0, 0, 0);
+                    const float t0 = (d0[0] + d0[1]) + (d0[2] + d0[3]);
+                    const float t1 = (d1[0] + d1[1]) + (d1[2] + d1[3]);
+                    const f32x4 r0 = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, t0, zero, 0, 0, 0);
+                    const f32x4 r1 = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, t1, zero, 0, 0, 0);
+                    const float mine = (g & 1) ? r1[0] : r0[0];
+                    if (KSW == 1 || ks == KSW - 1) {
+                        const float v = (KSW == 2 && lane < 32) ? held[f] : mine;
+                        const int k0 = min(grp * FRG + wave * FW, F - 1);
+                        sums[(size_t)(min(k0 + f, F - 1) - k0) * tpf * C + ks0 * 32] = v;
+                    } else {
+                        held[f] = mine;
+                    }
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);               // keep the K-steps apart: bounded live ranges
         }
     };
@@ -670,7 +717,7 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
         TTF_REQUEST_ANCHOR(pp + 2);                                   \
         TTF_REQUEST_SOURCE(pp + 2, A[((j) + 2) % 3]);                 \
         __builtin_amdgcn_sched_barrier(0);                            \
-        compute(pp & 1, A[(j)]);                                      \
+        compute(pp & 1, A[(j)], pp * KSW);                            \
         __builtin_amdgcn_sched_barrier(0);                            \
         lds_barrier();                                                \
     } while (0)
@@ -701,8 +748,9 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
 #pragma unroll
         for (int j = 0; j < 4; ++j) nn[j] = __shfl(nv[s], 4 * (4 * g + j), 64);
         const int si = grp * FRG + wave * FW + s / 2;
-        finish_tile<CT, RAD, ALL, PAD>(acc[s], nn, s, si < nsrc, min(si, nsrc - 1), a, b, F, H, i0, t, ai_tile,
-                                       fuse_map, best_sim, best_idx, keep16, win_sim, lane, Wg, c0);
+        // (in the speculative pass the anchor frame is walked for its sums only)
+        finish_tile<CT, RAD, ALL, PAD>(acc[s], nn, s, si < nsrc && (SPEC != 1 || si != a_in), min(si, nsrc - 1), a, b, F,
+                                       H, i0, t, ai_tile, fuse_map, best_sim, best_idx, keep16, win_sim, lane, Wg, c0);
     }
 }
 
@@ -737,9 +785,9 @@ hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor
     const unsigned grid = (unsigned)blocks;
     const int ks_total = p.C / 32;                           // K-steps per token
     uint16_t* keep16 = reinterpret_cast<uint16_t*>(w.keep_bits);
-    if (spec_mode != 0) {
+    if (spec_mode != 0 && shape_uses_plain_kernel<CT, RAD>(p, p.F - 1)) {
         // the speculative path is for large inputs: the two layouts that serve those, nothing else
-        if (win_sim || !shape_uses_plain_kernel<CT, RAD>(p, p.F - 1)) return hipErrorInvalidValue;
+        if (win_sim) return hipErrorInvalidValue;
 #define TTF_LAUNCH_SPEC(KSW, NW, SPEC)                                                                            \
     k_search_mfma<CT, RAD, KSW, NW, false, 0, SPEC><<<grid, NW * 64, 0, s>>>(                                     \
         xs, w.anchor_frag, anchor_index, w.anchor_inv, fuse_map, best_sim, best_idx, keep16, nullptr, p.F, p.H, p.C, \
@@ -762,21 +810,26 @@ hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor
         // twice (measured on B4 F64 32x32 C4096 r2: 0.48-0.52 ms against 0.58-0.60 ms for one-wave
         // workgroups; for the smaller windows the split-channel kernel below is as fast or faster)
         constexpr int FWS = 1;                               // frames per wave
-        const int groups8 = (nsrc + 4 * FWS - 1) / (4 * FWS);
+        const int nsrc_plain = external_anchor ? p.F : p.F - 1;   // (the route does not depend on the pass kind)
+        const int groups8 = (nsrc_plain + 4 * FWS - 1) / (4 * FWS);
         const size_t wgs = (size_t)p.B * groups8 * (N / 32);
         constexpr int KSWS = 2;                              // K-steps per pass of the shared-anchor kernel
         if (wgs >= 2 * 256 && ks_total % KSWS == 0) {
             const size_t lds = 2 * KSWS * (size_t)S::NA * 1024;
-            auto go = [&](auto kernel) {
+            auto go = [&](auto kernel, int frames) {
+                const int groups_ = (frames + 4 * FWS - 1) / (4 * FWS);
+                const size_t wgs_ = (size_t)p.B * groups_ * (N / 32);
                 hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kernel), lds);
                 if (e != hipSuccess) return e;
-                kernel<<<(unsigned)wgs, 256, lds, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv, fuse_map,
-                                                       best_sim, best_idx, keep16, win_sim, p.F, p.H, p.C, p.t, groups8,
-                                                       p.W);
+                kernel<<<(unsigned)wgs_, 256, lds, s>>>(xs, w.anchor_frag, anchor_index, w.anchor_inv, fuse_map,
+                                                        best_sim, best_idx, keep16, win_sim, p.F, p.H, p.C, p.t, groups_,
+                                                        p.W, w.spec, w.strip_sum);
                 return hipGetLastError();
             };
-            return win_sim ? go(k_search_mfma_shared<CT, RAD, KSWS, FWS, true>)
-                           : go(k_search_mfma_shared<CT, RAD, KSWS, FWS, false>);
+            if (spec_mode == 1) return go(k_search_mfma_shared<CT, RAD, KSWS, FWS, false, false, 1>, p.F);
+            if (spec_mode == 2) return go(k_search_mfma_shared<CT, RAD, KSWS, FWS, false, false, 2>, p.F - 1);
+            return win_sim ? go(k_search_mfma_shared<CT, RAD, KSWS, FWS, true>, nsrc)
+                           : go(k_search_mfma_shared<CT, RAD, KSWS, FWS, false>, nsrc);
         }
     }
 #define TTF_LAUNCH_AS(KSW, NW, ALL)                                                                           \
@@ -856,7 +909,7 @@ hipError_t launch_padded(const ttf_params& p, const void* x, bool external_ancho
             if (e != hipSuccess) return e;
             kernel<<<(unsigned)wgs, 256, lds, s>>>(static_cast<const uint16_t*>(x), w.anchor_frag, anchor_index,
                                                    w.anchor_inv, fuse_map, best_sim, best_idx, nullptr, win_sim, p.F,
-                                                   p.H, p.C, p.t, groups, p.W);
+                                                   p.H, p.C, p.t, groups, p.W, nullptr, nullptr);
             return hipGetLastError();
         };
         const hipError_t e = win_sim ? go(k_search_mfma_shared<CT, RAD, KSWS, FWS, true, true>)
@@ -901,21 +954,10 @@ bool mfma_search_padded(const ttf_params& p)
     return !mfma_search_supported(p);
 }
 
-// True when the speculative anchor path can run this problem's search: an aligned grid served by
-// k_search_mfma.
+// True when the speculative anchor path can run this problem's search: the aligned grids.
 bool mfma_search_speculative(const ttf_params& p)
 {
-    if (!mfma_search_supported(p) || !speculation_shape(p) || p.F < 2) return false;
-#define TTF_CASE(CT, RAD) \
-    if (p.W == 16 * CT && p.r == RAD) return shape_uses_plain_kernel<CT, RAD>(p, p.F - 1)
-    TTF_CASE(1, 0);
-    TTF_CASE(1, 1);
-    TTF_CASE(1, 2);
-    TTF_CASE(2, 0);
-    TTF_CASE(2, 1);
-    TTF_CASE(2, 2);
-#undef TTF_CASE
-    return false;
+    return mfma_search_supported(p) && speculation_shape(p) && p.F >= 2;
 }
 
 hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,

@@ -66,6 +66,8 @@ SHAPES = [
     (1, 2, 16, 16, 1024, 1),     # one source frame
     (2, 33, 16, 16, 1024, 1),    # 33 frames: nine groups of four, the last with one frame
     (40, 13, 16, 16, 1024, 1),   # enough workgroups for the one-wave layout (6144 and more)
+    (2, 18, 64, 32, 1024, 2),    # 5x5 window on a large 32-wide input: the kernel with anchors shared through LDS
+    (1, 21, 128, 32, 1024, 2),   # the same kernel, 21 frames: five full groups of four and one frame
 ]
 
 
