@@ -22,7 +22,7 @@ hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool ex
                                      int32_t* best_idx, float* win_sim, int spec_mode, hipStream_t s);
 bool mfma_search_speculative(const ttf_params& p);
 
-// bf16 tokens with r <= 2 and C % 128 == 0 take the matrix-core kernels (grids exactly 16 or 32 wide
+// bf16 tokens with r <= 2 and C % 32 == 0 take the matrix-core kernels (grids exactly 16 or 32 wide
 // with whole keep words the aligned ones, every other grid the padded-tile ones); fp32 input, larger radii and other channel counts take the general
 // wave-per-token kernel.  The environment variable TTF_SEARCH=general, read once per process, forces
 // the general kernels (for comparisons).

@@ -245,7 +245,10 @@ __device__ __forceinline__ bf16x8 channel_picker(int h, int lane)
 // sums come from two extra MFMAs per source tile and K-step (channel_picker) whose accumulators add
 // the two tiles of a strip; four in-lane adds and two cross-row steps finish them.
 // SPEC 2: the plain search for the clips marked in spec[b][2] only (guess refuted); other clips exit.
-template <int CT, int RAD, int KSW, int NW, bool ALL, int FRO = 0, int SPEC = 0>
+// RAG: the K-steps need not divide over the waves and passes.  The passes are dealt to the waves in
+// contiguous runs of nearly equal length (a wave may get none); the wave that owns the end of the
+// channel axis finishes with a pass of the K-steps left over.
+template <int CT, int RAD, int KSW, int NW, bool ALL, int FRO = 0, int SPEC = 0, bool RAG = false>
 __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ anchor_frag,
     const int32_t* __restrict__ anchor_index, const float* __restrict__ anchor_inv,
@@ -294,8 +297,16 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
 
     const int y0 = i0 / W;                                   // first (or only) source row
     const int ylo = y0 - RAD;
-    const int slice = C / NW;                                // channels per wave
+    static_assert(!(RAG && SPEC != 0), "the speculative pass runs on channel counts that divide evenly");
     const int KS = C / 32;                                   // K-steps per token
+    // first K-step of this wave and how many it has.  RAG: the ceil(KS / KSW) passes are dealt to the
+    // waves as evenly as whole passes allow, so only the last wave can end on a short pass; a wave left
+    // without any starts at K-step 0, where its pointers stay inside the row (it loads nothing)
+    const int units = (KS + KSW - 1) / KSW;
+    const int kfirst = RAG ? (wave * units / NW) * KSW : wave * (KS / NW);
+    const int ks_mine = RAG ? min(KS, ((wave + 1) * units / NW) * KSW) - kfirst : KS / NW;
+    const int kbase = (RAG && ks_mine == 0) ? 0 : kfirst;
+    const int slice = (KS / NW) * 32;                        // channels per wave (even split)
     const int nsrc = (SPEC == 1 || a_in < 0) ? F : F - 1;    // frames walked per clip (>= 1 here)
 
     // source frame of slot f: the f-th walked frame of this group, the last one repeated past the end
@@ -307,7 +318,7 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
         const int si = min(grp * FR + s / 2, nsrc - 1);
         const int k = si + (si >= a_skip ? 1 : 0);
         sp[s] = x + (((size_t)b * F + k) * N + i0 + 16 * (s % 2) + (lane >> 2)) * (size_t)C +
-                wave * slice + (lane & 3) * 8;
+                kbase * 32 + (lane & 3) * 8;
     }
     const int bperm = (4 * m + g) * 4;                       // operand lane (token m, chunk g) <- load lane 4m+g
     const uint16_t* ap[NA];
@@ -316,7 +327,7 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
     for (int q = 0; q < NA; ++q) {
         const int yy = min(max(ylo + S::tile_row(q), 0), H - 1);      // rows outside the grid: clamped, masked later
         const int tile = yy * CT + S::tile_col(q);
-        ap[q] = anchor_frag + (((size_t)b * (N / 16) + tile) * KS + wave * (slice / 32)) * 512 + lane * 8;
+        ap[q] = anchor_frag + (((size_t)b * (N / 16) + tile) * KS + kbase) * 512 + lane * 8;
         ai_tile[q] = anchor_inv[(size_t)b * N + 16 * tile + m];       // requested now, used in the epilogue
     }
 
@@ -374,57 +385,64 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
         }                                                                                                     \
     } while (0)
 
-    for (int pass = 0; pass < passes; ++pass) {
-        const int ks0 = pass * KSW;
-        // Anchor fragments run PF K-steps ahead of their use in a ring of PF+1 buffers; the first
-        // PF are requested before the source loads (loads complete in issue order).
-        bf16x8 Bt[NB][NA];
-#pragma unroll
-        for (int d = 0; d < PF && d < KSW; ++d) {
-#pragma unroll
-            for (int q = 0; q < NA; ++q)
-                Bt[d][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(ap[q] + (size_t)(ks0 + d) * 512));
-        }
-        u32x4 A[NS][KSW];
-#pragma unroll
-        for (int ks = 0; ks < KSW; ++ks) {
-#pragma unroll
-            for (int s = 0; s < NS; ++s) A[s][ks] = *reinterpret_cast<const u32x4*>(sp[s] + (ks0 + ks) * 32);
-        }
-        // every source load of the pass is issued before any product (the scheduler would
-        // otherwise sink them to their uses and serialise on HBM latency)
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int ks = 0; ks < KSW; ++ks) {
-            if (ks + PF < KSW) {
-#pragma unroll
-                for (int q = 0; q < NA; ++q)
-                    Bt[(ks + PF) % NB][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(ap[q] + (size_t)(ks0 + ks + PF) * 512));
-            }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                // (fragments are kept as four plain 32-bit words: v_dot2 on elements extracted from
-                // a bit-cast vector was observed to read element 0 four times)
-                uint32_t r[4] = {A[s][ks][0], A[s][ks][1], A[s][ks][2], A[s][ks][3]};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const bf16x2 p = __builtin_bit_cast(bf16x2, r[e]);
-                    nv[s] = __builtin_amdgcn_fdot2_f32_bf16(p, p, nv[s], false);
-                }
-#pragma unroll
-                for (int e = 0; e < 4; ++e) r[e] = (uint32_t)__builtin_amdgcn_ds_bpermute(bperm, (int)r[e]);
-                const bf16x8 av = __builtin_bit_cast(bf16x8, uint4{r[0], r[1], r[2], r[3]});
-#pragma unroll
-                for (int q = 0; q < NPS; ++q)
-                    acc[s][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, Bt[ks % NB][S::pair_tile(s % 2, q)],
-                                                                        acc[s][q], 0, 0, 0);
-                if constexpr (SPEC == 1) TTF_STRIP_SUM_STEP(av, s, ks, ks0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
+    // One pass over KN_ (<= KSW) K-steps starting at this wave's K-step ks0_.  (A macro on purpose: with
+    // the body in a lambda the same code ran 10 % slower.)
+    //  * Anchor fragments run PF K-steps ahead of their use in a ring of PF+1 buffers; the first PF are
+    //    requested before the source loads (loads complete in issue order).
+    //  * Every source load of the pass is issued before any product (the scheduler would otherwise sink
+    //    them to their uses and serialise on HBM latency).
+    //  * Fragments are kept as four plain 32-bit words: v_dot2 on elements extracted from a bit-cast
+    //    vector was observed to read element 0 four times.
+#define TTF_SEARCH_PASS(KN_, ks0_)                                                                            \
+    do {                                                                                                      \
+        const int ks0 = (ks0_);                                                                               \
+        bf16x8 Bt[NB][NA];                                                                                    \
+        _Pragma("unroll") for (int d = 0; d < PF && d < (KN_); ++d) {                                         \
+            _Pragma("unroll") for (int q = 0; q < NA; ++q)                                                    \
+                Bt[d][q] = __builtin_bit_cast(bf16x8,                                                         \
+                                              *reinterpret_cast<const u32x4*>(ap[q] + (size_t)(ks0 + d) * 512)); \
+        }                                                                                                     \
+        u32x4 A[NS][(KN_)];                                                                                   \
+        _Pragma("unroll") for (int ks = 0; ks < (KN_); ++ks) {                                                \
+            _Pragma("unroll") for (int s = 0; s < NS; ++s)                                                    \
+                A[s][ks] = *reinterpret_cast<const u32x4*>(sp[s] + (ks0 + ks) * 32);                          \
+        }                                                                                                     \
+        __builtin_amdgcn_sched_barrier(0);                                                                    \
+        _Pragma("unroll") for (int ks = 0; ks < (KN_); ++ks) {                                                \
+            if (ks + PF < (KN_)) {                                                                            \
+                _Pragma("unroll") for (int q = 0; q < NA; ++q)                                                \
+                    Bt[(ks + PF) % NB][q] = __builtin_bit_cast(                                               \
+                        bf16x8, *reinterpret_cast<const u32x4*>(ap[q] + (size_t)(ks0 + ks + PF) * 512));      \
+            }                                                                                                 \
+            __builtin_amdgcn_sched_barrier(0);                                                                \
+            _Pragma("unroll") for (int s = 0; s < NS; ++s) {                                                  \
+                uint32_t r[4] = {A[s][ks][0], A[s][ks][1], A[s][ks][2], A[s][ks][3]};                         \
+                _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                               \
+                    const bf16x2 p = __builtin_bit_cast(bf16x2, r[e]);                                        \
+                    nv[s] = __builtin_amdgcn_fdot2_f32_bf16(p, p, nv[s], false);                              \
+                }                                                                                             \
+                _Pragma("unroll") for (int e = 0; e < 4; ++e)                                                 \
+                    r[e] = (uint32_t)__builtin_amdgcn_ds_bpermute(bperm, (int)r[e]);                          \
+                const bf16x8 av = __builtin_bit_cast(bf16x8, uint4{r[0], r[1], r[2], r[3]});                  \
+                _Pragma("unroll") for (int q = 0; q < NPS; ++q)                                               \
+                    acc[s][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                                      \
+                        av, Bt[ks % NB][S::pair_tile(s % 2, q)], acc[s][q], 0, 0, 0);                         \
+                if constexpr (SPEC == 1) TTF_STRIP_SUM_STEP(av, s, ks, ks0);                                  \
+            }                                                                                                 \
+            __builtin_amdgcn_sched_barrier(0);                                                                \
+        }                                                                                                     \
+    } while (0)
+
+    if constexpr (RAG) {
+        static_assert(KSW == 2, "one leftover K-step at most");
+        const int whole = ks_mine / KSW;                     // wave-uniform
+        for (int pass = 0; pass < whole; ++pass) TTF_SEARCH_PASS(KSW, pass * KSW);
+        if (ks_mine % KSW) TTF_SEARCH_PASS(1, whole * KSW);
+    } else {
+        for (int pass = 0; pass < passes; ++pass) TTF_SEARCH_PASS(KSW, pass * KSW);
     }
 
+#undef TTF_SEARCH_PASS
 #undef TTF_STRIP_SUM_STEP
 
     // squared-norm partials: lanes 4i..4i+3 hold the four chunks of token i
@@ -516,7 +534,9 @@ __device__ __forceinline__ void lds_barrier()
 // PAD: grids narrower than the tile row (Wg <= 16*CT) and of any height; see finish_tile.
 // SPEC: as for k_search_mfma (1: speculative pass -- every frame walked, strip sums written, clips
 // without a trusted guess skipped; 2: second search of the marked clips only).
-template <int CT, int RAD, int KSW, int FW, bool ALL, bool PAD = false, int SPEC = 0>
+// RAG: the K-step count need not be a multiple of KSW; the slots of the last pass beyond it read the
+// last K-step again (valid memory) with the source fragment replaced by zeros.
+template <int CT, int RAD, int KSW, int FW, bool ALL, bool PAD = false, int SPEC = 0, bool RAG = false>
 __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ anchor_frag,
     const int32_t* __restrict__ anchor_index, const float* __restrict__ anchor_inv,
@@ -524,7 +544,7 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
     uint16_t* __restrict__ keep16, float* __restrict__ win_sim, int F, int H, int C, float t, int groups, int Wg,
     const int32_t* __restrict__ spec, float* __restrict__ strip_sum)
 {
-    static_assert(SPEC == 0 || (!PAD && !ALL && CT <= 2 && KSW <= 2), "speculative pass: aligned grids only");
+    static_assert(SPEC == 0 || (!PAD && !ALL && CT <= 2 && KSW <= 2 && !RAG), "speculative pass: aligned grids only");
     using S = Shape<CT, RAD>;
     constexpr int W = S::W, NA = S::NA, NPS = S::NPS;
     constexpr int NS = 2 * FW;                               // source tiles per wave (FW frames)
@@ -568,7 +588,7 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
     const int i0 = CT == 3 ? y0 * W : tp * 32;
     const int ylo = y0 - RAD;
     const int KS = C / 32;
-    const int passes = KS / KSW;
+    const int passes = RAG ? (KS + KSW - 1) / KSW : KS / KSW;
 
     const uint16_t* sp[NS];
 #pragma unroll
@@ -593,7 +613,7 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
         const int e = wave + 4 * i, ks = e / NA, q = e % NA;
         const int yy = min(max(ylo + S::tile_row(q), 0), H - 1);
         const int tile = yy * CTt + min(max(c0 + S::tile_col(q), 0), CTt - 1);   // outside the grid: clamped, masked later
-        goff[i] = (tile * KS + ks) * 512;
+        goff[i] = RAG ? tile * KS : (tile * KS + ks) * 512;      // RAG: in K-steps, the pass's K-step is added (clamped) at the access
         gslot[i] = (ks * NA + q) * 64;
     }
 
@@ -613,14 +633,17 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
     do {                                                                                                      \
         const int pq = min((pass_), passes - 1);                                                              \
         _Pragma("unroll") for (int i = 0; i < GL; ++i)                                                        \
-            G[i] = *reinterpret_cast<const u32x4*>(gbase + goff[i] + pq * (KSW * 512));                       \
+            G[i] = *reinterpret_cast<const u32x4*>(                                                           \
+                gbase + (RAG ? (goff[i] + min(pq * KSW + (wave + 4 * i) / NA, KS - 1)) * 512                  \
+                             : goff[i] + pq * (KSW * 512)));                                                  \
     } while (0)
 #define TTF_REQUEST_SOURCE(pass_, Abuf)                                                                       \
     do {                                                                                                      \
         const int pq = min((pass_), passes - 1);                                                              \
         _Pragma("unroll") for (int ks = 0; ks < KSW; ++ks) {                                                  \
             _Pragma("unroll") for (int s = 0; s < NS; ++s)                                                    \
-                Abuf[s][ks] = *reinterpret_cast<const u32x4*>(sp[s] + (pq * KSW + ks) * 32);                  \
+                Abuf[s][ks] = *reinterpret_cast<const u32x4*>(                                                \
+                    sp[s] + (RAG ? min(pq * KSW + ks, KS - 1) : pq * KSW + ks) * 32);                         \
         }                                                                                                     \
     } while (0)
 #define TTF_STAGE(buf_)                                                                                       \
@@ -646,6 +669,11 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
                 uint32_t r[4] = {Abuf[s][ks][0], Abuf[s][ks][1], Abuf[s][ks][2], Abuf[s][ks][3]};
+                if constexpr (RAG) {                             // a slot past the last K-step adds nothing
+                    const bool real = ks0 + ks < KS;             // wave-uniform
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) r[e] = real ? r[e] : 0u;
+                }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const bf16x2 p = __builtin_bit_cast(bf16x2, r[e]);
@@ -842,6 +870,16 @@ hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor
         if (win_sim) TTF_LAUNCH_AS(KSW, NW, true); \
         else TTF_LAUNCH_AS(KSW, NW, false);   \
     } while (0)
+    // (ragged: each wave takes ceil(K-steps / NW) K-steps, in passes of KSW)
+#define TTF_LAUNCH_RAG_AS(KSW, NW, ALL)                                                                       \
+    k_search_mfma<CT, RAD, KSW, NW, ALL, 0, 0, true><<<grid, NW * 64, 0, s>>>(                                    \
+        xs, w.anchor_frag, anchor_index, w.anchor_inv, fuse_map, best_sim, best_idx, keep16, win_sim, p.F, p.H,   \
+        p.C, p.t, 0 /* passes: the waves count their own */, groups, nullptr, nullptr)
+#define TTF_LAUNCH_RAG(KSW, NW)                       \
+    do {                                              \
+        if (win_sim) TTF_LAUNCH_RAG_AS(KSW, NW, true); \
+        else TTF_LAUNCH_RAG_AS(KSW, NW, false);       \
+    } while (0)
     // With several rounds of workgroups per wave slot, one wave per workgroup walks the whole
     // channel axis (no cross-wave sum, no LDS).  With fewer, such long-running single waves
     // leave SIMDs unevenly loaded (measured: 0.24 ms against 0.20 ms on 1024 workgroups), so the
@@ -863,10 +901,13 @@ hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor
                                                                         nullptr);
     } else if (blocks >= 3 * kSimds * S::OCC && S::OCC == 1 && ks_total % 4 == 0) TTF_LAUNCH(4, 1);
     else if (blocks >= 3 * kSimds * S::OCC && ks_total % 2 == 0) TTF_LAUNCH(2, 1);
+    else if (blocks >= 3 * kSimds * S::OCC) TTF_LAUNCH_RAG(2, 1);     // odd K-step count
     else if (ks_total % 8 == 0) TTF_LAUNCH(2, 4);
-    else TTF_LAUNCH(1, 4);
+    else TTF_LAUNCH_RAG(2, 4);                                       // K-steps that do not divide into 4 waves x 2-step passes
 #undef TTF_LAUNCH
 #undef TTF_LAUNCH_AS
+#undef TTF_LAUNCH_RAG
+#undef TTF_LAUNCH_RAG_AS
     return hipGetLastError();
 }
 
@@ -912,8 +953,12 @@ hipError_t launch_padded(const ttf_params& p, const void* x, bool external_ancho
                                                    p.H, p.C, p.t, groups, p.W, nullptr, nullptr);
             return hipGetLastError();
         };
-        const hipError_t e = win_sim ? go(k_search_mfma_shared<CT, RAD, KSWS, FWS, true, true>)
-                                     : go(k_search_mfma_shared<CT, RAD, KSWS, FWS, false, true>);
+        const bool ragged = (p.C / 32) % KSWS != 0;          // odd K-step count: the variant with a guarded last pass
+        const hipError_t e =
+            ragged ? (win_sim ? go(k_search_mfma_shared<CT, RAD, KSWS, FWS, true, true, 0, true>)
+                              : go(k_search_mfma_shared<CT, RAD, KSWS, FWS, false, true, 0, true>))
+                   : (win_sim ? go(k_search_mfma_shared<CT, RAD, KSWS, FWS, true, true>)
+                              : go(k_search_mfma_shared<CT, RAD, KSWS, FWS, false, true>));
         if (e != hipSuccess) return e;
     }
     if (win_sim) return hipSuccess;                          // tied-batch mode: the tie kernel forms the keep words
@@ -933,11 +978,12 @@ hipError_t launch_pack_keep(const ttf_params& p, const int32_t* fuse_map, const 
 }
 
 // True when the matrix-core kernels cover this problem: bf16, grid width 16 or 32, radius <= 2,
-// channel count a multiple of 128 (4 wave slices of whole 32-channel K-steps), and a token count
-// per frame that is a multiple of 64 so that 64-bit keep words are whole.
+// channel count a multiple of 32 (whole K-steps; where they do not divide over waves and passes the
+// ragged variants run), and a token count per frame that is a multiple of 64 so that 64-bit keep
+// words are whole.
 bool mfma_search_supported(const ttf_params& p)
 {
-    if (p.dtype != TTF_BF16 || p.r > 2 || p.C % 128 != 0) return false;
+    if (p.dtype != TTF_BF16 || p.r > 2 || p.C % 32 != 0) return false;
     if (p.W == 16) return p.H % 4 == 0;
     if (p.W == 32) return p.H % 2 == 0;
     return false;
@@ -947,7 +993,7 @@ bool mfma_search_supported(const ttf_params& p)
 // kernels.
 bool mfma_search_padded(const ttf_params& p)
 {
-    if (p.dtype != TTF_BF16 || p.r > 2 || p.C % 128 != 0) return false;
+    if (p.dtype != TTF_BF16 || p.r > 2 || p.C % 32 != 0) return false;
     // the padded kernels index a clip's anchor fragments with 32-bit offsets
     const long long padded_tokens = (long long)p.H * ((p.W + 15) / 16) * 16;
     if (padded_tokens * p.C >= (1ll << 31)) return false;

@@ -470,6 +470,8 @@ TIED = [
     ("tiny", dict(B=2, F=4, H=5, W=13, C=129, dtype="bf16"), 3, "auto"),
     ("tiny", dict(B=1, F=4, H=6, W=6, C=64, dtype="bf16"), 1, "auto"),      # B = 1: the plain pass
     ("qwen3vl_2b", dict(B=2, F=1, C=128), 1, "auto"),                       # no source frame
+    ("qwen3vl_2b", dict(B=2, F=5, C=96), 1, "auto"),                        # 3 K-steps over four waves
+    ("qwen3vl_2b", dict(B=2, F=4, H=10, W=20, C=160), 2, "auto"),           # padded tile rows, 5 K-steps
     ("qwen3vl_2b", dict(B=3, F=4, H=14, W=14, C=128), 1, "auto"),           # 14x14: padded tile rows
     ("qwen3vl_2b", dict(B=2, F=5, H=9, W=24, C=256), 2, "auto"),
     ("qwen3vl_2b", dict(B=2, F=6, H=5, W=44, C=128), 1, 0),                 # wider than 32

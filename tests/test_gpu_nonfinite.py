@@ -22,6 +22,8 @@ PATHS = [
     ("padded tiles",        2, 4, 14, 14,  128, "bf16", 1, None),
     ("shared anchors",      2, 18, 64, 32, 128, "bf16", 2, None),
     ("speculative",         2, 6, 16, 16, 1024, "bf16", 1, 1),
+    ("ragged K-steps",      2, 5, 16, 16,   96, "bf16", 1, None),       # empty pass slots multiply zeros with anchor data
+    ("padded ragged",       2, 4, 14, 14,   96, "bf16", 2, None),
     ("general fp32",        2, 4,  6,  7,   33, "f32",  1, None),
     ("general bf16",        1, 4,  9,  9,   72, "bf16", 2, None),
     ("general tiled",       4, 33, 64, 16,  40, "f32",  1, None),

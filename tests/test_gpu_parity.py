@@ -127,9 +127,17 @@ SHAPES = [
     (1, 2, 70, 20, 1024, "bf16", 1),     # one source frame, long rows of channels (8 K-steps per pass variant not used here)
     (1, 3, 16, 16, 1024, "bf16", 1),     # fewer workgroups than CUs and C % 1024 == 0: one-frame long-pass variant
     (1, 5, 8, 32, 2048, "bf16", 2),      # the same variant on a 32-wide grid with a 5x5 window
+    # channel counts that are whole 32-channel K-steps but do not divide over four waves or two-step passes
+    (1, 4, 8, 32, 160, "bf16", 1),       # 5 K-steps: waves own 2, 2, 1 and 0 of them
+    (2, 6, 16, 16, 4000, "bf16", 1),     # 125 K-steps: 32, 32, 32, 29
+    (2, 5, 14, 14, 96, "bf16", 1),       # padded tile rows, 3 K-steps: the last pass half empty
+    (1, 4, 6, 40, 224, "bf16", 2),       # wide grid, 7 K-steps, 5x5 window
+    (1, 3, 12, 12, 32, "bf16", 2),       # a single K-step
+    (4, 33, 384, 16, 32, "bf16", 1),     # 6144 workgroups: one wave walks every K-step, odd count (1)
+    (2, 25, 128, 32, 96, "bf16", 2),     # the same on a 32-wide grid with a 5x5 window (3 K-steps)
     # general path at >= 2048 keep words: the LDS-tiled kernel (anchor halo staged per workgroup)
     (4, 33, 64, 16, 40, "f32", 1),       # fp32, one partial channel chunk
-    (4, 33, 64, 16, 72, "bf16", 2),      # bf16 with C % 128 != 0, 5x5 window
+    (4, 33, 64, 16, 72, "bf16", 2),      # bf16 with C % 32 != 0, 5x5 window
     (4, 31, 63, 17, 264, "f32", 1),      # ragged keep words, two channel chunks
     (2, 40, 90, 20, 8, "bf16", 0),       # 1x1 window, a single 16-byte piece per row
     (3, 12, 64, 64, 16, "f32", 1),       # the LDS-tiled kernel on a 64-wide grid (eight patches per grid row)
