@@ -55,7 +55,7 @@ __host__ __device__ inline int guess_segment_start(int C, int j)
 inline int guess_parts(const ttf_params& p)
 {
     const long long n = (long long)p.H * p.W;
-    return n >= 2048 ? 8 : (n >= 1024 ? 4 : (n >= 512 ? 2 : 1));
+    return n >= 2048 ? 8 : (n >= 1024 ? 4 : (n >= 256 ? 2 : 1));   // (16x16 grids: 23 -> 16 us with two)
 }
 // Shapes the speculative anchor path exists for: the aligned matrix-core search kernels (bf16, grid
 // 16 or 32 wide with whole keep words, C % 128 == 0) with at least 1024 channels, so that the guess
