@@ -114,8 +114,9 @@ ttf_status ttf_workspace_size(const ttf_params* params, size_t* bytes);
  * Errors: INVALID_ARG (NULL params/features/workspace/out or required output, a size < 1,
  * more than 2^25 tokens (frames rounded up to 64), r < 0, t not finite, anchor_index outside [-F,F) in FIXED mode, unknown
  * anchor_mode), UNSUPPORTED (unknown dtype; features, tokens_out or workspace misaligned),
- * WORKSPACE_TOO_SMALL, HIP.  Any C, grid and radius work.  Fast paths: bf16 input with
- * C % 32 == 0 and r <= 2 runs the window search on the matrix cores (any grid; grids exactly 16
+ * WORKSPACE_TOO_SMALL, HIP.  Any C, grid and radius work.  Fast paths: bf16 and fp32 input with
+ * C % 32 == 0 and r <= 2 runs the window search on the matrix cores (fp32 as three bf16 pieces
+ * per value, 24 significant bits) (any grid; grids exactly 16
  * or 32 tokens wide with H*W % 64 == 0 are the best case); rows whose byte length is a multiple
  * of 16 are read and copied with 16-byte accesses.
  */

@@ -653,6 +653,109 @@ __global__ __launch_bounds__(512) void k_anchor_prepare(const uint16_t* __restri
     }
 }
 
+// The three bf16 pieces of two fp32 values, each pair packed into one 32-bit word: hi = bf16(v),
+// mid = bf16(v - hi), lo = bf16(v - hi - mid), round to nearest even.  Both subtractions are exact in
+// fp32, so hi + mid + lo carries 24 significant bits of v.
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+__device__ __forceinline__ void split_bf16x3(float a, float b, uint32_t& hi, uint32_t& mid, uint32_t& lo)
+{
+    hi = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2));
+    const float ra = a - __builtin_bit_cast(float, hi << 16), rb = b - __builtin_bit_cast(float, hi & 0xffff0000u);
+    mid = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{ra, rb}, bf16x2));
+    const float sa = ra - __builtin_bit_cast(float, mid << 16), sb = rb - __builtin_bit_cast(float, mid & 0xffff0000u);
+    lo = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{sa, sb}, bf16x2));
+}
+
+// Matrix-core path for fp32 tokens.  As k_anchor_prepare, but the anchor frame is stored as three
+// bf16 planes (hi, mid, lo pieces of every value) per tile and K-step of 32 channels:
+// anchor_frag[b][tile][K-step][plane][lane][8 bf16], 3 KiB per tile and K-step.  Inside a K-step the
+// operand lane (token n, group g) holds channels 4g..4g+3 and 16+4g..16+4g+3: the order in which two
+// coalesced 16-byte loads per lane (lane l: token l/4, floats 4(l%4).. of each 64-byte half) arrive
+// after one lane permutation.  The search splits and orders its source fragments the same way.
+template <bool PAD>
+__global__ __launch_bounds__(512) void k_anchor_prepare_f32(const float* __restrict__ x,
+                                                            const float* __restrict__ ext_anchor,
+                                                            const double* __restrict__ score_part,
+                                                            const double* __restrict__ clip_part,
+                                                            int32_t* __restrict__ anchor_index,
+                                                            float* __restrict__ anchor_inv,
+                                                            uint16_t* __restrict__ anchor_frag,
+                                                            int32_t* __restrict__ fuse_map,
+                                                            float* __restrict__ best_sim,
+                                                            int32_t* __restrict__ best_idx,
+                                                            uint16_t* __restrict__ keep16, int F, int N, int C, int S,
+                                                            int fixed_anchor, int tiles, int Wg, int CT)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int b = blockIdx.x / tiles, tile = blockIdx.x % tiles;
+    const int a = ext_anchor ? -1
+                : fixed_anchor >= 0 ? fixed_anchor
+                : fixed_anchor == kAnchorGiven ? anchor_index[b]
+                                               : pick_anchor(score_part, clip_part, b, F, S, lane);
+    if (fixed_anchor != kAnchorGiven && tile == 0 && threadIdx.x == 0) anchor_index[b] = a;
+    const int first = PAD ? (tile / CT) * Wg + 16 * (tile % CT) : 16 * tile;
+    const int ncol = PAD ? min(16, Wg - 16 * (tile % CT)) : 16;
+    if (a >= 0 && fuse_map && (int)threadIdx.x < ncol) {     // anchor tokens are always retained
+        const size_t o = ((size_t)b * F + a) * N + first + threadIdx.x;
+        fuse_map[o] = -1;
+        if (best_sim) best_sim[o] = 1.0f;
+        if (best_idx) best_idx[o] = first + (int)threadIdx.x;
+        if (!PAD && threadIdx.x == 0) keep16[o / 16] = 0xffffu;
+    }
+    const int KS = C / 32;
+    const float* frame = ext_anchor ? ext_anchor + (size_t)b * N * C : x + ((size_t)b * F + a) * N * C;
+    const bool real = (lane >> 2) < ncol;                    // this lane's token exists (padding reads the tile's first)
+    const float* src = frame + (size_t)(first + (real ? lane >> 2 : 0)) * C + (lane & 3) * 4;
+    uint16_t* dst = anchor_frag + ((size_t)b * tiles + tile) * (size_t)KS * 1536 + lane * 8;
+    const int bperm = (4 * (lane & 15) + (lane >> 4)) * 4;
+    float nn = 0.f;
+    constexpr int UN = 4;                                   // K-steps in flight per wave
+    for (int k0 = wave; k0 < KS; k0 += 8 * UN) {
+        uint4 v[UN][2];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int ks = k0 + 8 * u;
+            if (ks < KS) {
+                v[u][0] = *reinterpret_cast<const uint4*>(src + (size_t)ks * 32);
+                v[u][1] = *reinterpret_cast<const uint4*>(src + (size_t)ks * 32 + 16);
+                if (PAD && !real) v[u][0] = v[u][1] = uint4{0u, 0u, 0u, 0u};
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int ks = k0 + 8 * u;
+            if (ks < KS) {
+                uint32_t r[8] = {v[u][0].x, v[u][0].y, v[u][0].z, v[u][0].w, v[u][1].x, v[u][1].y, v[u][1].z, v[u][1].w};
+                float f[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float t = __builtin_bit_cast(float, r[e]);
+                    nn = fmaf(t, t, nn);
+                    f[e] = __builtin_bit_cast(float, (uint32_t)__builtin_amdgcn_ds_bpermute(bperm, (int)r[e]));
+                }
+                uint32_t hi[4], mid[4], lo[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) split_bf16x3(f[2 * e], f[2 * e + 1], hi[e], mid[e], lo[e]);
+                uint16_t* o = dst + (size_t)ks * 1536;
+                *reinterpret_cast<uint4*>(o) = uint4{hi[0], hi[1], hi[2], hi[3]};
+                *reinterpret_cast<uint4*>(o + 512) = uint4{mid[0], mid[1], mid[2], mid[3]};
+                *reinterpret_cast<uint4*>(o + 1024) = uint4{lo[0], lo[1], lo[2], lo[3]};
+            }
+        }
+    }
+    nn += __shfl_xor(nn, 1, 64);
+    nn += __shfl_xor(nn, 2, 64);
+    __shared__ float part[8][16];
+    if ((lane & 3) == 0) part[wave][lane >> 2] = nn;
+    __syncthreads();
+    if (threadIdx.x < 16) {
+        float ss = part[0][threadIdx.x];
+#pragma unroll
+        for (int w = 1; w < 8; ++w) ss += part[w][threadIdx.x];
+        anchor_inv[((size_t)b * tiles + tile) * 16 + threadIdx.x] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+    }
+}
+
 template <typename F>
 hipError_t by_layout(const ttf_params& p, F&& f)
 {
@@ -769,6 +872,26 @@ hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const 
         return hipGetLastError();
     };
     return pad ? go(k_anchor_prepare<true>) : go(k_anchor_prepare<false>);
+}
+
+hipError_t launch_anchor_prepare_mfma_f32(const ttf_params& p, const void* x, const void* ext_anchor,
+                                          const Workspace& w, int32_t* anchor_index, int32_t* fuse_map,
+                                          float* best_sim, int32_t* best_idx, bool anchor_given, hipStream_t s)
+{
+    const int N = p.H * p.W;
+    const int fixed = anchor_given ? kAnchorGiven : fixed_frame(p);
+    const bool pad = !mfma_f32_aligned(p);
+    const int CT = (p.W + 15) / 16;                          // column tiles per grid row
+    const int tiles = pad ? p.H * CT : N / 16;
+    auto go = [&](auto kernel) {
+        kernel<<<(unsigned)(p.B * tiles), 512, 0, s>>>(static_cast<const float*>(x), static_cast<const float*>(ext_anchor),
+                                                       w.score_part, w.clip_part, anchor_index, w.anchor_inv,
+                                                       w.anchor_frag, fuse_map, best_sim, best_idx,
+                                                       reinterpret_cast<uint16_t*>(w.keep_bits), p.F, N, p.C,
+                                                       (p.C + 255) / 256, fixed, tiles, p.W, CT);
+        return hipGetLastError();
+    };
+    return pad ? go(k_anchor_prepare_f32<true>) : go(k_anchor_prepare_f32<false>);
 }
 
 }  // namespace ttf

@@ -21,10 +21,13 @@ hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool ex
                                      const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                      int32_t* best_idx, float* win_sim, int spec_mode, hipStream_t s);
 bool mfma_search_speculative(const ttf_params& p);
+hipError_t launch_window_search_mfma_f32(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,
+                                         const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
+                                         int32_t* best_idx, float* win_sim, hipStream_t s);
 
-// bf16 tokens with r <= 2 and C % 32 == 0 take the matrix-core kernels (grids exactly 16 or 32 wide
-// with whole keep words the aligned ones, every other grid the padded-tile ones); fp32 input, larger radii and other channel counts take the general
-// wave-per-token kernel.  The environment variable TTF_SEARCH=general, read once per process, forces
+// bf16 and fp32 tokens with r <= 2 and C % 32 == 0 take the matrix-core kernels (grids exactly 16 or 32
+// wide with whole keep words the aligned ones, every other grid the padded-tile ones); larger radii and
+// other channel counts take the general wave-per-token kernel.  The environment variable TTF_SEARCH=general, read once per process, forces
 // the general kernels (for comparisons).
 bool use_mfma_path(const ttf_params& p)
 {
@@ -32,16 +35,32 @@ bool use_mfma_path(const ttf_params& p)
         const char* force = std::getenv("TTF_SEARCH");
         return force && std::strcmp(force, "general") == 0;
     }();
-    return !general && (mfma_search_supported(p) || mfma_search_padded(p));
+    return !general && (mfma_search_supported(p) || mfma_search_padded(p) || mfma_search_f32_supported(p));
+}
+
+// Anchor preparation of the matrix-core path for the element type at hand (fp32: three bf16 planes).
+hipError_t launch_anchor_prepare_any(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
+                                     int32_t* anchor_index, int32_t* fuse_map, float* best_sim, int32_t* best_idx,
+                                     bool anchor_given, int spec_mode, hipStream_t s)
+{
+    if (p.dtype == TTF_F32)
+        return launch_anchor_prepare_mfma_f32(p, x, ext_anchor, w, anchor_index, fuse_map, best_sim, best_idx,
+                                              anchor_given, s);
+    return launch_anchor_prepare_mfma(p, x, ext_anchor, w, anchor_index, fuse_map, best_sim, best_idx, anchor_given,
+                                      spec_mode, s);
 }
 
 hipError_t launch_window_search(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                 const int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                 int32_t* best_idx, float* win_sim, hipStream_t s)
 {
-    if (use_mfma_path(p))
+    if (use_mfma_path(p)) {
+        if (p.dtype == TTF_F32)
+            return launch_window_search_mfma_f32(p, x, ext_anchor != nullptr, w, anchor_index, fuse_map, best_sim,
+                                                 best_idx, win_sim, s);
         return launch_window_search_mfma(p, x, ext_anchor != nullptr, w, anchor_index, fuse_map, best_sim, best_idx,
                                          win_sim, 0, s);
+    }
     return launch_window_search_generic(p, x, ext_anchor, w, anchor_index, fuse_map, best_sim, best_idx, win_sim, s);
 }
 
@@ -172,8 +191,8 @@ static ttf_status run_pass(const ttf_params* params, const void* features, const
     if (pick && !spec) TTF_STEP(launch_anchor_scores(p, w, false, s));
     mark();
     if (use_mfma_path(p))
-        TTF_STEP(launch_anchor_prepare_mfma(p, features, ext_anchor, w, out->anchor_index, out->fuse_map,
-                                            out->best_sim, out->best_idx, false, spec ? 1 : 0, s));
+        TTF_STEP(launch_anchor_prepare_any(p, features, ext_anchor, w, out->anchor_index, out->fuse_map,
+                                           out->best_sim, out->best_idx, false, spec ? 1 : 0, s));
     else TTF_STEP(launch_anchor_norms(p, features, ext_anchor, w, out->anchor_index, false, s));
     mark();
     if (spec)
@@ -307,8 +326,8 @@ ttf_status ttf_compress_tied(const ttf_params* params, const void* features, voi
     }
     TTF_STEP(launch_tied_anchor(p, w, out->anchor_index, s));
     if (use_mfma_path(p))
-        TTF_STEP(launch_anchor_prepare_mfma(p, features, nullptr, w, out->anchor_index, nullptr, nullptr, nullptr,
-                                            true, 0, s));
+        TTF_STEP(launch_anchor_prepare_any(p, features, nullptr, w, out->anchor_index, nullptr, nullptr, nullptr,
+                                           true, 0, s));
     else TTF_STEP(launch_anchor_norms(p, features, nullptr, w, out->anchor_index, true, s));
     TTF_STEP(launch_window_search(p, features, nullptr, w, out->anchor_index, nullptr, nullptr, nullptr,
                                   tw.win_sim, s));

@@ -21,6 +21,10 @@ constexpr size_t kMaxBlocks256 = (1u << 24) - 1;
 // Lets `kernel` use `bytes` of dynamic LDS.  The limit is a property of the function on a device, so it
 // is raised once (per function, device and size reached) and not on every launch.
 hipError_t allow_dynamic_lds(const void* kernel, size_t bytes);
+// fp32 tokens on the matrix cores (ttf_search_mfma_f32.hip): can this problem take them; is its grid one
+// whose keep words the search writes itself (exactly 16 or 32 wide, whole 64-token words)
+bool mfma_search_f32_supported(const ttf_params& p);
+bool mfma_f32_aligned(const ttf_params& p);
 
 // Device scratch carved out of the caller's workspace.  All sections are 256-byte aligned.
 struct Workspace {
@@ -77,7 +81,9 @@ inline Workspace carve(const ttf_params& p, void* base)
     const size_t o_sp = take(B * S * F * 2 * sizeof(double));
     const size_t o_cp = take(B * S * sizeof(double));
     const size_t o_ai = take(B * NP * sizeof(float));
-    const size_t o_af = take(p.dtype == TTF_BF16 ? B * NP * C * sizeof(uint16_t) : 0);
+    // anchor frame in fragment order: bf16 as is, fp32 as three bf16 planes (where the matrix-core path can run)
+    const size_t o_af = take(p.dtype == TTF_BF16 ? B * NP * C * sizeof(uint16_t)
+                                                 : (C % 32 == 0 ? 3 * B * NP * C * sizeof(uint16_t) : 0));
     const size_t o_kb = take(B * F * NW * sizeof(uint64_t));
     const size_t o_fb = take(B * F * sizeof(int32_t));
     const size_t o_sr = take(B * F * N * sizeof(int32_t));
@@ -127,6 +133,10 @@ hipError_t launch_anchor_norms(const ttf_params& p, const void* x, const void* e
 hipError_t launch_anchor_prepare_mfma(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
                                       int32_t* anchor_index, int32_t* fuse_map, float* best_sim,
                                       int32_t* best_idx, bool anchor_given, int spec_mode, hipStream_t s);
+// The same for fp32 tokens: the anchor frame as three bf16 planes per tile and K-step (no speculative modes).
+hipError_t launch_anchor_prepare_mfma_f32(const ttf_params& p, const void* x, const void* ext_anchor,
+                                          const Workspace& w, int32_t* anchor_index, int32_t* fuse_map,
+                                          float* best_sim, int32_t* best_idx, bool anchor_given, hipStream_t s);
 bool mfma_search_supported(const ttf_params& p);   // grids exactly 16 or 32 wide with whole keep words
 bool mfma_search_padded(const ttf_params& p);      // every other grid (tile rows padded to 16 columns)
 hipError_t launch_window_search(const ttf_params& p, const void* x, const void* ext_anchor, const Workspace& w,
