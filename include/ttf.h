@@ -294,6 +294,19 @@ int ttf_last_hip_error(void);
 ttf_status ttf_set_speculation(int mode);
 
 /*
+ * Which window-search kernels a problem takes (Section 3, "Pointwise Matching with Local Window
+ * Search"): a host-side query, no GPU work.  Results never depend on the route, only the time does.
+ *   params  host; checked as in ttf_compress.
+ *   route   host, out: one of the TTF_ROUTE_* values.
+ * Errors: INVALID_ARG (NULL pointer, bad params), UNSUPPORTED (unknown dtype).
+ */
+#define TTF_ROUTE_GENERAL      0   /* wave-per-token kernels (any C, any radius) */
+#define TTF_ROUTE_MFMA_BF16    1   /* matrix cores, bf16, grid exactly 16 or 32 wide with whole keep words */
+#define TTF_ROUTE_MFMA_BF16_PADDED 2   /* matrix cores, bf16, any other grid (tile rows padded to 16 columns) */
+#define TTF_ROUTE_MFMA_F32     3   /* matrix cores, fp32 as three bf16 pieces per value, any grid */
+ttf_status ttf_search_route(const ttf_params* params, int* route);
+
+/*
  * Per-stage timing, for benchmarks.  Stages, in launch order:
  *   0 frame sums (speculative route: over the guess channels only)   1 anchor scores (two-pass
  *     route only)   2 anchor choice + norms   3 window search + gate

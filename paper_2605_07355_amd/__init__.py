@@ -28,6 +28,7 @@ from .binding import (  # noqa: F401
     ttf_select_threshold,
     ttf_regate,
     ttf_set_speculation,
+    ttf_search_route,
     ttf_profile_enable,
     ttf_profile_read,
 )

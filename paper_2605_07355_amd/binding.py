@@ -84,6 +84,8 @@ def load_library() -> ctypes.CDLL:
         lib.ttf_regate.restype = ctypes.c_int
         lib.ttf_regate.argtypes = [ctypes.POINTER(_Params), vp, vp, vp, ctypes.c_size_t,
                                    ctypes.POINTER(_Outputs), vp]
+        lib.ttf_search_route.restype = ctypes.c_int
+        lib.ttf_search_route.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int)]
         lib.ttf_set_speculation.restype = ctypes.c_int
         lib.ttf_set_speculation.argtypes = [ctypes.c_int]
         lib.ttf_status_string.restype = ctypes.c_char_p
@@ -438,6 +440,18 @@ def ttf_regate(features: torch.Tensor, out: TTFOutput, thresholds: Optional[torc
         _check(load_library().ttf_regate(ctypes.byref(p), features.data_ptr(), _ptr(thresholds), ws_ptr, ws_bytes,
                                          ctypes.byref(o), _stream_ptr(stream, features.device)))
     return out
+
+
+ROUTE_NAMES = {0: "general", 1: "mfma_bf16", 2: "mfma_bf16_padded", 3: "mfma_f32"}
+
+
+def ttf_search_route(B: int, F: int, H: int, W: int, C: int, dtype: torch.dtype = torch.bfloat16,
+                     r: int = 1, t: float = 0.7, anchor: Union[str, int] = "auto") -> str:
+    """Name of the window-search kernels this problem takes (see ROUTE_NAMES); host-side query."""
+    p = _make_params(B, F, H, W, C, _dtype_code(dtype), r, t, anchor)
+    route = ctypes.c_int(-1)
+    _check(load_library().ttf_search_route(ctypes.byref(p), ctypes.byref(route)))
+    return ROUTE_NAMES[int(route.value)]
 
 
 def ttf_set_speculation(mode: int) -> None:

@@ -441,6 +441,19 @@ ttf_status ttf_regate(const ttf_params* params, const void* features, const floa
     return TTF_OK;
 }
 
+ttf_status ttf_search_route(const ttf_params* params, int* route)
+{
+    if (!route) return TTF_ERR_INVALID_ARG;
+    const ttf_status st = check_params(params);
+    if (st != TTF_OK) return st;
+    const ttf_params& p = *params;
+    *route = !use_mfma_path(p)              ? TTF_ROUTE_GENERAL
+           : p.dtype == TTF_F32             ? TTF_ROUTE_MFMA_F32
+           : mfma_search_supported(p)       ? TTF_ROUTE_MFMA_BF16
+                                            : TTF_ROUTE_MFMA_BF16_PADDED;
+    return TTF_OK;
+}
+
 ttf_status ttf_set_speculation(int mode)
 {
     if (mode < -1 || mode > 1) return TTF_ERR_INVALID_ARG;

@@ -24,6 +24,8 @@
 #include "ttf_internal.h"
 #include "ttf_search_tile.h"
 
+#include <algorithm>
+
 namespace ttf {
 namespace {
 
@@ -147,48 +149,67 @@ __global__ __launch_bounds__(256, (Shape<CT, RAD>::NA * 6 > 80 ? 1 : 2)) void k_
             if (wave + 4 * i < NFR) frag_lds[(buf_) * (NFR * 64) + gslot[i] + lane] = G[i];                   \
     } while (0)
 
+    // The LDS round trips of a pass (lane permutations, anchor planes) are requested ahead of the
+    // arithmetic that hides them: with two waves per SIMD nothing else covers an exposed LDS wait.
     auto compute = [&](int buf, const u32x4 (&Abuf)[NS][2]) {
-        bf16x8 ah[NS], am[NS], al[NS];                       // source tiles in operand order, three pieces
+        const u32x4* fr = frag_lds + buf * (NFR * 64) + lane;
+        // phase 1: squared norms, and every lane permutation of the pass in flight at once
+        uint32_t f[NS][8];
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            uint32_t r[8] = {Abuf[s][0][0], Abuf[s][0][1], Abuf[s][0][2], Abuf[s][0][3],
-                             Abuf[s][1][0], Abuf[s][1][1], Abuf[s][1][2], Abuf[s][1][3]};
-            float f[8];
+            const uint32_t r[8] = {Abuf[s][0][0], Abuf[s][0][1], Abuf[s][0][2], Abuf[s][0][3],
+                                   Abuf[s][1][0], Abuf[s][1][1], Abuf[s][1][2], Abuf[s][1][3]};
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float v = __builtin_bit_cast(float, r[e]);
                 nv[s] = fmaf(v, v, nv[s]);
-                f[e] = __builtin_bit_cast(float, (uint32_t)__builtin_amdgcn_ds_bpermute(bperm, (int)r[e]));
+                f[s][e] = (uint32_t)__builtin_amdgcn_ds_bpermute(bperm, (int)r[e]);
             }
+        }
+        u32x4 bq[2][3];                                      // anchor planes of the current and the next tile
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl) bq[0][pl] = fr[pl * 64];
+        __builtin_amdgcn_sched_barrier(0);
+        // phase 2: the three bf16 pieces of every source tile, in operand order
+        bf16x8 ah[NS], am[NS], al[NS];
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
             uint32_t hi[4], mid[4], lo[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) split_bf16x3(f[2 * e], f[2 * e + 1], hi[e], mid[e], lo[e]);
+            for (int e = 0; e < 4; ++e)
+                split_bf16x3(__builtin_bit_cast(float, f[s][2 * e]), __builtin_bit_cast(float, f[s][2 * e + 1]), hi[e],
+                             mid[e], lo[e]);
             ah[s] = __builtin_bit_cast(bf16x8, uint4{hi[0], hi[1], hi[2], hi[3]});
             am[s] = __builtin_bit_cast(bf16x8, uint4{mid[0], mid[1], mid[2], mid[3]});
             al[s] = __builtin_bit_cast(bf16x8, uint4{lo[0], lo[1], lo[2], lo[3]});
         }
-        // one anchor tile at a time from LDS, used by every source tile paired with it
+        __builtin_amdgcn_sched_barrier(0);
+        // phase 3: one anchor tile at a time, the next tile's planes requested before this tile's products
 #pragma unroll
         for (int qa = 0; qa < NA; ++qa) {
-            const u32x4* fr = frag_lds + buf * (NFR * 64) + qa * 3 * 64 + lane;
-            const bf16x8 bh = __builtin_bit_cast(bf16x8, fr[0]);
-            const bf16x8 bm = __builtin_bit_cast(bf16x8, fr[64]);
-            const bf16x8 bl = __builtin_bit_cast(bf16x8, fr[128]);
+            if (qa + 1 < NA) {
 #pragma unroll
-            for (int s = 0; s < NS; ++s) {
+                for (int pl = 0; pl < 3; ++pl) bq[(qa + 1) & 1][pl] = fr[((qa + 1) * 3 + pl) * 64];
+            }
+            const bf16x8 bh = __builtin_bit_cast(bf16x8, bq[qa & 1][0]);
+            const bf16x8 bm = __builtin_bit_cast(bf16x8, bq[qa & 1][1]);
+            const bf16x8 bl = __builtin_bit_cast(bf16x8, bq[qa & 1][2]);
+            // the six piece products, smallest first; term by term over every accumulator that uses this
+            // anchor tile, so that consecutive MFMAs do not wait for each other's result
 #pragma unroll
-                for (int q = 0; q < NPS; ++q) {                  // the pair (if any) of this source tile that uses tile qa
-                    if (S::pair_tile(s % 2, q) == qa) {
-                        f32x4 c = acc[s][q];                     // smallest terms first
-                        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[s], bh, c, 0, 0, 0);
-                        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[s], bl, c, 0, 0, 0);
-                        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(am[s], bm, c, 0, 0, 0);
-                        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(am[s], bh, c, 0, 0, 0);
-                        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[s], bm, c, 0, 0, 0);
-                        acc[s][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[s], bh, c, 0, 0, 0);
+            for (int term = 0; term < 6; ++term) {
+                const bf16x8 bb = term == 0 ? bh : (term == 1 ? bl : (term == 2 ? bm : (term == 3 ? bh : (term == 4 ? bm : bh))));
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    const bf16x8 aa = term == 0 ? al[s] : (term == 2 || term == 3 ? am[s] : ah[s]);
+#pragma unroll
+                    for (int q = 0; q < NPS; ++q) {              // the pair (if any) of this source tile that uses tile qa
+                        if (S::pair_tile(s % 2, q) == qa)
+                            acc[s][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aa, bb, acc[s][q], 0, 0, 0);
                     }
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
@@ -287,13 +308,21 @@ bool mfma_f32_aligned(const ttf_params& p)
     return (p.W == 16 && p.H % 4 == 0) || (p.W == 32 && p.H % 2 == 0);
 }
 
-// True when the matrix-core kernels for fp32 tokens cover this problem: radius <= 2, whole 32-channel
-// K-steps, and a clip's anchor planes within 32-bit reach of the staging offsets.
+// True when the matrix-core kernels for fp32 tokens take this problem: radius <= 2, whole 32-channel
+// K-steps, and enough workgroups.  A workgroup walks the channel axis one K-step per pass (about 1.6 us
+// each on an idle chip), so a handful of them is slower than the wave-per-token kernels, which spread
+// the same tokens over hundreds of waves (measured: B1 F16 16x16 C2048, 16 workgroups, 0.104 against
+// 0.033 ms; B4 F16 16x16 C1024, 64 workgroups, 0.059 against 0.069 ms).
 bool mfma_search_f32_supported(const ttf_params& p)
 {
     if (p.dtype != TTF_F32 || p.r > 2 || p.C % 32 != 0) return false;
-    const long long padded_tokens = (long long)p.H * ((p.W + 15) / 16) * 16;
-    return padded_tokens * p.C * 3 < (1ll << 40);
+    const int ct = p.W <= 16 ? 1 : (p.W <= 32 ? 2 : 3);
+    const int nps = (ct == 1 ? 1 : ct) * (2 * p.r + 1);              // anchor tiles paired with a source tile
+    const int frames_per_wg = nps <= 3 ? 8 : 4;
+    const long long groups = (std::max(p.F - 1, 1) + frames_per_wg - 1) / frames_per_wg;
+    const long long strips = mfma_f32_aligned(p) ? (long long)p.H * p.W / 32
+                           : ct == 1 ? (p.H + 1) / 2 : (ct == 2 ? p.H : (long long)p.H * (((p.W + 15) / 16 + 1) / 2));
+    return (long long)p.B * groups * strips >= 48;
 }
 
 hipError_t launch_window_search_mfma_f32(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,

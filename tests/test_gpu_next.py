@@ -467,8 +467,8 @@ TIED = [
     ("highres_wide", dict(B=2, F=4, H=8, C=128), 2, "auto"),                # 32-wide grid
     ("highres_wide", dict(B=2, F=3, H=4, C=128), 1, -1),
     ("tiny", dict(B=3, F=5, H=7, W=9, C=40, dtype="f32"), 1, "auto"),       # general kernels
-    ("qwen3vl_2b", dict(B=3, F=5, C=128, dtype="f32"), 1, "auto"),          # fp32 on the matrix cores
-    ("qwen3vl_2b", dict(B=2, F=4, H=9, W=24, C=64, dtype="f32"), 2, "auto"),   # fp32, padded tile rows
+    ("qwen3vl_2b", dict(B=6, F=5, C=128, dtype="f32"), 1, "auto"),          # fp32 on the matrix cores
+    ("qwen3vl_2b", dict(B=6, F=4, H=9, W=24, C=64, dtype="f32"), 2, "auto"),   # fp32, padded tile rows
     ("tiny", dict(B=2, F=4, H=5, W=13, C=129, dtype="bf16"), 3, "auto"),
     ("tiny", dict(B=1, F=4, H=6, W=6, C=64, dtype="bf16"), 1, "auto"),      # B = 1: the plain pass
     ("qwen3vl_2b", dict(B=2, F=1, C=128), 1, "auto"),                       # no source frame

@@ -24,8 +24,8 @@ PATHS = [
     ("speculative",         2, 6, 16, 16, 1024, "bf16", 1, 1),
     ("ragged K-steps",      2, 5, 16, 16,   96, "bf16", 1, None),       # empty pass slots multiply zeros with anchor data
     ("padded ragged",       2, 4, 14, 14,   96, "bf16", 2, None),
-    ("matrix cores fp32",   2, 5, 16, 16,  128, "f32",  1, None),       # a non-finite value makes its split pieces NaN
-    ("padded fp32",         2, 4, 14, 14,   64, "f32",  2, None),
+    ("matrix cores fp32",   6, 5, 16, 16,  128, "f32",  1, None),       # a non-finite value makes its split pieces NaN
+    ("padded fp32",         7, 4, 14, 14,   64, "f32",  2, None),
     ("general fp32",        2, 4,  6,  7,   33, "f32",  1, None),
     ("general bf16",        1, 4,  9,  9,   72, "bf16", 2, None),
     ("general tiled",       4, 33, 64, 16,  40, "f32",  1, None),

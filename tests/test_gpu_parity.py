@@ -80,6 +80,26 @@ def test_highres_wide_config():
 
 
 # ----------------------------------------------------------------- shapes that span tiles and ragged tails
+F32_MFMA_SHAPES = [
+    # fp32 tokens with whole 32-channel K-steps: matrix cores on three bf16 pieces per value (batch sizes
+    # chosen so that the search has at least 48 workgroups: smaller problems take the general kernels)
+    (6, 6, 16, 16, 256, "f32", 1),       # aligned 16-wide grid, two frames per wave
+    (6, 5, 16, 16, 128, "f32", 2),       # 5x5 window: one frame per wave
+    (6, 6, 16, 16, 96, "f32", 0),        # 1x1 window, 3 K-steps (one full round of the 3-deep pipeline)
+    (6, 2, 16, 16, 32, "f32", 1),        # a single K-step and a single source frame
+    (6, 3, 16, 16, 64, "f32", 1),        # two K-steps
+    (6, 1, 16, 16, 128, "f32", 1),       # no source frame
+    (3, 7, 8, 32, 128, "f32", 1),        # 32-wide grid
+    (2, 4, 32, 32, 64, "f32", 2),        # 32-wide, 5x5 window
+    (2, 18, 64, 32, 128, "f32", 2),      # 17 source frames: 4 full groups of 4 and one with a single frame
+    (7, 6, 14, 14, 128, "f32", 1),       # padded tile rows
+    (4, 4, 15, 20, 64, "f32", 2),        # odd height, second column tile partly empty
+    (3, 5, 9, 40, 128, "f32", 1),        # wider than 32
+    (4, 4, 6, 48, 32, "f32", 2),         # wide grid, 5x5 window: one workgroup per CU
+    (3, 3, 4, 100, 64, "f32", 0),        # 7 column tiles
+    (6, 6, 16, 16, 4096, "f32", 1),      # the full channel count (128 K-steps)
+]
+
 SHAPES = [
     # B, F, H,  W,  C,   dtype,  r
     (2, 3, 5, 7, 40, "f32", 1),          # N=35 < one 64-token word, C multiple of 4 only
@@ -135,22 +155,6 @@ SHAPES = [
     (1, 3, 12, 12, 32, "bf16", 2),       # a single K-step
     (4, 33, 384, 16, 32, "bf16", 1),     # 6144 workgroups: one wave walks every K-step, odd count (1)
     (2, 25, 128, 32, 96, "bf16", 2),     # the same on a 32-wide grid with a 5x5 window (3 K-steps)
-    # fp32 tokens with whole 32-channel K-steps: matrix cores on three bf16 pieces per value
-    (1, 6, 16, 16, 256, "f32", 1),       # aligned 16-wide grid, two frames per wave
-    (2, 5, 16, 16, 128, "f32", 2),       # 5x5 window: one frame per wave
-    (1, 6, 16, 16, 96, "f32", 0),        # 1x1 window, 3 K-steps (one full round of the 3-deep pipeline)
-    (1, 2, 16, 16, 32, "f32", 1),        # a single K-step and a single source frame
-    (1, 3, 16, 16, 64, "f32", 1),        # two K-steps
-    (2, 1, 16, 16, 128, "f32", 1),       # no source frame
-    (2, 7, 8, 32, 128, "f32", 1),        # 32-wide grid
-    (1, 4, 32, 32, 64, "f32", 2),        # 32-wide, 5x5 window
-    (2, 18, 64, 32, 128, "f32", 2),      # 17 source frames: 4 full groups of 4 and one with a single frame
-    (2, 6, 14, 14, 128, "f32", 1),       # padded tile rows
-    (2, 4, 15, 20, 64, "f32", 2),        # odd height, second column tile partly empty
-    (1, 5, 9, 40, 128, "f32", 1),        # wider than 32
-    (2, 4, 6, 48, 32, "f32", 2),         # wide grid, 5x5 window: one workgroup per CU
-    (1, 3, 4, 100, 64, "f32", 0),        # 7 column tiles
-    (2, 6, 16, 16, 4096, "f32", 1),      # the full channel count (128 K-steps)
     # general path at >= 2048 keep words: the LDS-tiled kernel (anchor halo staged per workgroup)
     (4, 33, 64, 16, 40, "f32", 1),       # fp32, one partial channel chunk
     (4, 33, 64, 16, 72, "bf16", 2),      # bf16 with C % 32 != 0, 5x5 window
@@ -164,7 +168,7 @@ SHAPES = [
     (2, 4, 5, 7, 1536, "f32", 1),        # 6 KiB fp32 rows, N = 35: one ragged keep word, general path
     (1, 3, 9, 9, 3072, "bf16", 1),       # 6 KiB bf16 rows on padded tile rows
     (2, 3, 3, 70, 1540, "f32", 2),       # rows that are not a whole number of 256-piece rounds (385 pieces)
-]
+] + F32_MFMA_SHAPES
 
 
 @pytest.mark.parametrize("B,F,H,W,C,dtype,r", SHAPES)
@@ -330,8 +334,8 @@ GRAPH_CASES = [
     ("aligned matrix cores",     2, 6, 16, 16,  256, "bf16", 1, None),
     ("padded tile rows",         2, 6, 14, 14,  128, "bf16", 1, None),       # dynamic LDS, k_pack_keep
     ("5x5 shared anchors",       2, 18, 64, 32, 128, "bf16", 2, None),       # dynamic LDS
-    ("fp32 matrix cores",        2, 6, 16, 16,  128, "f32",  1, None),       # dynamic LDS
-    ("fp32 padded tile rows",    2, 5, 14, 14,   64, "f32",  2, None),       # dynamic LDS, k_pack_keep
+    ("fp32 matrix cores",        6, 6, 16, 16,  128, "f32",  1, None),       # dynamic LDS
+    ("fp32 padded tile rows",    7, 5, 14, 14,   64, "f32",  2, None),       # dynamic LDS, k_pack_keep
     ("general LDS-tiled",        4, 33, 64, 16,  40, "f32",  1, None),       # dynamic LDS
     ("speculative anchor route", 2, 6, 16, 16, 1024, "bf16", 1, 1),
 ]

@@ -63,6 +63,37 @@ def test_workspace_size_and_argument_checks():
     assert e.value.status == 1
 
 
+def test_search_routes():
+    """Host-side route query: which window-search kernels a problem takes.  The GPU parity cases that
+    are meant for the matrix-core kernels must really be sent there."""
+    import torch
+    import paper_2605_07355_amd as ttf
+    bf, f32 = torch.bfloat16, torch.float32
+    route = ttf.ttf_search_route
+    assert route(16, 32, 16, 16, 4096, bf, r=1) == "mfma_bf16"
+    assert route(4, 64, 32, 32, 4096, bf, r=2) == "mfma_bf16"
+    assert route(2, 6, 16, 16, 4000, bf, r=1) == "mfma_bf16"              # whole K-steps, ragged passes
+    assert route(2, 6, 14, 14, 128, bf, r=1) == "mfma_bf16_padded"
+    assert route(1, 9, 3, 200, 32, bf, r=1) == "mfma_bf16_padded"
+    assert route(4, 33, 64, 16, 72, bf, r=2) == "general"                 # C % 32 != 0
+    assert route(1, 3, 32, 16, 128, bf, r=3) == "general"                 # radius beyond 5x5
+    assert route(16, 32, 16, 16, 4096, f32, r=1) == "mfma_f32"
+    assert route(1, 4, 8, 8, 256, f32, r=1) == "general"                  # a handful of workgroups only
+    assert route(4, 33, 64, 16, 40, f32, r=1) == "general"
+    from test_gpu_parity import F32_MFMA_SHAPES, GRAPH_CASES
+    from test_gpu_nonfinite import PATHS
+    assert len(F32_MFMA_SHAPES) >= 15
+    for B, F, H, W, C, dtype, r in F32_MFMA_SHAPES:
+        assert route(B, F, H, W, C, f32, r=r) == "mfma_f32", (B, F, H, W, C, r)
+    for name, B, F, H, W, C, dtype, r, spec in list(GRAPH_CASES) + list(PATHS):
+        if "fp32" in name and "general" not in name:
+            assert route(B, F, H, W, C, f32, r=r) == "mfma_f32", name
+        if name.startswith("general"):
+            assert route(B, F, H, W, C, f32 if dtype == "f32" else bf, r=r) == "general", name
+    with pytest.raises(ttf.TTFError):
+        route(0, 4, 8, 8, 64, bf)
+
+
 def test_compress_rejects_null_pointers_without_a_gpu():
     """Validation happens before any HIP call, so these return an error code on any machine."""
     import paper_2605_07355_amd as ttf
