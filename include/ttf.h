@@ -287,7 +287,8 @@ int ttf_last_hip_error(void);
  *                 was wrong).
  *                 Available for bf16 input on grids 16 or 32 wide with H*W % 64 == 0, C % 128 == 0,
  *                 C >= 1024, r <= 2, F >= 2, automatic anchor.
- * mode  0 (default): speculative for inputs of 256 MiB and more where available, else two-pass;
+ * mode  0 (default): speculative for inputs of 256 MiB and more in clips of at most 128 frames
+ *       where available, else two-pass;
  *       1: speculative wherever available;  -1: always two-pass.
  * Process-wide; takes effect for calls made after it returns.  INVALID_ARG for other values.
  */

@@ -83,9 +83,13 @@ namespace {
 
 thread_local int g_last_hip_error = 0;
 
-// Speculative anchor: -1 never, 0 for inputs of at least kSpeculationMinBytes, 1 whenever the shape allows.
+// Speculative anchor: -1 never, 0 for inputs of at least kSpeculationMinBytes in clips of at most
+// kSpeculationMaxFrames frames, 1 whenever the shape allows.  (Long clips: the more frames, the closer the
+// best two anchor scores; at 256 frames no guess of the synthetic workloads clears the trust gap, every
+// clip falls back to the two-pass kernels and the guess costs 0.05 ms for nothing.)
 std::atomic<int> g_speculation{0};
 constexpr unsigned long long kSpeculationMinBytes = 256ull << 20;
+constexpr int kSpeculationMaxFrames = 128;
 
 // Event sets for stage timing: `slots` sets of TTF_NUM_STAGES+1 events, used round-robin by
 // successive profiled calls so that a benchmark can time many calls and read them afterwards.
@@ -182,7 +186,8 @@ static ttf_status run_pass(const ttf_params* params, const void* features, const
     const int spec_pref = g_speculation.load(std::memory_order_relaxed);
     const unsigned long long in_bytes = (unsigned long long)p.B * p.F * p.H * p.W * p.C * 2ull;
     const bool spec = pick && use_mfma_path(p) && mfma_search_speculative(p) &&
-                      (spec_pref > 0 || (spec_pref == 0 && in_bytes >= kSpeculationMinBytes));
+                      (spec_pref > 0 ||
+                       (spec_pref == 0 && in_bytes >= kSpeculationMinBytes && p.F <= kSpeculationMaxFrames));
 
     mark();                                                    // start of stage 0
     if (spec) TTF_STEP(launch_guess_sums(p, features, w, s));
