@@ -98,16 +98,17 @@ def compare_with_oracle(x_np, buf, ref, row_stride=1):
     return bad
 
 
-def run_workload(name, t, steps, warmup, dev, with_oracle=True, row_stride=1):
-    """Generate `name`, enforce the decision margins with the oracle (outside any timing), time
-    `steps` calls at threshold t, and compare the last call's outputs with the oracle."""
+def run_workload(name, t, steps, warmup, dev, with_oracle=True, row_stride=1, cfg=None):
+    """Generate `name` (or the given variant of a configuration), enforce the decision margins with the
+    oracle (outside any timing), time `steps` calls at threshold t, and compare the last call's outputs
+    with the oracle."""
     import numpy as np
     import torch
 
     import paper_2605_07355_amd as ttf
     from workloads import CONFIGS, make_clip_batch
 
-    cfg = CONFIGS[name]
+    cfg = cfg if cfg is not None else CONFIGS[name]
     r = cfg.r
     batch = make_clip_batch(cfg)
     ref = None
@@ -203,6 +204,7 @@ def summary(rec):
     dom_ms = rec["stage_ms"][dom]
     out = {
         "shape": f"B{cfg.B} F{cfg.F} {cfg.H}x{cfg.W} C{cfg.C} {cfg.dtype} r{cfg.r}", "t": rec["t"],
+        "search_route": search_route(cfg),
         "steps": rec["steps"], "ms_per_call": round(ms, 4), "ms_per_call_event_median": round(rec["median_ms"], 4),
         "GTok_per_s": round(tokens / (ms * 1e-3) / 1e9, 5),
         "kappa": round(rec["kappa"], 4), "fused_fraction": round(rec["fused_fraction"], 4),
@@ -219,6 +221,14 @@ def summary(rec):
         out["note"] = ("the same tensor every call and small enough for the 256 MiB Infinity Cache: "
                        "cache-resident run, no bandwidth claim")
     return out
+
+
+def search_route(cfg):
+    """Which window-search kernels the library sends this configuration to."""
+    import torch
+    import paper_2605_07355_amd as ttf
+    dtype = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    return ttf.ttf_search_route(cfg.B, cfg.F, cfg.H, cfg.W, cfg.C, dtype, r=cfg.r)
 
 
 def both_roofs(rec):
@@ -444,6 +454,20 @@ def main() -> int:
                 del rec
                 torch.cuda.empty_cache()
 
+    # inputs outside the five configurations: the headline shape with fp32 tokens, with a channel count
+    # that is not a multiple of 128, and on a grid that is not 16 wide (same oracle comparison)
+    other_inputs = None
+    if not args.no_workloads:
+        other_inputs = {}
+        base = CONFIGS["qwen3vl_8b_batched"]
+        for key, variant in (("fp32_tokens", base.scaled(dtype="f32")), ("C4000", base.scaled(C=4000)),
+                             ("grid_14x14", base.scaled(H=14, W=14))):
+            rec = run_workload(key, variant.t[0], min(steps, 10), min(warmup, 3), dev, with_oracle=oracle_on,
+                               row_stride=7, cfg=variant)
+            other_inputs[key] = summary(rec)
+            del rec
+            torch.cuda.empty_cache()
+
     line = {
         "metric": "ttf_visual_tokens_per_sec", "value": round(gtok_s, 5), "unit": "GTok/s",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 4),
@@ -455,7 +479,7 @@ def main() -> int:
                              + ("; the same tensor every step and small enough for the 256 MiB Infinity Cache "
                                 "(cache-resident run: no bandwidth claim)" if tokens * row_bytes <= (192 << 20) else "")},
         "roofline": roofline, "path": path, "cpu_baseline": cpu_baseline, "extensions": extensions,
-        "workloads": workloads,
+        "workloads": workloads, "other_inputs": other_inputs,
         "context": "paper reports ~67% of tokens removed at t=0.70 and ~0.16 GFLOPs matching cost on an "
                    "A100 40GB; no timing of the pass itself",
     }

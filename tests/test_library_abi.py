@@ -90,6 +90,11 @@ def test_search_routes():
             assert route(B, F, H, W, C, f32, r=r) == "mfma_f32", name
         if name.startswith("general"):
             assert route(B, F, H, W, C, f32 if dtype == "f32" else bf, r=r) == "general", name
+    # the padded bf16 kernels index a clip's anchor fragments with 32-bit offsets: a grid whose padded
+    # frame holds 2^31 elements or more must not reach them
+    assert route(1, 2, 1000, 1001, 2048, bf, r=1) == "mfma_bf16_padded"    # 1000 x 1008 x 2048 < 2^31
+    assert route(1, 2, 1000, 1001, 4096, bf, r=1) == "general"             # 1000 x 1008 x 4096 >= 2^31
+    assert route(1, 2, 1000, 1001, 4096, f32, r=1) == "mfma_f32"           # 64-bit offsets there
     with pytest.raises(ttf.TTFError):
         route(0, 4, 8, 8, 64, bf)
 
