@@ -447,7 +447,7 @@ def main() -> int:
                 if name == args.workload and wt == t:
                     workloads[key] = head_summary
                     continue
-                rec = run_workload(name, wt, min(steps, 10), min(warmup, 3), dev, with_oracle=oracle_on, row_stride=7)
+                rec = run_workload(name, wt, min(steps, 20), min(warmup, 5), dev, with_oracle=oracle_on, row_stride=7)
                 workloads[key] = summary(rec)
                 if wcfg.r >= 2:
                     workloads[key]["window_search_roofs"] = both_roofs(rec)
@@ -462,7 +462,7 @@ def main() -> int:
         base = CONFIGS["qwen3vl_8b_batched"]
         for key, variant in (("fp32_tokens", base.scaled(dtype="f32")), ("C4000", base.scaled(C=4000)),
                              ("grid_14x14", base.scaled(H=14, W=14))):
-            rec = run_workload(key, variant.t[0], min(steps, 10), min(warmup, 3), dev, with_oracle=oracle_on,
+            rec = run_workload(key, variant.t[0], min(steps, 20), min(warmup, 5), dev, with_oracle=oracle_on,
                                row_stride=7, cfg=variant)
             other_inputs[key] = summary(rec)
             del rec

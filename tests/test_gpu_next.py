@@ -37,6 +37,7 @@ SMALL = [
     ("tiny", dict(B=2, F=4, H=5, W=13, C=129, dtype="bf16")),          # odd row length (2-byte copies)
     ("tiny", dict(B=2, F=4, H=5, W=7, C=1540, dtype="f32")),           # long rows: one block per token, 385 pieces
     ("qwen3vl_2b", dict(B=1, F=4, H=6, W=16, C=1024)),                 # 2 KiB rows: 128-thread blocks in restoration
+    ("qwen3vl_2b", dict(B=6, F=5, C=128, dtype="f32")),                # fp32 tokens on the matrix cores
 ]
 
 
@@ -326,6 +327,8 @@ SEGMENTS = [
     ("qwen3vl_2b", dict(B=1, F=4, H=9, W=24, C=256), 2),
     ("qwen3vl_2b", dict(B=1, F=6, H=7, W=44, C=128), 1),               # wider than 32
     ("tiny", dict(B=2, F=4, H=5, W=7, C=1540, dtype="f32"), 1),        # long rows: one block per token
+    ("qwen3vl_2b", dict(B=6, F=6, C=128, dtype="f32"), 1),             # fp32 on the matrix cores, external anchor
+    ("qwen3vl_2b", dict(B=7, F=5, H=14, W=14, C=64, dtype="f32"), 2),  # the same on padded tile rows, 5x5 window
 ]
 
 
