@@ -285,8 +285,8 @@ int ttf_last_hip_error(void);
  *                 exact rule in every case; only the time differs (one pass over the input instead
  *                 of two when the guesses hold, one extra search for a clip whose trusted guess
  *                 was wrong).
- *                 Available for bf16 input on grids 16 or 32 wide with H*W % 64 == 0, C % 128 == 0,
- *                 C >= 1024, r <= 2, F >= 2, automatic anchor.
+ *                 Available for bf16 input on grids 12..16 or 24..32 tokens wide (any height),
+ *                 C % 128 == 0, C >= 1024, r <= 2, F >= 2, automatic anchor.
  * mode  0 (default): speculative for inputs of 256 MiB and more in clips of at most 128 frames
  *       where available, else two-pass;
  *       1: speculative wherever available;  -1: always two-pass.

@@ -41,7 +41,7 @@ struct Workspace {
     float*    guess_sum;     // [B,F,P,kGuessChannels] frame sums over the guess channels only, in P = guess_parts()
                              // shares (one per run of tokens)
     int32_t*  spec;          // [B,4]    guessed anchor, guess trusted (1/0), second search needed (1/0), unused
-    float*    strip_sum;     // [B,F,N/32,C] sum of every 32-token strip of every frame, written by the search
+    float*    strip_sum;     // [B,F,spec_strips(),C] sum of every 32-cell strip of every frame, written by the search
     size_t    bytes;
 };
 
@@ -61,13 +61,22 @@ inline int guess_parts(const ttf_params& p)
     const long long n = (long long)p.H * p.W;
     return n >= 2048 ? 8 : (n >= 1024 ? 4 : (n >= 256 ? 2 : 1));   // (16x16 grids: 23 -> 16 us with two)
 }
-// Shapes the speculative anchor path exists for: the aligned matrix-core search kernels (bf16, grid
-// 16 or 32 wide with whole keep words, C % 128 == 0) with at least 1024 channels, so that the guess
-// channels are a small part of a row.  The radius is not looked at (the workspace must not depend on it).
+// Shapes the speculative anchor path exists for: the matrix-core search kernels on grids up to 32 tokens
+// wide whose rows fill at least three quarters of their 16-column tiles (12..16 or 24..32 wide: the
+// strip sums are stored per padded strip), bf16, C % 128 == 0 and at least 1024 channels, so that the
+// guess channels are a small part of a row.  The radius is not looked at (the workspace must not depend
+// on it).
 inline bool speculation_shape(const ttf_params& p)
 {
     if (p.dtype != TTF_BF16 || p.C % 128 != 0 || p.C < 1024 || p.F < 2) return false;
-    return (p.W == 16 && p.H % 4 == 0) || (p.W == 32 && p.H % 2 == 0);
+    return (p.W >= 12 && p.W <= 16) || (p.W >= 24 && p.W <= 32);
+}
+// 32-cell strips per frame as the matrix-core search cuts them (grids up to 32 wide): aligned grids N/32;
+// padded tile rows: two grid rows per strip up to 16 columns, one row per strip beyond.
+inline int spec_strips(const ttf_params& p)
+{
+    const bool aligned = (p.W == 16 && p.H % 4 == 0) || (p.W == 32 && p.H % 2 == 0);
+    return aligned ? p.H * p.W / 32 : (p.W <= 16 ? (p.H + 1) / 2 : p.H);
 }
 
 inline Workspace carve(const ttf_params& p, void* base)
@@ -90,7 +99,7 @@ inline Workspace carve(const ttf_params& p, void* base)
     const bool spec = speculation_shape(p);
     const size_t o_gs = take(spec ? B * F * guess_parts(p) * kGuessChannels * sizeof(float) : 0);
     const size_t o_sp2 = take(spec ? B * 4 * sizeof(int32_t) : 0);
-    const size_t o_ss = take(spec ? B * F * (N / 32) * C * sizeof(float) : 0);
+    const size_t o_ss = take(spec ? B * F * (size_t)spec_strips(p) * C * sizeof(float) : 0);
     char* c = static_cast<char*>(base);
     Workspace w;
     w.frame_sum   = reinterpret_cast<float*>(c + o_fs);

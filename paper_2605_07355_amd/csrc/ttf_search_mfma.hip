@@ -357,7 +357,7 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
     uint16_t* __restrict__ keep16, float* __restrict__ win_sim, int F, int H, int C, float t, int groups, int Wg,
     const int32_t* __restrict__ spec, float* __restrict__ strip_sum)
 {
-    static_assert(SPEC == 0 || (!PAD && !ALL && CT <= 2 && KSW <= 2 && !RAG), "speculative pass: aligned grids only");
+    static_assert(SPEC == 0 || (!ALL && CT <= 2 && KSW <= 2 && !RAG), "speculative pass: grids up to 32 wide");
     using S = Shape<CT, RAD>;
     constexpr int W = S::W, NA = S::NA, NPS = S::NPS;
     constexpr int NS = 2 * FW;                               // source tiles per wave (FW frames)
@@ -469,11 +469,22 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
     bf16x8 pick0, pick1;
     float* sums = nullptr;
     float held[FW];
+    bool pad_cell[2] = {false, false};                       // PAD: operand lane m of tile kind u holds a padding cell
     if constexpr (SPEC == 1) {
         pick0 = channel_picker(0, lane);
         pick1 = channel_picker(1, lane);
         const int k0 = min(grp * FRG + wave * FW, F - 1);
         sums = strip_sum + ((((size_t)b * F + k0) * tpf + tp) * (size_t)C) + (KSW == 2 ? lane : (lane & 31));
+        if constexpr (PAD) {
+            // padding cells were pointed at a real token (their results are dropped); in the strip sums
+            // they must count as zero
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int ys = y0 + (CT == 1 ? u : 0);
+                const int xs = (CT == 1 ? 0 : 16 * (c0 + u)) + m;
+                pad_cell[u] = ys >= H || xs >= Wg;
+            }
+        }
     }
     auto compute = [&](int buf, const u32x4 (&Abuf)[NS][KSW], int ks0) {
 #pragma unroll
@@ -494,6 +505,10 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
                 }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) r[e] = (uint32_t)__builtin_amdgcn_ds_bpermute(bperm, (int)r[e]);
+                if constexpr (PAD && SPEC == 1) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) r[e] = pad_cell[s % 2] ? 0u : r[e];
+                }
                 av[s] = __builtin_bit_cast(bf16x8, uint4{r[0], r[1], r[2], r[3]});
             }
             // one anchor tile at a time from LDS, used by every source tile paired with it
@@ -746,10 +761,10 @@ __global__ __launch_bounds__(256) void k_pack_keep(const int32_t* __restrict__ f
 template <int CT, int RAD>
 hipError_t launch_padded(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,
                          const int32_t* anchor_index, int32_t* fuse_map, float* best_sim, int32_t* best_idx,
-                         float* win_sim, hipStream_t s)
+                         float* win_sim, int spec_mode, hipStream_t s)
 {
     using S = Shape<CT, RAD>;
-    const int nsrc = external_anchor ? p.F : p.F - 1;
+    const int nsrc = (external_anchor || spec_mode == 1) ? p.F : p.F - 1;   // frames walked per clip
     const int N = p.H * p.W, NW = (N + 63) / 64;
     const size_t words = (size_t)p.B * p.F * NW;
     if (nsrc >= 1) {
@@ -763,10 +778,25 @@ hipError_t launch_padded(const ttf_params& p, const void* x, bool external_ancho
             if (e != hipSuccess) return e;
             kernel<<<(unsigned)wgs, 256, lds, s>>>(static_cast<const uint16_t*>(x), w.anchor_frag, anchor_index,
                                                    w.anchor_inv, fuse_map, best_sim, best_idx, nullptr, win_sim, p.F,
-                                                   p.H, p.C, p.t, groups, p.W, nullptr, nullptr);
+                                                   p.H, p.C, p.t, groups, p.W, w.spec, w.strip_sum);
             return hipGetLastError();
         };
         const bool ragged = (p.C / 32) % KSWS != 0;          // odd K-step count: the variant with a guarded last pass
+        if constexpr (CT <= 2) {
+            // speculative pass (every frame walked, strip sums written; the keep words are packed after the
+            // last search of the call), and the second search of the clips it leaves
+            if (spec_mode == 1) return (win_sim || ragged) ? hipErrorInvalidValue
+                                                           : go(k_search_mfma_shared<CT, RAD, KSWS, FWS, false, true, 1>);
+            if (spec_mode == 2) {
+                if (win_sim || ragged) return hipErrorInvalidValue;
+                const hipError_t e2 = go(k_search_mfma_shared<CT, RAD, KSWS, FWS, false, true, 2>);
+                if (e2 != hipSuccess) return e2;
+                k_pack_keep<<<(unsigned)((words + 3) / 4), 256, 0, s>>>(fuse_map, anchor_index, w.keep_bits, p.F, N, NW,
+                                                                        words);
+                return hipGetLastError();
+            }
+        }
+        if (spec_mode != 0) return hipErrorInvalidValue;
         const hipError_t e =
             ragged ? (win_sim ? go(k_search_mfma_shared<CT, RAD, KSWS, FWS, true, true, 0, true>)
                               : go(k_search_mfma_shared<CT, RAD, KSWS, FWS, false, true, 0, true>))
@@ -813,10 +843,11 @@ bool mfma_search_padded(const ttf_params& p)
     return !mfma_search_supported(p);
 }
 
-// True when the speculative anchor path can run this problem's search: the aligned grids.
+// True when the speculative anchor path can run this problem's search: matrix-core kernels on grids up
+// to 32 wide.
 bool mfma_search_speculative(const ttf_params& p)
 {
-    return mfma_search_supported(p) && speculation_shape(p) && p.F >= 2;
+    return (mfma_search_supported(p) || mfma_search_padded(p)) && speculation_shape(p) && p.F >= 2;
 }
 
 hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool external_anchor, const Workspace& w,
@@ -824,11 +855,11 @@ hipError_t launch_window_search_mfma(const ttf_params& p, const void* x, bool ex
                                      int32_t* best_idx, float* win_sim, int spec_mode, hipStream_t s)
 {
     if (mfma_search_padded(p)) {
-        if (spec_mode != 0) return hipErrorInvalidValue;
         const int ct = p.W <= 16 ? 1 : (p.W <= 32 ? 2 : 3);
 #define TTF_PCASE(CT, RAD)                              \
     if (ct == CT && p.r == RAD)                         \
-    return launch_padded<CT, RAD>(p, x, external_anchor, w, anchor_index, fuse_map, best_sim, best_idx, win_sim, s)
+    return launch_padded<CT, RAD>(p, x, external_anchor, w, anchor_index, fuse_map, best_sim, best_idx, win_sim, \
+                                  spec_mode, s)
         TTF_PCASE(1, 0);
         TTF_PCASE(1, 1);
         TTF_PCASE(1, 2);

@@ -22,6 +22,7 @@ PATHS = [
     ("padded tiles",        2, 4, 14, 14,  128, "bf16", 1, None),
     ("shared anchors",      2, 18, 64, 32, 128, "bf16", 2, None),
     ("speculative",         2, 6, 16, 16, 1024, "bf16", 1, 1),
+    ("padded speculative",  2, 6, 14, 14, 1024, "bf16", 1, 1),
     ("ragged K-steps",      2, 5, 16, 16,   96, "bf16", 1, None),       # empty pass slots multiply zeros with anchor data
     ("padded ragged",       2, 4, 14, 14,   96, "bf16", 2, None),
     ("matrix cores fp32",   6, 5, 16, 16,  128, "f32",  1, None),       # a non-finite value makes its split pieces NaN

@@ -338,6 +338,7 @@ GRAPH_CASES = [
     ("fp32 padded tile rows",    7, 5, 14, 14,   64, "f32",  2, None),       # dynamic LDS, k_pack_keep
     ("general LDS-tiled",        4, 33, 64, 16,  40, "f32",  1, None),       # dynamic LDS
     ("speculative anchor route", 2, 6, 16, 16, 1024, "bf16", 1, 1),
+    ("speculative, padded rows", 2, 6, 14, 14, 1024, "bf16", 1, 1),           # k_pack_keep after the second search
 ]
 
 

@@ -68,6 +68,15 @@ SHAPES = [
     (40, 13, 16, 16, 1024, 1),   # enough workgroups for the one-wave layout (6144 and more)
     (2, 18, 64, 32, 1024, 2),    # 5x5 window on a large 32-wide input: the kernel with anchors shared through LDS
     (1, 21, 128, 32, 1024, 2),   # the same kernel, 21 frames: five full groups of four and one frame
+    # grids that are not exactly 16 or 32 wide, or whose height leaves partial strips: padded tile rows
+    # (padding cells must not count in the strip sums)
+    (2, 6, 14, 14, 1024, 1),     # 14x14: two columns of padding per row, two frames per wave
+    (2, 11, 14, 14, 1024, 2),    # 5x5 window, ten source frames: three groups of four frames
+    (1, 7, 13, 16, 1024, 1),     # 16 wide, odd height: the last strip has one real row
+    (2, 6, 9, 24, 1024, 1),      # 24 wide: the second column tile half empty
+    (1, 7, 11, 31, 2048, 2),     # 31 wide, 5x5 window
+    (2, 6, 12, 12, 1152, 0),     # 1x1 window, 36 K-steps
+    (1, 10, 40, 30, 1024, 1),    # 40 strips per frame: the streaming strip reduction ahead of the scores
 ]
 
 
@@ -101,6 +110,13 @@ def test_refuted_guess_is_searched_again():
     assert res.anchor_index[0] == batch.clean_frame[0, 0]
 
 
+def test_refuted_guess_on_a_padded_grid():
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=2, F=8, H=14, W=14, C=2048)
+    batch = _with_foreign_guess_channels(cfg, seed=4150)
+    res = _check(batch, cfg, ["refuted", "confirmed"])
+    assert res.anchor_index[0] == batch.clean_frame[0, 0]
+
+
 def test_unclear_guess_takes_the_two_pass_route():
     # every frame as noisy as the others: no frame stands out, neither to the guess nor to the full rule
     cfg = CONFIGS["qwen3vl_2b"].scaled(B=2, F=8, C=1024, clean_sigma=1.0)
@@ -108,8 +124,9 @@ def test_unclear_guess_takes_the_two_pass_route():
     _check(batch, cfg, ["fallback", "fallback"])
 
 
-def test_all_three_kinds_in_one_batch():
-    cfg = CONFIGS["qwen3vl_2b"].scaled(B=4, F=10, C=2048)
+@pytest.mark.parametrize("H,W", [(16, 16), (9, 24)])
+def test_all_three_kinds_in_one_batch(H, W):
+    cfg = CONFIGS["qwen3vl_2b"].scaled(B=4, F=10, H=H, W=W, C=2048)
     batch = _with_foreign_guess_channels(cfg, seed=4300)
     flat = make_clip_batch(cfg.scaled(clean_sigma=1.0), seed=4300)
     batch.x[2] = flat.x[2]
