@@ -285,8 +285,9 @@ int ttf_last_hip_error(void);
  *                 exact rule in every case; only the time differs (one pass over the input instead
  *                 of two when the guesses hold, one extra search for a clip whose trusted guess
  *                 was wrong).
- *                 Available for bf16 input on grids 12..16 or 24..32 tokens wide (any height),
- *                 C % 128 == 0, C >= 1024, r <= 2, F >= 2, automatic anchor.
+ *                 Available for bf16 input on grids whose rows fill at least 70 % of the 32-cell
+ *                 strips the search cuts them into (12..16, 23..32, 45..64, ... columns; any
+ *                 height), C % 128 == 0, C >= 1024, r <= 2, F >= 2, automatic anchor.
  * mode  0 (default): speculative for inputs of 256 MiB and more in clips of at most 128 frames
  *       where available, else two-pass;
  *       1: speculative wherever available;  -1: always two-pass.

@@ -797,7 +797,7 @@ hipError_t launch_anchor_scores(const ttf_params& p, const Workspace& w, bool mi
     int FG = 1;
     while (FG < 16 && (size_t)S * p.B * FG < 512 && p.F >= 64 * FG) FG *= 2;
     const unsigned grid = (unsigned)((size_t)S * p.B * FG);
-    const int strips = spec_strips(p);
+    const int strips = (int)spec_strips(p);
     if (mixed && strips > 8) {
         k_reduce_strips<<<dim3((unsigned)(p.B * p.F), (unsigned)((p.C + 1023) / 1024)), 256, 0, s>>>(
             w.strip_sum, w.frame_sum, w.spec, p.F, p.C, strips);

@@ -61,22 +61,23 @@ inline int guess_parts(const ttf_params& p)
     const long long n = (long long)p.H * p.W;
     return n >= 2048 ? 8 : (n >= 1024 ? 4 : (n >= 256 ? 2 : 1));   // (16x16 grids: 23 -> 16 us with two)
 }
-// Shapes the speculative anchor path exists for: the matrix-core search kernels on grids up to 32 tokens
-// wide whose rows fill at least three quarters of their 16-column tiles (12..16 or 24..32 wide: the
-// strip sums are stored per padded strip), bf16, C % 128 == 0 and at least 1024 channels, so that the
-// guess channels are a small part of a row.  The radius is not looked at (the workspace must not depend
-// on it).
+// 32-cell strips per frame as the matrix-core search cuts them: aligned grids N/32; padded tile rows: two
+// grid rows per strip up to 16 columns, one row per strip up to 32, ceil(column tiles / 2) per row beyond.
+inline long long spec_strips(const ttf_params& p)
+{
+    const bool aligned = (p.W == 16 && p.H % 4 == 0) || (p.W == 32 && p.H % 2 == 0);
+    if (aligned) return (long long)p.H * p.W / 32;
+    if (p.W <= 16) return (p.H + 1) / 2;
+    return (long long)p.H * (((p.W + 15) / 16 + 1) / 2);
+}
+// Shapes the speculative anchor path exists for: the matrix-core search kernels (bf16, C % 128 == 0) on
+// grids whose tokens fill at least 70 % of the padded 32-cell strips (the strip sums are stored per
+// padded strip: 12..16, 23..32, 45..64 columns, ...), with at least 1024 channels, so that the guess
+// channels are a small part of a row.  The radius is not looked at (the workspace must not depend on it).
 inline bool speculation_shape(const ttf_params& p)
 {
     if (p.dtype != TTF_BF16 || p.C % 128 != 0 || p.C < 1024 || p.F < 2) return false;
-    return (p.W >= 12 && p.W <= 16) || (p.W >= 24 && p.W <= 32);
-}
-// 32-cell strips per frame as the matrix-core search cuts them (grids up to 32 wide): aligned grids N/32;
-// padded tile rows: two grid rows per strip up to 16 columns, one row per strip beyond.
-inline int spec_strips(const ttf_params& p)
-{
-    const bool aligned = (p.W == 16 && p.H % 4 == 0) || (p.W == 32 && p.H % 2 == 0);
-    return aligned ? p.H * p.W / 32 : (p.W <= 16 ? (p.H + 1) / 2 : p.H);
+    return 10ll * p.H * p.W >= 7ll * 32 * spec_strips(p);
 }
 
 inline Workspace carve(const ttf_params& p, void* base)

@@ -357,7 +357,7 @@ __global__ __launch_bounds__(256, 2) void k_search_mfma_shared(
     uint16_t* __restrict__ keep16, float* __restrict__ win_sim, int F, int H, int C, float t, int groups, int Wg,
     const int32_t* __restrict__ spec, float* __restrict__ strip_sum)
 {
-    static_assert(SPEC == 0 || (!ALL && CT <= 2 && KSW <= 2 && !RAG), "speculative pass: grids up to 32 wide");
+    static_assert(SPEC == 0 || (!ALL && KSW <= 2 && !RAG), "speculative pass: plain outputs, whole passes");
     using S = Shape<CT, RAD>;
     constexpr int W = S::W, NA = S::NA, NPS = S::NPS;
     constexpr int NS = 2 * FW;                               // source tiles per wave (FW frames)
@@ -782,7 +782,7 @@ hipError_t launch_padded(const ttf_params& p, const void* x, bool external_ancho
             return hipGetLastError();
         };
         const bool ragged = (p.C / 32) % KSWS != 0;          // odd K-step count: the variant with a guarded last pass
-        if constexpr (CT <= 2) {
+        {
             // speculative pass (every frame walked, strip sums written; the keep words are packed after the
             // last search of the call), and the second search of the clips it leaves
             if (spec_mode == 1) return (win_sim || ragged) ? hipErrorInvalidValue
@@ -843,8 +843,7 @@ bool mfma_search_padded(const ttf_params& p)
     return !mfma_search_supported(p);
 }
 
-// True when the speculative anchor path can run this problem's search: matrix-core kernels on grids up
-// to 32 wide.
+// True when the speculative anchor path can run this problem's search.
 bool mfma_search_speculative(const ttf_params& p)
 {
     return (mfma_search_supported(p) || mfma_search_padded(p)) && speculation_shape(p) && p.F >= 2;

@@ -77,6 +77,11 @@ SHAPES = [
     (1, 7, 11, 31, 2048, 2),     # 31 wide, 5x5 window
     (2, 6, 12, 12, 1152, 0),     # 1x1 window, 36 K-steps
     (1, 10, 40, 30, 1024, 1),    # 40 strips per frame: the streaming strip reduction ahead of the scores
+    # wider than 32: strips of 32 columns with the neighbouring column tiles on both sides
+    (1, 6, 9, 48, 1024, 1),      # three column tiles: the second strip of a row is half padding
+    (2, 5, 6, 64, 1024, 2),      # whole tiles, 5x5 window
+    (1, 7, 5, 100, 2048, 0),     # seven column tiles, 1x1 window
+    (1, 6, 7, 45, 1024, 1),      # the emptiest rows the route takes (45 of 64 strip cells)
 ]
 
 
