@@ -118,7 +118,9 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
 
     const int y0 = i0 / W;                                   // first (or only) source row
     const int ylo = y0 - RAD;
-    static_assert(!(RAG && SPEC != 0), "the speculative pass runs on channel counts that divide evenly");
+    // (speculative pass: C % 128 == 0, so the K-step count is even and a ragged split only hands the waves
+    // different numbers of whole two-step passes; the one-step pass below never runs there)
+    static_assert(!(RAG && SPEC == 1) || KSW == 2, "strip sums are stored per pair of K-steps");
     const int KS = C / 32;                                   // K-steps per token
     // first K-step of this wave and how many it has.  RAG: the ceil(KS / KSW) passes are dealt to the
     // waves as evenly as whole passes allow, so only the last wave can end on a short pass; a wave left
@@ -127,7 +129,6 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
     const int kfirst = RAG ? (wave * units / NW) * KSW : wave * (KS / NW);
     const int ks_mine = RAG ? min(KS, ((wave + 1) * units / NW) * KSW) - kfirst : KS / NW;
     const int kbase = (RAG && ks_mine == 0) ? 0 : kfirst;
-    const int slice = (KS / NW) * 32;                        // channels per wave (even split)
     const int nsrc = (SPEC == 1 || a_in < 0) ? F : F - 1;    // frames walked per clip (>= 1 here)
 
     // source frame of slot f: the f-th walked frame of this group, the last one repeated past the end
@@ -169,7 +170,7 @@ __global__ __launch_bounds__(NW * 64, (Shape<CT, RAD>::OCC)) void k_search_mfma(
         static_assert(KSW <= 2, "strip sums are stored once per pass from the two halves of a wave");
         pick0 = channel_picker(0, lane);
         pick1 = channel_picker(1, lane);
-        sums = strip_sum + ((((size_t)b * F + (size_t)grp * FR) * tpf + tp) * (size_t)C) + wave * slice +
+        sums = strip_sum + ((((size_t)b * F + (size_t)grp * FR) * tpf + tp) * (size_t)C) + kbase * 32 +
                (KSW == 2 ? lane : (lane & 31));
     }
 
@@ -653,9 +654,15 @@ hipError_t launch_shape(const ttf_params& p, const void* x, bool external_anchor
         if (spec_mode == 1) TTF_LAUNCH_SPEC(KSW, NW, 1);   \
         else TTF_LAUNCH_SPEC(KSW, NW, 2);                  \
     } while (0)
+#define TTF_LAUNCH_SPEC_RAG(SPEC)                                                                                 \
+    k_search_mfma<CT, RAD, 2, 4, false, 0, SPEC, true><<<grid, 256, 0, s>>>(                                      \
+        xs, w.anchor_frag, anchor_index, w.anchor_inv, fuse_map, best_sim, best_idx, keep16, nullptr, p.F, p.H, p.C, \
+        p.t, 0 /* passes: the waves count their own */, groups, w.spec, w.strip_sum)
         if (blocks >= 3 * kSimds * S::OCC && ks_total % 2 == 0) TTF_LAUNCH_SPEC_AS(2, 1);
         else if (ks_total % 8 == 0) TTF_LAUNCH_SPEC_AS(2, 4);
-        else TTF_LAUNCH_SPEC_AS(1, 4);
+        else if (spec_mode == 1) TTF_LAUNCH_SPEC_RAG(1);     // (C % 256 == 128: passes dealt unevenly, none short)
+        else TTF_LAUNCH_SPEC_RAG(2);
+#undef TTF_LAUNCH_SPEC_RAG
 #undef TTF_LAUNCH_SPEC_AS
 #undef TTF_LAUNCH_SPEC
         return hipGetLastError();
